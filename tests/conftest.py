@@ -1,0 +1,36 @@
+import os
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def pytest_configure(config):
+    config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+
+
+@pytest.fixture(scope="session")
+def blob():
+    from paper_2212_01185_amd import synth
+    return synth.make_blob(0)
+
+
+@pytest.fixture(scope="session")
+def sharp_blob():
+    from paper_2212_01185_amd import synth
+    return synth.make_blob(0, sharp=True)
+
+
+@pytest.fixture(scope="session")
+def orc(blob):
+    from oracle import pcc_oracle
+    return pcc_oracle.Oracle(blob)
+
+
+@pytest.fixture(scope="session")
+def orc_sharp(sharp_blob):
+    from oracle import pcc_oracle
+    return pcc_oracle.Oracle(sharp_blob)
