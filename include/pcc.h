@@ -1,0 +1,119 @@
+/*
+ * pcc.h -- C ABI of libpcc: per-pixel causal-context lossless image coding on
+ * one MI355X (gfx950).
+ *
+ * The method is the learned pixel-by-pixel coder of arXiv 2212.01185: a small
+ * network maps every pixel's causal neighbourhood of already coded pixels to
+ * the parameters of a discretised Gaussian mixture per colour channel
+ * (Sec. III-A, Eq. (1)-(4); network Sec. III-B), an entropy coder codes the
+ * sub-pixels with those distributions, the encoder evaluates all pixels in
+ * parallel and the decoder proceeds as a wavefront (Sec. III-C, Eq. (6)).
+ *
+ * Conventions
+ *   - Images are uint8, layout [n][H][W][3] (rows, columns, RGB), contiguous,
+ *     in DEVICE memory.  "d_" arguments are device pointers, "h_" host pointers.
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the null stream).
+ *     Kernels are launched on it; nothing else is synchronised.
+ *   - Every buffer named in a call is owned by the caller; the library neither
+ *     frees nor keeps it beyond the call.  A pcc_ctx owns its packed copy of
+ *     the weights and a private device workspace that grows on demand
+ *     (hipMalloc inside the first call that needs it, reused afterwards).
+ *   - A pcc_ctx must not be used by two calls at the same time.
+ *   - All functions returning int return PCC_OK (0) or a negative PCC_E_* code;
+ *     no exceptions or aborts cross this boundary and damaged input cannot
+ *     make a call hang (device waits are bounded).
+ *
+ * Weight blob (host memory): 16 little-endian uint32 header words {magic
+ * "PCCW", version 1, n_layers, dims[8], K, neighbourhood size, wavefront delay
+ * per row, activation id, distribution id}, then per layer W[out][in] and
+ * b[out] as fp32.  This library accepts the shape 30 -> 160 -> 160 -> 128 -> 60,
+ * ReLU, K = 5 Gaussian components, the 10-pixel neighbourhood {rows r-2, r-1 at
+ * columns c-2..c+1; row r at c-2, c-1} and delay 2; weights must be exactly
+ * representable in bf16 (biases are fp32).  Head layout o[60]: for each of
+ * R,G,B: 5 mixture logits, 5 means, 5 log-sigmas (units of 1/256 of the grey
+ * range); then 5 alphas, 5 betas, 5 gammas of Eq. (3)-(4).
+ *
+ * Stream (device memory): 8 little-endian uint32 words {magic "PCC1", version
+ * 1, n, H, W, K | nbhd<<8 | delay<<16 | 16<<24, 0, 0}, uint64 offsets[n*H+1]
+ * (relative to the end of that table), then one rANS payload per image row:
+ * 8-byte initial decoder state, then 32-bit words in the order the decoder
+ * reads them.  Streams written by this library are read by this library; the
+ * bytes depend on its floating-point evaluation order and are not portable to
+ * another implementation of the same model.
+ */
+#ifndef PCC_H
+#define PCC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PCC_OK 0
+#define PCC_E_ARG (-1)      /* null pointer, non-positive or too large dimension */
+#define PCC_E_BLOB (-2)     /* weight blob: bad magic, unsupported shape, size mismatch, non-bf16 weight */
+#define PCC_E_CAP (-3)      /* output capacity too small */
+#define PCC_E_STREAM (-4)   /* stream: bad header, dimensions differ, offsets out of range, payload over/under-read */
+#define PCC_E_HIP (-5)      /* a HIP runtime call failed */
+#define PCC_E_INTERNAL (-6) /* zero frequency or bounded device wait expired */
+#define PCC_E_UNIMPL (-7)
+
+#define PCC_HEAD_OUTPUTS 60
+
+typedef struct pcc_ctx pcc_ctx;
+
+/* Parse and pack the weight blob (host pointer) for device `hip_device`.
+ * On success *out owns device memory until pcc_destroy. */
+int pcc_create(pcc_ctx **out, const void *h_blob, size_t blob_bytes, int hip_device);
+void pcc_destroy(pcc_ctx *ctx);
+
+/* Upper bound in bytes of the stream pcc_encode writes for n images of H x W. */
+size_t pcc_stream_bound(int n, int H, int W);
+
+/* Number of wavefront passes for an H x W image: Eq. (6) with a right reach of
+ * one column, T = W + 2 (H - 1). */
+long pcc_wavefront_steps(int H, int W);
+
+/* Network evaluation for every pixel (Sec. III-C first paragraph: at the
+ * encoder all pixels are known and are processed in parallel).
+ *   d_params [n][H][W][60] fp32: raw head outputs in the head layout above.
+ *   d_bits   [n][H][W] fp32 or NULL: -log2 of the quantised joint probability
+ *            of the pixel's true (r,g,b), i.e. its term of the loss Eq. (5).
+ * Asynchronous: returns after the launch. */
+int pcc_encode_probs(pcc_ctx *ctx, const uint8_t *d_img, int n, int H, int W,
+                     float *d_params, float *d_bits, void *hip_stream);
+
+/* Encoder (Sec. IV-C first paragraph): parameters for all pixels in parallel,
+ * integer CDF values of the true sub-pixels, row-wise rANS, stream assembly.
+ * Writes at most cap_bytes to d_stream and the byte count to *h_nbytes_out.
+ * Synchronises hip_stream before returning (the size is read back). */
+int pcc_encode(pcc_ctx *ctx, const uint8_t *d_img, int n, int H, int W,
+               uint8_t *d_stream, size_t cap_bytes, size_t *h_nbytes_out, void *hip_stream);
+
+/* Wavefront decoder (Sec. III-C): pass t decodes every pixel (r, c) with
+ * 2r + c = t.  d_img_out [n][H][W][3] is fully overwritten.  Synchronises
+ * hip_stream before returning (the device status word is read back).  On
+ * PCC_E_STREAM the image content is unspecified. */
+int pcc_decode(pcc_ctx *ctx, const uint8_t *d_stream, size_t nbytes, int n, int H, int W,
+               uint8_t *d_img_out, void *hip_stream);
+
+/* Test hooks (not on the hot path). */
+
+/* Eq. (1)-(4) + integer CDF rule alone: from given head outputs d_params
+ * [count][60] and the conditioning sub-pixels d_rg [count][2] (r, g) write the
+ * full tables d_cq [count][3][257] (uint32).  Asynchronous. */
+int pcc_cdf_tables(pcc_ctx *ctx, const float *d_params, const uint8_t *d_rg, size_t count,
+                   uint32_t *d_cq, void *hip_stream);
+
+/* Copy the (start, freq) pairs the last pcc_encode on this ctx fed to the
+ * coder: d_out [n][H][W][3] uint32, start | (freq - 1) << 16.  Asynchronous. */
+int pcc_copy_intervals(pcc_ctx *ctx, uint32_t *d_out, size_t count, void *hip_stream);
+
+const char *pcc_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PCC_H */

@@ -1,0 +1,826 @@
+// libpcc: kernels and C ABI (see include/pcc.h for the contract).
+//
+// Kernels
+//   encode_kernel      gather + network (MFMA) + mixture -> (start,freq) of the
+//                      true sub-pixels, all pixels in parallel
+//   rans_rows_kernel   one lane per image row: push the row's symbols last to
+//                      first into a per-row slab, written backwards
+//   scan_kernel        exclusive prefix sum of row payload sizes, header, offsets
+//   compact_kernel     slabs -> contiguous stream
+//   decode_kernel      persistent wavefront decoder: one wave per band of 16
+//                      rows, step t handles pixel (r, t - 2r) of each row
+//   cdf_tables_kernel  test hook: full integer CDF tables from given parameters
+#include <hip/hip_runtime.h>
+
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "pcc.h"
+#include "pcc_device.h"
+
+namespace pcc {
+
+constexpr uint32_t kBlobMagic = 0x57434350u;    // "PCCW"
+constexpr uint32_t kStreamMagic = 0x31434350u;  // "PCC1"
+constexpr int kStreamHeader = 32;
+constexpr uint32_t kModelTag = 5u | (10u << 8) | (2u << 16) | (16u << 24);
+constexpr int kBandRows = 16;
+constexpr uint32_t kMailTag = 0x80000000u;
+// Encode kernel variants: tiles of 16 pixels per wave per iteration x threads per workgroup.
+// More tiles per wave reuse each LDS weight read more often but need more registers
+// (4 tiles only fit with one wave per SIMD).
+struct EncodeVariant { int tiles, threads; };
+constexpr EncodeVariant kEncodeVariants[3] = {{2, 512}, {3, 512}, {4, 256}};
+constexpr int kDefaultEncodeVariant = 0;
+
+// status words in device memory
+enum { kStErr = 0, kStAbort = 1, kStTicket = 2, kStWords = 4 };
+
+__host__ __device__ inline size_t slab_words(int W) { return (6 * (size_t)W + 16) / 4 + 1; }
+
+// ---------------------------------------------------------------------------
+// shared device helpers
+// ---------------------------------------------------------------------------
+
+__device__ __forceinline__ void set_error(int* status, int code) { atomicCAS(&status[kStErr], 0, code); }
+
+// An offset of zero the optimiser cannot see through.  Added to the LDS base
+// inside a loop it keeps the (loop-invariant) weight reads from being hoisted
+// out of the loop and parked in registers or scratch.
+__device__ __forceinline__ uint32_t opaque_zero() {
+    uint32_t z = 0;
+    asm volatile("" : "+s"(z));
+    return z;
+}
+
+__device__ __forceinline__ void copy_model_to_lds(uint8_t* lds, const uint8_t* __restrict__ model) {
+    const uint4* src = reinterpret_cast<const uint4*>(model);
+    uint4* dst = reinterpret_cast<uint4*>(lds);
+    for (int i = threadIdx.x; i < kModelBytes / 16; i += blockDim.x) dst[i] = src[i];
+}
+
+// Source of slot i of lane group g in the first-layer operand: row offset and
+// byte within the row's neighbour run (which starts at column c-2).
+__device__ __forceinline__ void slot_source(int g, int i, int& dr, int& b, bool& used) {
+    if (i < 4) {
+        dr = (g < 2) ? -2 : -1;
+        b = (g & 1) ? 8 + i : i;
+        used = true;
+    } else {
+        dr = (g & 1) ? 0 : ((g == 0) ? -2 : -1);
+        b = (g == 1) ? i - 4 : i;
+        used = !(g == 3 && i >= 6);
+    }
+}
+
+// Raw head registers of one lane after the network -> mixture of "its" channel
+// (lane groups 0,1,2 = R,G,B) with the coupling coefficients pulled from group 3.
+struct LaneHead {
+    ChanParams cp;
+    float c1[5];  // alpha (group 1) or beta (group 2)
+    float c2[5];  // gamma (group 2)
+};
+
+__device__ __forceinline__ void lane_head_setup(const f32x4_t (&o)[kL4_OB], int lane, LaneHead& h) {
+    float v[16];
+#pragma unroll
+    for (int ob = 0; ob < kL4_OB; ++ob) {
+        v[4 * ob + 0] = o[ob].x; v[4 * ob + 1] = o[ob].y; v[4 * ob + 2] = o[ob].z; v[4 * ob + 3] = o[ob].w;
+    }
+    const int g = lane >> 4;
+    const int src = (lane & 15) + 48;
+    float x3[13];
+#pragma unroll
+    for (int s = 0; s < 13; ++s) x3[s] = __shfl(v[s], src);
+    float raw[15];
+#pragma unroll
+    for (int s = 0; s < 15; ++s) raw[s] = v[s];
+    channel_setup(raw, h.cp);
+    h.c1[0] = v[15];
+#pragma unroll
+    for (int k = 1; k < 5; ++k) h.c1[k] = (g == 1) ? x3[k - 1] : x3[3 + k];
+#pragma unroll
+    for (int k = 0; k < 5; ++k) h.c2[k] = x3[8 + k];
+}
+
+// ---------------------------------------------------------------------------
+// encode: all pixels in parallel
+// ---------------------------------------------------------------------------
+template <int T, int THREADS>
+__global__ void __launch_bounds__(THREADS)
+encode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ img, int H, int W, uint32_t P,
+              uint32_t* __restrict__ sf, float* __restrict__ params, float* __restrict__ bits, int* status) {
+    extern __shared__ __align__(16) uint8_t lds[];
+    copy_model_to_lds(lds, model);
+    __syncthreads();
+    const float2* lut = reinterpret_cast<const float2*>(lds + kLutOff);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
+    const int g = lane >> 4, nl = lane & 15;
+    const uint32_t groups = (P + 16 * T - 1) / (16 * T);
+
+    for (uint32_t grp = blockIdx.x * nwaves + wave; grp < groups; grp += gridDim.x * nwaves) {
+        u32x4_t in[T][1];
+        uint32_t pix[T];   // the pixel's own bytes r | g<<8 | b<<16
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            const uint32_t p = grp * (16 * T) + 16 * t + nl;
+            uint32_t slots[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) slots[i] = 0;
+            pix[t] = 0;
+            if (p < P) {
+                const uint32_t rowg = p / (uint32_t)W;
+                const int c = (int)(p - rowg * (uint32_t)W);
+                const uint32_t im = rowg / (uint32_t)H;
+                const int r = (int)(rowg - im * (uint32_t)H);
+                const uint8_t* base = img + (size_t)im * H * W * 3;
+                const uint8_t* me = base + ((size_t)r * W + c) * 3;
+                pix[t] = (uint32_t)me[0] | ((uint32_t)me[1] << 8) | ((uint32_t)me[2] << 16);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    int dr, b;
+                    bool used;
+                    slot_source(g, i, dr, b, used);
+                    const int rr = r + dr;
+                    const int cc = c - 2 + ((b * 11) >> 5);
+                    if (used && rr >= 0 && cc >= 0 && cc < W)
+                        slots[i] = byte_to_bf16(base[((size_t)rr * W + (c - 2)) * 3 + b]);
+                }
+            }
+            in[t][0].x = slots[0] | (slots[1] << 16);
+            in[t][0].y = slots[2] | (slots[3] << 16);
+            in[t][0].z = slots[4] | (slots[5] << 16);
+            in[t][0].w = slots[6] | (slots[7] << 16);
+        }
+
+        f32x4_t out[T][kL4_OB];
+        mlp_forward<T, 2, 2>(lds + opaque_zero(), lane, in, out);
+
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            const uint32_t p = grp * (16 * T) + 16 * t + nl;
+            const bool live = p < P;
+            if (params != nullptr && live) {
+#pragma unroll
+                for (int ob = 0; ob < kL4_OB; ++ob) {
+                    const float vv[4] = {out[t][ob].x, out[t][ob].y, out[t][ob].z, out[t][ob].w};
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const int idx = head_index(g, 4 * ob + i);
+                        if (idx >= 0) params[(size_t)p * PCC_HEAD_OUTPUTS + idx] = vv[i];
+                    }
+                }
+            }
+            LaneHead h;
+            lane_head_setup(out[t], lane, h);
+            const float rhat = (float)(pix[t] & 0xFF) * (1.0f / 256.0f);
+            const float ghat = (float)((pix[t] >> 8) & 0xFF) * (1.0f / 256.0f);
+            if (g == 1) couple_green(h.cp, h.c1, rhat);
+            if (g == 2) couple_blue(h.cp, h.c1, h.c2, rhat, ghat);
+            const int x = (int)((pix[t] >> (8 * (g & 3))) & 0xFF);   // group 3 reads the zero top byte
+            const uint32_t lo = cq_full(h.cp, x, lut);
+            const uint32_t hi = cq_full(h.cp, x + 1, lut);
+            uint32_t freq = hi - lo;
+            if (g < 3 && live && (hi <= lo || freq > 65536u)) { set_error(status, PCC_E_INTERNAL); freq = 1; }
+            if (sf != nullptr && g < 3 && live) sf[(size_t)p * 3 + g] = lo | ((freq - 1u) << 16);
+            if (bits != nullptr) {
+                const float mine = 16.0f - __builtin_amdgcn_logf((float)freq);
+                const float tot = (__shfl(mine, nl) + __shfl(mine, nl + 16)) + __shfl(mine, nl + 32);
+                if (g == 0 && live) bits[p] = tot;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// rANS encode, one lane per row
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(64)
+rans_rows_kernel(const uint32_t* __restrict__ sf, int W, uint32_t rows, uint32_t* __restrict__ slabs,
+                 uint32_t* __restrict__ row_words) {
+    const uint32_t row = blockIdx.x * blockDim.x + threadIdx.x;
+    if (row >= rows) return;
+    const size_t sw = slab_words(W);
+    const uint32_t* s = sf + (size_t)row * W * 3;
+    uint32_t* slab = slabs + (size_t)row * sw;
+    size_t wp = sw;
+    uint64_t x = kRansL;
+    for (int i = 3 * W - 1; i >= 0; --i) {
+        const uint32_t v = s[i];
+        const uint64_t start = v & 0xFFFFu, f = (uint64_t)(v >> 16) + 1u;
+        if (x >= (f << 47)) { slab[--wp] = (uint32_t)x; x >>= 32; }
+        // exact x / f for x < 2^47 * f <= 2^64: fp64 estimate (error < 1) and one correction
+        const double rf = 1.0 / (double)f;
+        uint64_t q = (uint64_t)((double)x * rf);
+        int64_t rem = (int64_t)(x - q * f);
+        if (rem < 0) { q -= 1; rem += (int64_t)f; }
+        else if (rem >= (int64_t)f) { q += 1; rem -= (int64_t)f; }
+        x = (q << 16) + (uint64_t)rem + start;
+    }
+    slab[--wp] = (uint32_t)(x >> 32);
+    slab[--wp] = (uint32_t)x;
+    row_words[row] = (uint32_t)(sw - wp);
+}
+
+// Single workgroup: offsets[k] = 4 * sum_{j<k} row_words[j]; header; total size.
+__global__ void __launch_bounds__(1024)
+scan_kernel(const uint32_t* __restrict__ row_words, uint32_t rows, int n, int H, int W, uint8_t* __restrict__ stream,
+            uint64_t* __restrict__ total_bytes) {
+    __shared__ uint64_t part[1024];
+    __shared__ uint64_t carry;
+    uint64_t* offsets = reinterpret_cast<uint64_t*>(stream + kStreamHeader);
+    if (threadIdx.x == 0) {
+        carry = 0;
+        uint32_t* hdr = reinterpret_cast<uint32_t*>(stream);
+        hdr[0] = kStreamMagic; hdr[1] = 1; hdr[2] = (uint32_t)n; hdr[3] = (uint32_t)H; hdr[4] = (uint32_t)W;
+        hdr[5] = kModelTag; hdr[6] = 0; hdr[7] = 0;
+    }
+    __syncthreads();
+    for (uint32_t base = 0; base < rows; base += 1024) {
+        const uint32_t k = base + threadIdx.x;
+        const uint64_t mine = k < rows ? 4ull * row_words[k] : 0ull;
+        part[threadIdx.x] = mine;
+        __syncthreads();
+        for (int d = 1; d < 1024; d <<= 1) {
+            const uint64_t add = threadIdx.x >= (uint32_t)d ? part[threadIdx.x - d] : 0ull;
+            __syncthreads();
+            part[threadIdx.x] += add;
+            __syncthreads();
+        }
+        if (k < rows) offsets[k] = carry + part[threadIdx.x] - mine;
+        __syncthreads();
+        if (threadIdx.x == 1023) carry += part[1023];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        offsets[rows] = carry;
+        *total_bytes = (uint64_t)kStreamHeader + 8ull * (rows + 1) + carry;
+    }
+}
+
+__global__ void __launch_bounds__(64)
+compact_kernel(const uint32_t* __restrict__ slabs, const uint32_t* __restrict__ row_words, int W, uint32_t rows,
+               uint8_t* __restrict__ stream, uint64_t cap_bytes, int* status) {
+    const uint32_t row = blockIdx.x;
+    const size_t sw = slab_words(W);
+    const uint64_t table = (uint64_t)kStreamHeader + 8ull * (rows + 1);
+    const uint64_t off = reinterpret_cast<const uint64_t*>(stream + kStreamHeader)[row];
+    const uint32_t nw = row_words[row];
+    if (table + off + 4ull * nw > cap_bytes) {
+        if (threadIdx.x == 0) set_error(status, PCC_E_CAP);
+        return;
+    }
+    const uint32_t* src = slabs + (size_t)row * sw + (sw - nw);
+    uint32_t* dst = reinterpret_cast<uint32_t*>(stream + table + off);
+    for (uint32_t i = threadIdx.x; i < nw; i += blockDim.x) dst[i] = src[i];
+}
+
+// ---------------------------------------------------------------------------
+// wavefront decode
+// ---------------------------------------------------------------------------
+struct RowReader {          // lives in the lanes of group 0
+    uint64_t x;
+    const uint32_t* words;  // payload after the 8-byte state
+    uint32_t nwords, pos;
+    uint32_t w0, w1;        // words[pos], words[pos+1], fetched ahead of use
+    bool bad;
+};
+
+__device__ __forceinline__ void reader_advance(RowReader& rd, uint32_t slot, uint32_t start, uint32_t freq) {
+    rd.x = (uint64_t)freq * (rd.x >> 16) + slot - start;
+    if (rd.x < kRansL) {
+        if (rd.pos >= rd.nwords) rd.bad = true;
+        rd.x = (rd.x << 32) | rd.w0;
+        rd.pos += 1;
+        rd.w0 = rd.w1;
+        rd.w1 = (rd.pos + 1 < rd.nwords) ? rd.words[rd.pos + 1] : 0u;
+    }
+}
+
+__global__ void __launch_bounds__(64)
+decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ stream, uint64_t nbytes, int n, int H,
+              int W, int nbands, uint8_t* __restrict__ img_out, uint32_t* mailbox, int* status, uint32_t spin_limit) {
+    extern __shared__ __align__(16) uint8_t lds[];
+    uint32_t (*ring)[8] = reinterpret_cast<uint32_t (*)[8]>(lds + kModelBytes);   // [18][8]
+    int* lds_ticket = reinterpret_cast<int*>(lds + kModelBytes + 18 * 8 * 4);
+    const int lane = threadIdx.x;
+    const int g = lane >> 4, nl = lane & 15;
+
+    // Bands take tickets in start order: a band only ever waits for the band
+    // above it, which holds a smaller ticket and is therefore already running.
+    if (lane == 0) *lds_ticket = atomicAdd(&status[kStTicket], 1);
+    copy_model_to_lds(lds, model);
+    for (int i = lane; i < 18 * 8; i += 64) (&ring[0][0])[i] = 0u;
+    __syncthreads();
+    const int ticket = *lds_ticket;
+    const int im = ticket / nbands, band = ticket - im * nbands;
+    if (im >= n) return;
+    const float2* lut = reinterpret_cast<const float2*>(lds + kLutOff);
+
+    const int r0 = band * kBandRows;
+    const int row = r0 + nl;
+    const bool row_ok = row < H;
+    const uint64_t rows_total = (uint64_t)n * H;
+    const uint64_t table = (uint64_t)kStreamHeader + 8ull * (rows_total + 1);
+    const uint64_t payload_bytes = nbytes - table;   // host guarantees nbytes >= table
+
+    if (ticket == 0 && lane == 0) {
+        const uint32_t* hdr = reinterpret_cast<const uint32_t*>(stream);
+        const uint64_t last = reinterpret_cast<const uint64_t*>(stream + kStreamHeader)[rows_total];
+        if (hdr[0] != kStreamMagic || hdr[1] != 1u || hdr[2] != (uint32_t)n || hdr[3] != (uint32_t)H ||
+            hdr[4] != (uint32_t)W || hdr[5] != kModelTag || last != payload_bytes)
+            set_error(status, PCC_E_STREAM);
+    }
+
+    RowReader rd;
+    rd.x = kRansL; rd.words = nullptr; rd.nwords = 0; rd.pos = 0; rd.w0 = 0; rd.w1 = 0; rd.bad = false;
+    if (g == 0 && row_ok) {
+        const uint64_t* offs = reinterpret_cast<const uint64_t*>(stream + kStreamHeader);
+        const uint64_t rowg = (uint64_t)im * H + row;
+        const uint64_t a = offs[rowg], b = offs[rowg + 1];
+        if (a > b || b > payload_bytes || (b - a) < 8 || ((b - a) & 3) != 0 || (a & 3) != 0 ||
+            (b - a) > 4ull * slab_words(W)) {
+            rd.bad = true;
+        } else {
+            const uint32_t* p = reinterpret_cast<const uint32_t*>(stream + table + a);
+            rd.x = (uint64_t)p[0] | ((uint64_t)p[1] << 32);
+            rd.words = p + 2;
+            rd.nwords = (uint32_t)((b - a) / 4) - 2;
+            rd.w0 = rd.nwords > 0 ? rd.words[0] : 0u;
+            rd.w1 = rd.nwords > 1 ? rd.words[1] : 0u;
+            if (rd.x < kRansL || (rd.x >> 63)) { rd.bad = true; rd.x = kRansL; }
+        }
+    }
+
+    uint8_t* out_img = img_out + (size_t)im * H * W * 3;
+    const uint32_t* mail_in = mailbox + ((size_t)im * nbands + (band > 0 ? band - 1 : 0)) * 2 * (size_t)W;
+    uint32_t* mail_out = mailbox + ((size_t)im * nbands + band) * 2 * (size_t)W;
+
+    const int last_row = min(r0 + kBandRows - 1, H - 1);
+    const int t_begin = 2 * r0, t_end = 2 * last_row + W - 1;
+    bool aborted = false;
+
+    for (int t = t_begin - 1; t <= t_end && !aborted; ++t) {
+        // Pixels of the two rows above the band, column cc = (t - 2 r0) + 1,
+        // published by the band above (t_begin - 1 is a prologue that brings in column 0).
+        const int cc = t - t_begin + 1;
+        if (band > 0 && lane < 2 && cc < W) {
+            const uint32_t* src = mail_in + (size_t)lane * W + cc;
+            uint32_t v = 0, spins = 0;
+            bool fail = false;
+            for (;;) {
+                v = __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (v & kMailTag) break;
+                ++spins;
+                if (spins > spin_limit) { set_error(status, PCC_E_INTERNAL); fail = true; break; }
+                if ((spins & 63u) == 0u &&
+                    __hip_atomic_load(&status[kStAbort], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+                    fail = true;
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(1);
+            }
+            if (fail) {
+                __hip_atomic_store(&status[kStAbort], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                aborted = true;
+            }
+            ring[lane][cc & 7] = v & 0xFFFFFFu;
+        }
+        aborted = __ballot(aborted) != 0ull;
+        __syncthreads();
+        if (aborted || t < t_begin) continue;
+
+        const int c = t - 2 * row;
+        const bool active = row_ok && c >= 0 && c < W;
+
+        // gather C_ij from the ring (zero outside the image)
+        u32x4_t in[1][1];
+        {
+            uint32_t slots[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                int dr, b;
+                bool used;
+                slot_source(g, i, dr, b, used);
+                const int pc = (b * 11) >> 5;               // neighbour column index 0..3
+                const int colx = c - 2 + pc;
+                const int ch = b - 3 * pc;
+                const bool ok = used && (row + dr) >= 0 && colx >= 0 && colx < W;
+                const uint32_t px = ring[nl + 2 + dr][colx & 7];
+                slots[i] = ok ? byte_to_bf16((px >> (8 * ch)) & 0xFFu) : 0u;
+            }
+            in[0][0].x = slots[0] | (slots[1] << 16);
+            in[0][0].y = slots[2] | (slots[3] << 16);
+            in[0][0].z = slots[4] | (slots[5] << 16);
+            in[0][0].w = slots[6] | (slots[7] << 16);
+        }
+
+        f32x4_t out[1][kL4_OB];
+        mlp_forward<1, 10, 8>(lds + opaque_zero(), lane, in, out);
+
+        LaneHead h;
+        lane_head_setup(out[0], lane, h);
+
+        uint32_t start = 0, freq = 1;
+        int sym = 0;
+        // R
+        uint32_t slot = __shfl((uint32_t)rd.x & 0xFFFFu, nl);
+        if (g == 0) sym = cq_search(h.cp, slot, lut, start, freq);
+        if (g == 0 && active) reader_advance(rd, slot, start, freq);
+        const int sr = __shfl(sym, nl);
+        const float rhat = (float)sr * (1.0f / 256.0f);
+        // G given R
+        if (g == 1) couple_green(h.cp, h.c1, rhat);
+        slot = __shfl((uint32_t)rd.x & 0xFFFFu, nl);
+        if (g == 1) sym = cq_search(h.cp, slot, lut, start, freq);
+        const int sg = __shfl(sym, nl + 16);
+        {
+            const uint32_t st = __shfl(start, nl + 16), fq = __shfl(freq, nl + 16);
+            if (g == 0 && active) reader_advance(rd, slot, st, fq);
+        }
+        const float ghat = (float)sg * (1.0f / 256.0f);
+        // B given R, G
+        if (g == 2) couple_blue(h.cp, h.c1, h.c2, rhat, ghat);
+        slot = __shfl((uint32_t)rd.x & 0xFFFFu, nl);
+        if (g == 2) sym = cq_search(h.cp, slot, lut, start, freq);
+        const int sb = __shfl(sym, nl + 32);
+        {
+            const uint32_t st = __shfl(start, nl + 32), fq = __shfl(freq, nl + 32);
+            if (g == 0 && active) reader_advance(rd, slot, st, fq);
+        }
+
+        if (g == 0 && active) {
+            const uint32_t px = (uint32_t)sr | ((uint32_t)sg << 8) | ((uint32_t)sb << 16);
+            ring[nl + 2][c & 7] = px;
+            uint8_t* o = out_img + ((size_t)row * W + c) * 3;
+            o[0] = (uint8_t)sr; o[1] = (uint8_t)sg; o[2] = (uint8_t)sb;
+            if (nl >= kBandRows - 2)
+                __hip_atomic_store(mail_out + (size_t)(nl - (kBandRows - 2)) * W + c, px | kMailTag, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+            if (c == W - 1 && (rd.bad || rd.x != kRansL || rd.pos != rd.nwords)) set_error(status, PCC_E_STREAM);
+        }
+        __syncthreads();
+    }
+}
+
+// ---------------------------------------------------------------------------
+// test hook: full tables from given head outputs
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+cdf_tables_kernel(const uint8_t* __restrict__ model, const float* __restrict__ params, const uint8_t* __restrict__ rg,
+                  size_t count, uint32_t* __restrict__ cq) {
+    extern __shared__ __align__(16) uint8_t lds[];
+    float2* lut = reinterpret_cast<float2*>(lds);
+    const float2* src = reinterpret_cast<const float2*>(model + kLutOff);
+    for (int i = threadIdx.x; i < kLutEntries + 1; i += blockDim.x) lut[i] = src[i];
+    __syncthreads();
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= count * 3) return;
+    const size_t p = idx / 3;
+    const int ch = (int)(idx - p * 3);
+    const float* o = params + p * PCC_HEAD_OUTPUTS;
+    float raw[15];
+    for (int s = 0; s < 15; ++s) raw[s] = o[15 * ch + s];
+    ChanParams cp;
+    channel_setup(raw, cp);
+    const float rhat = (float)rg[2 * p] * (1.0f / 256.0f), ghat = (float)rg[2 * p + 1] * (1.0f / 256.0f);
+    float c1[5], c2[5];
+    for (int k = 0; k < 5; ++k) { c1[k] = ch == 1 ? o[45 + k] : o[50 + k]; c2[k] = o[55 + k]; }
+    if (ch == 1) couple_green(cp, c1, rhat);
+    if (ch == 2) couple_blue(cp, c1, c2, rhat, ghat);
+    uint32_t* dst = cq + idx * 257;
+    for (int e = 0; e <= 256; ++e) dst[e] = cq_full(cp, e, lut);
+}
+
+}  // namespace pcc
+
+// ===========================================================================
+// host side
+// ===========================================================================
+using namespace pcc;
+
+struct pcc_ctx {
+    int device = 0;
+    uint8_t* d_model = nullptr;
+    // workspace (grown on demand)
+    uint8_t* d_ws = nullptr;
+    size_t ws_bytes = 0;
+    int* d_status = nullptr;       // kStWords ints
+    uint64_t* d_total = nullptr;
+    int* h_status = nullptr;       // pinned, kStWords ints + 2 for the total
+    // layout of the last encode inside the workspace
+    uint32_t* d_sf = nullptr;
+    size_t sf_count = 0;
+    int num_cus = 0;
+    int encode_variant = kDefaultEncodeVariant;
+};
+
+namespace {
+
+inline uint32_t rd32(const uint8_t* p) {
+    return (uint32_t)p[0] | ((uint32_t)p[1] << 8) | ((uint32_t)p[2] << 16) | ((uint32_t)p[3] << 24);
+}
+inline float rdf(const uint8_t* p) { uint32_t u = rd32(p); float f; memcpy(&f, &u, 4); return f; }
+
+// fp32 -> bf16 bits, exact values only (caller has checked representability)
+inline bool bf16_exact(float f, uint16_t* out) {
+    uint32_t u; memcpy(&u, &f, 4);
+    *out = (uint16_t)(u >> 16);
+    return (u & 0xFFFFu) == 0u;
+}
+
+struct DeviceGuard {
+    int prev = -1;
+    bool ok = false;
+    explicit DeviceGuard(int dev) {
+        if (hipGetDevice(&prev) != hipSuccess) return;
+        ok = hipSetDevice(dev) == hipSuccess;
+    }
+    ~DeviceGuard() { if (prev >= 0) (void)hipSetDevice(prev); }
+};
+
+int ensure_workspace(pcc_ctx* ctx, size_t bytes) {
+    if (bytes <= ctx->ws_bytes) return PCC_OK;
+    if (ctx->d_ws) { (void)hipFree(ctx->d_ws); ctx->d_ws = nullptr; ctx->ws_bytes = 0; }
+    ctx->d_sf = nullptr; ctx->sf_count = 0;
+    const size_t want = bytes + bytes / 8 + 4096;
+    if (hipMalloc((void**)&ctx->d_ws, want) != hipSuccess) { (void)hipGetLastError(); return PCC_E_HIP; }
+    ctx->ws_bytes = want;
+    return PCC_OK;
+}
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+bool dims_ok(int n, int H, int W) {
+    if (n < 1 || H < 1 || W < 1) return false;
+    const uint64_t P = (uint64_t)n * H * W;
+    return P < (1ull << 31) && (uint64_t)W < (1u << 24) && (uint64_t)n * H < (1ull << 31);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* pcc_strerror(int code) {
+    switch (code) {
+        case PCC_OK: return "ok";
+        case PCC_E_ARG: return "invalid argument";
+        case PCC_E_BLOB: return "unsupported or malformed weight blob";
+        case PCC_E_CAP: return "output capacity too small";
+        case PCC_E_STREAM: return "malformed stream";
+        case PCC_E_HIP: return "HIP runtime error";
+        case PCC_E_INTERNAL: return "internal error (zero frequency or device wait expired)";
+        case PCC_E_UNIMPL: return "not implemented";
+        default: return "unknown error";
+    }
+}
+
+size_t pcc_stream_bound(int n, int H, int W) {
+    if (n < 1 || H < 1 || W < 1) return 0;
+    const size_t rows = (size_t)n * H;
+    return (size_t)kStreamHeader + 8 * (rows + 1) + rows * 4 * slab_words(W);
+}
+
+long pcc_wavefront_steps(int H, int W) { return (long)W + 2L * (H - 1); }
+
+int pcc_create(pcc_ctx** out, const void* h_blob, size_t blob_bytes, int hip_device) {
+    if (!out || !h_blob) return PCC_E_ARG;
+    *out = nullptr;
+    const uint8_t* p = (const uint8_t*)h_blob;
+    static const int dims[5] = {30, 160, 160, 128, 60};
+    if (blob_bytes < 64 || rd32(p) != kBlobMagic || rd32(p + 4) != 1u || rd32(p + 8) != 4u) return PCC_E_BLOB;
+    for (int i = 0; i < 5; ++i) if (rd32(p + 12 + 4 * i) != (uint32_t)dims[i]) return PCC_E_BLOB;
+    if (rd32(p + 44) != 5u || rd32(p + 48) != 10u || rd32(p + 52) != 2u || rd32(p + 56) != 0u || rd32(p + 60) != 0u)
+        return PCC_E_BLOB;
+    size_t need = 64;
+    for (int l = 0; l < 4; ++l) need += 4 * ((size_t)dims[l] * dims[l + 1] + dims[l + 1]);
+    if (blob_bytes != need) return PCC_E_BLOB;
+
+    const uint8_t* wsrc[4];
+    const uint8_t* bsrc[4];
+    const uint8_t* q = p + 64;
+    for (int l = 0; l < 4; ++l) {
+        wsrc[l] = q; q += 4 * (size_t)dims[l] * dims[l + 1];
+        bsrc[l] = q; q += 4 * (size_t)dims[l + 1];
+    }
+    auto Wat = [&](int l, int o, int i) { return rdf(wsrc[l] + 4 * ((size_t)o * dims[l] + i)); };
+    auto Bat = [&](int l, int o) { return rdf(bsrc[l] + 4 * (size_t)o); };
+
+    std::vector<uint8_t> image(kModelBytes, 0);
+    uint16_t* w16 = reinterpret_cast<uint16_t*>(image.data());
+    static const int nob[4] = {kL1_OB, kL2_OB, kL3_OB, kL4_OB}, nkb[4] = {kL1_KB, kL2_KB, kL3_KB, kL4_KB};
+    static const int woff[4] = {kW1Off, kW2Off, kW3Off, kW4Off}, boff[4] = {kB1Off, kB2Off, kB3Off, kB4Off};
+    for (int l = 0; l < 4; ++l) {
+        for (int ob = 0; ob < nob[l]; ++ob)
+            for (int kb = 0; kb < nkb[l]; ++kb)
+                for (int lane = 0; lane < 64; ++lane)
+                    for (int i = 0; i < 8; ++i) {
+                        const int m = lane & 15, g = lane >> 4;
+                        // output feature of A row m of this out-block
+                        const int o = l < 3 ? 16 * ob + m : head_index(m >> 2, 4 * ob + (m & 3));
+                        // input feature of k-slot (g, i) of this k-block
+                        const int in = l == 0 ? in1_index(g, i) : 32 * kb + kslot_feature(g, i);
+                        float v = 0.0f;
+                        if (o >= 0 && o < dims[l + 1] && in >= 0 && in < dims[l]) v = Wat(l, o, in);
+                        uint16_t h;
+                        if (!bf16_exact(v, &h)) return PCC_E_BLOB;
+                        if (l == 0 && v != 0.0f) {
+                            // fold the 1/256 input scaling into the first layer: exact unless it underflows
+                            const float s = v * (1.0f / 256.0f);
+                            if (!bf16_exact(s, &h) || s * 256.0f != v) return PCC_E_BLOB;
+                        }
+                        w16[(woff[l] + (((ob * nkb[l] + kb) * 64 + lane) * 16)) / 2 + i] = h;
+                    }
+        float* b = reinterpret_cast<float*>(image.data() + boff[l]);
+        const int padded = 16 * nob[l];
+        for (int s = 0; s < padded; ++s) {
+            const int ob = s >> 4, m = s & 15;
+            const int o = l < 3 ? s : head_index(m >> 2, 4 * ob + (m & 3));
+            b[s] = (o >= 0 && o < dims[l + 1]) ? Bat(l, o) : 0.0f;
+        }
+    }
+    // Normal CDF table in units of 2^-24 so that forward differences are exact in fp32.
+    float* lut = reinterpret_cast<float*>(image.data() + kLutOff);
+    std::vector<double> tq(kLutEntries + 1);
+    for (int i = 0; i < kLutEntries; ++i) {
+        const double z = (i - 768) / 128.0;
+        tq[i] = nearbyint(0.5 * erfc(-z / sqrt(2.0)) * 16777216.0);
+    }
+    tq[kLutEntries] = tq[kLutEntries - 1];
+    for (int i = 0; i < kLutEntries; ++i) {
+        lut[2 * i] = (float)(tq[i] / 16777216.0);
+        lut[2 * i + 1] = (float)((tq[i + 1] - tq[i]) / 16777216.0);
+    }
+    lut[2 * kLutEntries] = 1.0f;
+    lut[2 * kLutEntries + 1] = 0.0f;
+
+    DeviceGuard guard(hip_device);
+    if (!guard.ok) { (void)hipGetLastError(); return PCC_E_HIP; }
+    pcc_ctx* ctx = new (std::nothrow) pcc_ctx();
+    if (!ctx) return PCC_E_INTERNAL;
+    ctx->device = hip_device;
+    hipDeviceProp_t prop;
+    bool ok = hipGetDeviceProperties(&prop, hip_device) == hipSuccess;
+    if (ok) ctx->num_cus = prop.multiProcessorCount;
+    ok = ok && hipMalloc((void**)&ctx->d_model, kModelBytes) == hipSuccess;
+    ok = ok && hipMalloc((void**)&ctx->d_status, kStWords * sizeof(int) + sizeof(uint64_t)) == hipSuccess;
+    ok = ok && hipHostMalloc((void**)&ctx->h_status, kStWords * sizeof(int) + sizeof(uint64_t), hipHostMallocDefault) == hipSuccess;
+    ok = ok && hipMemcpy(ctx->d_model, image.data(), kModelBytes, hipMemcpyHostToDevice) == hipSuccess;
+    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void*>(&encode_kernel<2, 512>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, kModelBytes) == hipSuccess;
+    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void*>(&encode_kernel<3, 512>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, kModelBytes) == hipSuccess;
+    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void*>(&encode_kernel<4, 256>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, kModelBytes) == hipSuccess;
+    if (const char* e = getenv("PCC_ENCODE_VARIANT")) {
+        const int v = atoi(e);
+        if (v >= 0 && v < 3) ctx->encode_variant = v;
+    }
+    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_kernel),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, kModelBytes + 1024) == hipSuccess;
+    if (!ok) { (void)hipGetLastError(); pcc_destroy(ctx); return PCC_E_HIP; }
+    ctx->d_total = reinterpret_cast<uint64_t*>(ctx->d_status + kStWords);
+    *out = ctx;
+    return PCC_OK;
+}
+
+void pcc_destroy(pcc_ctx* ctx) {
+    if (!ctx) return;
+    DeviceGuard guard(ctx->device);
+    if (ctx->d_model) (void)hipFree(ctx->d_model);
+    if (ctx->d_ws) (void)hipFree(ctx->d_ws);
+    if (ctx->d_status) (void)hipFree(ctx->d_status);
+    if (ctx->h_status) (void)hipHostFree(ctx->h_status);
+    delete ctx;
+}
+
+static int launch_encode(pcc_ctx* ctx, const uint8_t* d_img, int n, int H, int W, uint32_t* sf, float* params,
+                         float* bits, hipStream_t st) {
+    const uint32_t P = (uint32_t)((uint64_t)n * H * W);
+    const EncodeVariant ev = kEncodeVariants[ctx->encode_variant];
+    const uint32_t per_block = 16u * ev.tiles * (ev.threads / 64);
+    uint32_t blocks = (P + per_block - 1) / per_block;
+    const uint32_t cus = ctx->num_cus > 0 ? (uint32_t)ctx->num_cus : 256u;
+    if (blocks > cus) blocks = cus;   // persistent: one workgroup per CU, looping over pixel groups
+    switch (ctx->encode_variant) {
+        case 0:
+            hipLaunchKernelGGL((encode_kernel<2, 512>), dim3(blocks), dim3(512), kModelBytes, st, ctx->d_model, d_img,
+                               H, W, P, sf, params, bits, ctx->d_status);
+            break;
+        case 1:
+            hipLaunchKernelGGL((encode_kernel<3, 512>), dim3(blocks), dim3(512), kModelBytes, st, ctx->d_model, d_img,
+                               H, W, P, sf, params, bits, ctx->d_status);
+            break;
+        default:
+            hipLaunchKernelGGL((encode_kernel<4, 256>), dim3(blocks), dim3(256), kModelBytes, st, ctx->d_model, d_img,
+                               H, W, P, sf, params, bits, ctx->d_status);
+            break;
+    }
+    return hipGetLastError() == hipSuccess ? PCC_OK : PCC_E_HIP;
+}
+
+int pcc_encode_probs(pcc_ctx* ctx, const uint8_t* d_img, int n, int H, int W, float* d_params, float* d_bits,
+                     void* hip_stream) {
+    if (!ctx || !d_img || !d_params || !dims_ok(n, H, W)) return PCC_E_ARG;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return PCC_E_HIP;
+    return launch_encode(ctx, d_img, n, H, W, nullptr, d_params, d_bits, (hipStream_t)hip_stream);
+}
+
+int pcc_encode(pcc_ctx* ctx, const uint8_t* d_img, int n, int H, int W, uint8_t* d_stream, size_t cap_bytes,
+               size_t* h_nbytes_out, void* hip_stream) {
+    if (!ctx || !d_img || !d_stream || !h_nbytes_out || !dims_ok(n, H, W)) return PCC_E_ARG;
+    if (((uintptr_t)d_stream & 7u) != 0) return PCC_E_ARG;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return PCC_E_HIP;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const uint64_t P = (uint64_t)n * H * W;
+    const uint32_t rows = (uint32_t)((uint64_t)n * H);
+    const size_t table = (size_t)kStreamHeader + 8 * ((size_t)rows + 1);
+    if (cap_bytes < table) return PCC_E_CAP;
+
+    const size_t sf_bytes = align_up(P * 3 * sizeof(uint32_t), 256);
+    const size_t slab_bytes = align_up((size_t)rows * slab_words(W) * 4, 256);
+    const size_t rw_bytes = align_up((size_t)rows * 4, 256);
+    int rc = ensure_workspace(ctx, sf_bytes + slab_bytes + rw_bytes);
+    if (rc != PCC_OK) return rc;
+    uint32_t* d_sf = reinterpret_cast<uint32_t*>(ctx->d_ws);
+    uint32_t* d_slabs = reinterpret_cast<uint32_t*>(ctx->d_ws + sf_bytes);
+    uint32_t* d_rw = reinterpret_cast<uint32_t*>(ctx->d_ws + sf_bytes + slab_bytes);
+    ctx->d_sf = d_sf;
+    ctx->sf_count = (size_t)P * 3;
+
+    if (hipMemsetAsync(ctx->d_status, 0, kStWords * sizeof(int) + sizeof(uint64_t), st) != hipSuccess) return PCC_E_HIP;
+    rc = launch_encode(ctx, d_img, n, H, W, d_sf, nullptr, nullptr, st);
+    if (rc != PCC_OK) return rc;
+    hipLaunchKernelGGL(rans_rows_kernel, dim3((rows + 63) / 64), dim3(64), 0, st, d_sf, W, rows, d_slabs, d_rw);
+    hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), 0, st, d_rw, rows, n, H, W, d_stream, ctx->d_total);
+    hipLaunchKernelGGL(compact_kernel, dim3(rows), dim3(64), 0, st, d_slabs, d_rw, W, rows, d_stream,
+                       (uint64_t)cap_bytes, ctx->d_status);
+    if (hipGetLastError() != hipSuccess) return PCC_E_HIP;
+    if (hipMemcpyAsync(ctx->h_status, ctx->d_status, kStWords * sizeof(int) + sizeof(uint64_t), hipMemcpyDeviceToHost,
+                       st) != hipSuccess) return PCC_E_HIP;
+    if (hipStreamSynchronize(st) != hipSuccess) { (void)hipGetLastError(); return PCC_E_HIP; }
+    if (ctx->h_status[kStErr] != 0) return ctx->h_status[kStErr];
+    uint64_t total;
+    memcpy(&total, ctx->h_status + kStWords, sizeof(total));
+    if (total > cap_bytes) return PCC_E_CAP;
+    *h_nbytes_out = (size_t)total;
+    return PCC_OK;
+}
+
+int pcc_decode(pcc_ctx* ctx, const uint8_t* d_stream, size_t nbytes, int n, int H, int W, uint8_t* d_img_out,
+               void* hip_stream) {
+    if (!ctx || !d_stream || !d_img_out || !dims_ok(n, H, W)) return PCC_E_ARG;
+    if (((uintptr_t)d_stream & 7u) != 0) return PCC_E_ARG;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return PCC_E_HIP;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const uint64_t rows = (uint64_t)n * H;
+    const uint64_t table = (uint64_t)kStreamHeader + 8 * (rows + 1);
+    if (nbytes < table + 8 * rows) return PCC_E_STREAM;   // every row payload holds at least its 8-byte state
+    const int nbands = (H + kBandRows - 1) / kBandRows;
+    const size_t mail_bytes = align_up((size_t)n * nbands * 2 * (size_t)W * 4, 256);
+    int rc = ensure_workspace(ctx, mail_bytes);
+    if (rc != PCC_OK) return rc;
+    ctx->d_sf = nullptr; ctx->sf_count = 0;
+    uint32_t* d_mail = reinterpret_cast<uint32_t*>(ctx->d_ws);
+    if (hipMemsetAsync(ctx->d_status, 0, kStWords * sizeof(int) + sizeof(uint64_t), st) != hipSuccess) return PCC_E_HIP;
+    if (hipMemsetAsync(d_mail, 0, mail_bytes, st) != hipSuccess) return PCC_E_HIP;
+    const uint32_t spin_limit = 1u << 22;
+    hipLaunchKernelGGL(decode_kernel, dim3((uint32_t)(n * nbands)), dim3(64), kModelBytes + 1024, st, ctx->d_model,
+                       d_stream, (uint64_t)nbytes, n, H, W, nbands, d_img_out, d_mail, ctx->d_status, spin_limit);
+    if (hipGetLastError() != hipSuccess) return PCC_E_HIP;
+    if (hipMemcpyAsync(ctx->h_status, ctx->d_status, kStWords * sizeof(int), hipMemcpyDeviceToHost, st) != hipSuccess)
+        return PCC_E_HIP;
+    if (hipStreamSynchronize(st) != hipSuccess) { (void)hipGetLastError(); return PCC_E_HIP; }
+    return ctx->h_status[kStErr];
+}
+
+int pcc_cdf_tables(pcc_ctx* ctx, const float* d_params, const uint8_t* d_rg, size_t count, uint32_t* d_cq,
+                   void* hip_stream) {
+    if (!ctx || !d_params || !d_rg || !d_cq || count == 0 || count > (1u << 26)) return PCC_E_ARG;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return PCC_E_HIP;
+    const size_t threads = count * 3;
+    hipLaunchKernelGGL(cdf_tables_kernel, dim3((uint32_t)((threads + 255) / 256)), dim3(256), (kLutEntries + 1) * 8,
+                       (hipStream_t)hip_stream, ctx->d_model, d_params, d_rg, count, d_cq);
+    return hipGetLastError() == hipSuccess ? PCC_OK : PCC_E_HIP;
+}
+
+int pcc_copy_intervals(pcc_ctx* ctx, uint32_t* d_out, size_t count, void* hip_stream) {
+    if (!ctx || !d_out) return PCC_E_ARG;
+    if (!ctx->d_sf || count != ctx->sf_count) return PCC_E_ARG;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return PCC_E_HIP;
+    if (hipMemcpyAsync(d_out, ctx->d_sf, count * sizeof(uint32_t), hipMemcpyDeviceToDevice, (hipStream_t)hip_stream) !=
+        hipSuccess) return PCC_E_HIP;
+    return PCC_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,291 @@
+"""HIP path against the CPU oracle, through the C ABI.  Needs an MI355X."""
+import struct
+
+import numpy as np
+import pytest
+
+from oracle import pcc_oracle as po
+from paper_2212_01185_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+# Raw head outputs: GPU (bf16 products, fp32 accumulation) against the oracle
+# evaluating the same bf16-activation network in fp64.  The bound the task sets.
+PARAM_ATOL = 2e-3
+# Against the oracle's exact (unrounded-activation) network: bf16 activations carry
+# 2^-9 relative error through three layers; reported, loosely bounded.
+PARAM_ATOL_EXACT = 5e-2
+BITS_RTOL = 1e-3          # bits/pixel within 0.1 %
+CQ_ATOL = 2               # integer CDF counts: fp32 + table-interpolated Phi vs fp64 erfc
+
+
+def _log(msg):
+    print(msg, flush=True)
+
+
+@pytest.fixture(scope="module")
+def codec(blob):
+    from paper_2212_01185_amd import binding
+    if not torch.cuda.is_available():
+        pytest.fail("no GPU visible")
+    c = binding.Codec(blob, 0)
+    yield c
+    c.close()
+
+
+@pytest.fixture(scope="module")
+def codec_sharp(sharp_blob):
+    from paper_2212_01185_amd import binding
+    c = binding.Codec(sharp_blob, 0)
+    yield c
+    c.close()
+
+
+def _dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def _roundtrip(codec, imgs):
+    n, h, w, _ = imgs.shape
+    d = _dev(imgs)
+    stream = codec.pcc_encode(d)
+    out = codec.pcc_decode(stream, n, h, w)
+    torch.cuda.synchronize()
+    return stream, out.cpu().numpy()
+
+
+# ----------------------------------------------------------------- config 0, element by element
+
+def test_params_match_oracle_config0(codec, orc):
+    imgs = synth.make_batch(0)
+    _log("config0 encode_probs")
+    params, bits = codec.pcc_encode_probs(_dev(imgs))
+    torch.cuda.synchronize()
+    params = params.cpu().numpy().astype(np.float64)[0]
+    want = orc.params_rows(imgs[0], range(64), po.MODE_BF16ACT)
+    err = np.abs(params - want).max()
+    _log("max |params - oracle(bf16 activations)| = %.3g" % err)
+    assert err <= PARAM_ATOL
+    exact = orc.params_rows(imgs[0], range(64), po.MODE_EXACT)
+    err_exact = np.abs(params - exact).max()
+    _log("max |params - oracle(exact activations)| = %.3g" % err_exact)
+    assert err_exact <= PARAM_ATOL_EXACT
+
+
+def test_bits_match_oracle_config0(codec, orc):
+    imgs = synth.make_batch(0)
+    _, bits = codec.pcc_encode_probs(_dev(imgs))
+    torch.cuda.synchronize()
+    bits = bits.cpu().numpy().astype(np.float64)
+    _, want = orc.encode(imgs, po.MODE_BF16ACT)
+    _, want_exact = orc.encode(imgs, po.MODE_EXACT)
+    _log("bpp gpu %.5f oracle(bf16act) %.5f oracle(exact) %.5f" % (bits.mean(), want.mean(), want_exact.mean()))
+    assert abs(bits.sum() / want.sum() - 1) <= BITS_RTOL
+    assert abs(bits.sum() / want_exact.sum() - 1) <= BITS_RTOL
+    # per pixel: the same distributions up to a few counts in 65536
+    assert np.abs(bits - want).max() < 0.25
+
+
+def test_roundtrip_config0_and_stream_length(codec, orc):
+    imgs = synth.make_batch(0)
+    stream, out = _roundtrip(codec, imgs)
+    np.testing.assert_array_equal(out, imgs)
+    _, bits = codec.pcc_encode_probs(_dev(imgs))
+    ideal = float(bits.double().sum().item())
+    rows = 64
+    over = 8 * stream.numel() - ideal
+    lo = 8 * (32 + 8 * (rows + 1)) + rows * 32
+    hi = 8 * (32 + 8 * (rows + 1)) + rows * 96 + 3 * 64 * 64 * 2.0 ** -14
+    _log("stream %d bytes, ideal %.1f bytes, overhead %.0f bits" % (stream.numel(), ideal / 8, over))
+    assert lo - 64 <= over <= hi + 64      # the fp32 log2 of the bit count carries a little rounding
+    # oracle stream is about as long (different floating point, same model)
+    ostream, _ = orc.encode(imgs, po.MODE_BF16ACT)
+    assert abs(stream.numel() / len(ostream) - 1) <= BITS_RTOL
+
+
+# ----------------------------------------------------------------- integer work, bit exact
+
+def _expected_stream(imgs_shape, intervals):
+    """Assemble the container from oracle-coded rows of the given (start, freq) pairs."""
+    n, h, w, _ = imgs_shape
+    sf = intervals.reshape(n * h, 3 * w).astype(np.uint32)
+    payloads = [po.rans_encode(row & 0xFFFF, (row >> 16) + 1) for row in sf]
+    offs = np.concatenate([[0], np.cumsum([len(p) for p in payloads])]).astype("<u8")
+    tag = 5 | (10 << 8) | (2 << 16) | (16 << 24)
+    head = struct.pack("<8I", 0x31434350, 1, n, h, w, tag, 0, 0)
+    return head + offs.tobytes() + b"".join(payloads)
+
+
+@pytest.mark.parametrize("shape", [(1, 64, 64), (2, 17, 33), (1, 5, 300)])
+def test_coder_and_container_bit_exact(codec, codec_sharp, shape):
+    n, h, w = shape
+    rng = np.random.default_rng(11)
+    imgs = rng.integers(0, 256, (n, h, w, 3), dtype=np.uint8)
+    for c in (codec, codec_sharp):
+        stream = c.pcc_encode(_dev(imgs))
+        iv = c.pcc_copy_intervals(n, h, w)
+        torch.cuda.synchronize()
+        iv = iv.cpu().numpy().view(np.uint32)
+        freq = (iv >> 16) + 1
+        assert freq.min() >= 1 and ((iv & 0xFFFF) + freq).max() <= 65536
+        want = _expected_stream(imgs.shape, iv)
+        got = stream.cpu().numpy().tobytes()
+        assert got == want
+
+
+def test_cdf_tables_against_oracle(codec, orc):
+    rng = np.random.default_rng(12)
+    heads = [rng.normal(0, s, 60) for s in (0.1, 0.5, 1.0, 3.0) for _ in range(40)]
+    for mu in (0.0, 0.5, 100.2 / 256, 100.5 / 256, 255 / 256, -3.0, 4.0):
+        for ls in (-20.0, -8.0, -4.0, 0.0, 4.0, 20.0):
+            o = np.zeros(60)
+            o[5:10] = o[20:25] = o[35:40] = mu
+            o[10:15] = o[25:30] = o[40:45] = ls
+            heads.append(o)
+    heads = np.asarray(heads, dtype=np.float32)
+    rg = rng.integers(0, 256, (len(heads), 2), dtype=np.uint8)
+    cq = codec.pcc_cdf_tables(_dev(heads), _dev(rg))
+    torch.cuda.synchronize()
+    cq = cq.cpu().numpy().astype(np.int64)
+    assert (cq[:, :, 0] == 0).all() and (cq[:, :, 256] == 65536).all()
+    assert (np.diff(cq, axis=2) >= 1).all()
+    worst = 0
+    for i, o in enumerate(heads.astype(np.float64)):
+        for ch in range(3):
+            want = orc.cdf_table(o, ch, int(rg[i, 0]), int(rg[i, 1])).astype(np.int64)
+            worst = max(worst, int(np.abs(cq[i, ch] - want).max()))
+    _log("max |Cq_gpu - Cq_oracle| = %d counts" % worst)
+    assert worst <= CQ_ATOL
+
+
+# ----------------------------------------------------------------- round trips: edge shapes
+
+def _edge_images():
+    rng = np.random.default_rng(13)
+    yield "1x1", rng.integers(0, 256, (1, 1, 1, 3), dtype=np.uint8)
+    yield "1x9", rng.integers(0, 256, (1, 1, 9, 3), dtype=np.uint8)
+    yield "9x1", rng.integers(0, 256, (1, 9, 1, 3), dtype=np.uint8)
+    yield "2x2", rng.integers(0, 256, (1, 2, 2, 3), dtype=np.uint8)
+    yield "3x5x2", rng.integers(0, 256, (2, 3, 5, 3), dtype=np.uint8)
+    yield "16x16", rng.integers(0, 256, (1, 16, 16, 3), dtype=np.uint8)
+    yield "17x33x3", rng.integers(0, 256, (3, 17, 33, 3), dtype=np.uint8)     # ragged band, ragged tile
+    yield "40x7", rng.integers(0, 256, (1, 40, 7, 3), dtype=np.uint8)         # taller than wide
+    yield "zeros", np.zeros((1, 33, 20, 3), dtype=np.uint8)
+    yield "ones", np.full((1, 33, 20, 3), 255, dtype=np.uint8)
+    yield "blobs", synth.make_image(3, synth.ImageSpec(100, 50, 5, 3.0, 12.0))[None]
+
+
+def test_roundtrip_edge_shapes(codec, codec_sharp):
+    for name, imgs in _edge_images():
+        for which, c in (("default", codec), ("sharp", codec_sharp)):
+            _log("roundtrip %s %s" % (name, which))
+            _, out = _roundtrip(c, imgs)
+            np.testing.assert_array_equal(out, imgs, err_msg="%s %s" % (name, which))
+
+
+def test_decode_output_is_fully_overwritten(codec):
+    imgs = synth.make_image(4, synth.ImageSpec(37, 21, 3, 2.0, 8.0))[None]
+    stream = codec.pcc_encode(_dev(imgs))
+    out = torch.full((1, 21, 37, 3), 77, dtype=torch.uint8, device="cuda")
+    codec.pcc_decode(stream, 1, 21, 37, out=out)
+    np.testing.assert_array_equal(out.cpu().numpy(), imgs)
+
+
+# ----------------------------------------------------------------- error paths (no hang, no fault)
+
+def test_errors_are_reported(codec):
+    from paper_2212_01185_amd import binding
+    imgs = synth.make_image(5, synth.ImageSpec(48, 40, 3, 2.0, 8.0))[None]
+    d = _dev(imgs)
+    stream = codec.pcc_encode(d)
+    with pytest.raises(binding.PccError) as e:
+        codec.pcc_encode(d, out=torch.empty(64, dtype=torch.uint8, device="cuda"))
+    assert e.value.code == binding.PCC_E_CAP
+    with pytest.raises(binding.PccError) as e:
+        codec.pcc_encode(d, out=torch.empty(stream.numel() - 4, dtype=torch.uint8, device="cuda"))
+    assert e.value.code == binding.PCC_E_CAP
+    for bad_dims in ((1, 40, 49), (1, 41, 48), (2, 40, 48)):
+        with pytest.raises(binding.PccError) as e:
+            codec.pcc_decode(stream, *bad_dims)
+        assert e.value.code == binding.PCC_E_STREAM
+    with pytest.raises(binding.PccError) as e:
+        codec.pcc_decode(stream[:-4].clone(), 1, 40, 48)
+    assert e.value.code == binding.PCC_E_STREAM
+    bad = stream.clone()
+    bad[0] ^= 1
+    with pytest.raises(binding.PccError) as e:
+        codec.pcc_decode(bad, 1, 40, 48)
+    assert e.value.code == binding.PCC_E_STREAM
+    # flipped payload bits: an error or a different image, never a hang and never silently the same
+    rng = np.random.default_rng(14)
+    table_end = 32 + 8 * 41
+    for _ in range(8):
+        bad = stream.clone()
+        pos = int(rng.integers(table_end, stream.numel()))
+        bad[pos] ^= 1 << int(rng.integers(0, 8))
+        try:
+            out = codec.pcc_decode(bad, 1, 40, 48).cpu().numpy()
+        except binding.PccError as err:
+            assert err.code == binding.PCC_E_STREAM
+            continue
+        assert (out != imgs).any()
+    # and the codec still works afterwards
+    out = codec.pcc_decode(stream, 1, 40, 48).cpu().numpy()
+    np.testing.assert_array_equal(out, imgs)
+
+
+# ----------------------------------------------------------------- full-size workloads
+
+def _sample_check(codec, orc, imgs, n_pixels, n_rows, seed):
+    """Sampled pixels' head outputs and sampled rows' bits against the oracle."""
+    n, h, w, _ = imgs.shape
+    params, bits = codec.pcc_encode_probs(_dev(imgs))
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(seed)
+    pts = [(0, 0, 0), (n - 1, h - 1, w - 1), (0, 0, w - 1), (n - 1, h - 1, 0), (0, 1, 1), (0, 2, 2)]
+    pts += [(int(rng.integers(n)), int(rng.integers(h)), int(rng.integers(w))) for _ in range(n_pixels)]
+    idx = torch.tensor(pts, device="cuda")
+    got = params[idx[:, 0], idx[:, 1], idx[:, 2]].cpu().numpy().astype(np.float64)
+    want = np.stack([orc.params_at(imgs[i], r, c, po.MODE_BF16ACT) for i, r, c in pts])
+    err = np.abs(got - want).max()
+    _log("sampled params: max err %.3g over %d pixels" % (err, len(pts)))
+    assert err <= PARAM_ATOL
+    # bits on whole rows: encode single-row-context strips with the oracle
+    tot_g = tot_o = 0.0
+    for _ in range(n_rows):
+        i, r = int(rng.integers(n)), int(rng.integers(2, h))
+        strip = imgs[i:i + 1, r - 2:r + 1]          # rows r-2..r: the last row sees its true context
+        _, b = orc.encode(strip, po.MODE_BF16ACT)
+        tot_o += b[0, 2].sum()
+        tot_g += float(bits[i, r].double().sum().item())
+    _log("sampled rows: bits gpu %.1f oracle %.1f" % (tot_g, tot_o))
+    assert abs(tot_g / tot_o - 1) <= BITS_RTOL
+
+
+@pytest.mark.parametrize("config", [1, 3, 4])
+def test_full_size_single_image(codec, orc, config):
+    _log("config %d: generate" % config)
+    imgs = synth.make_batch(config)
+    n, h, w, _ = imgs.shape
+    _sample_check(codec, orc, imgs, 200, 3 if config == 1 else 1, 20 + config)
+    _log("config %d: round trip" % config)
+    stream, out = _roundtrip(codec, imgs)
+    assert np.array_equal(out, imgs)
+    _, bits = codec.pcc_encode_probs(_dev(imgs))
+    ideal = float(bits.double().sum().item())
+    rows = n * h
+    over = 8 * stream.numel() - ideal
+    _log("config %d: %d bytes, %.4f bpsp, overhead %.0f bits" % (config, stream.numel(), ideal / imgs.size, over))
+    assert 8 * (32 + 8 * (rows + 1)) + rows * 32 - 1e-4 * ideal <= over
+    assert over <= 8 * (32 + 8 * (rows + 1)) + rows * 96 + imgs.size * 2.0 ** -14 + 1e-4 * ideal
+
+
+def test_batch_of_24(codec, orc):
+    _log("config 2: generate")
+    imgs = synth.make_batch(2)
+    _sample_check(codec, orc, imgs, 100, 2, 22)
+    _log("config 2: round trip")
+    _, out = _roundtrip(codec, imgs)
+    assert np.array_equal(out, imgs)

@@ -1,0 +1,49 @@
+"""The C-ABI library loads and exports every function include/pcc.h declares (no GPU needed)."""
+import ctypes
+import os
+import re
+
+from paper_2212_01185_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "pcc.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(pcc_[a-z_]+)\s*\(", text)))
+
+
+def test_header_and_binding_agree():
+    assert _declared() == sorted(binding.EXPORTS)
+
+
+def test_library_exports_every_declared_symbol():
+    lib = binding.load()
+    for name in _declared():
+        assert getattr(lib, name) is not None, name
+
+
+def test_host_only_entry_points():
+    assert binding.pcc_strerror(0) == "ok"
+    assert "stream" in binding.pcc_strerror(binding.PCC_E_STREAM)
+    assert binding.pcc_wavefront_steps(512, 768) == 1790
+    # header + offsets + per row (state + at most 2 bytes per symbol + slack)
+    b = binding.pcc_stream_bound(1, 64, 64)
+    assert 32 + 8 * 65 + 64 * (8 + 6 * 64) <= b <= 32 + 8 * 65 + 64 * (6 * 64 + 24)
+    assert binding.pcc_stream_bound(0, 1, 1) == 0
+
+
+def test_create_rejects_bad_blobs_before_touching_the_gpu(blob):
+    lib = binding.load()
+    h = ctypes.c_void_p()
+    for bad in (blob[:-4], b"\0" * len(blob), blob[:64]):
+        buf = ctypes.create_string_buffer(bad, len(bad))
+        assert lib.pcc_create(ctypes.byref(h), buf, len(bad), 0) == binding.PCC_E_BLOB
+    # a weight that is not a bf16 value
+    import numpy as np
+    arr = np.frombuffer(blob, dtype=np.uint8).copy()
+    arr[64] = 1            # low mantissa byte of W1[0][0]
+    buf = ctypes.create_string_buffer(arr.tobytes(), len(blob))
+    assert lib.pcc_create(ctypes.byref(h), buf, len(blob), 0) == binding.PCC_E_BLOB
+    assert lib.pcc_create(None, buf, len(blob), 0) == binding.PCC_E_ARG
