@@ -46,7 +46,7 @@
 #define ORC_MAX_WIDTH 512
 #define ORC_MAX_K 8
 
-enum { ORC_MODE_EXACT = 0, ORC_MODE_BF16ACT = 1 };
+enum { ORC_MODE_EXACT = 0, ORC_MODE_SPLIT_BF16 = 1 };
 enum { ORC_ORDER_RASTER = 0, ORC_ORDER_WAVEFRONT = 1 };
 
 typedef struct {
@@ -150,8 +150,11 @@ static double round_bf16(double x) {
 
 /* The probability network as a fully connected stack on C_ij (Sec. III-B with
  * the equivalence of Sec. III-C, second paragraph): ReLU between layers, none
- * after the last.  Mode BF16ACT rounds every hidden activation to bf16 before
- * the next layer -- the quantised network the matrix-core path implements. */
+ * after the last.  Mode EXACT is the definition.  Mode SPLIT_BF16 rounds every
+ * hidden activation a to hi + lo with hi = bf16(a), lo = bf16(a - hi), i.e. to
+ * about 16 significant bits -- the representation the matrix-core path feeds
+ * to its bf16 multipliers; it exists to show how little that rounding moves
+ * the outputs, not as a second definition. */
 void orc_mlp(const orc_model *m, const double *u, int mode, double *o) {
     double a[ORC_MAX_WIDTH], z[ORC_MAX_WIDTH];
     for (int i = 0; i < m->dims[0]; ++i) a[i] = u[i];
@@ -165,7 +168,8 @@ void orc_mlp(const orc_model *m, const double *u, int mode, double *o) {
         if (l + 1 < m->n_layers) {
             for (int j = 0; j < nout; ++j) {
                 double h = z[j] > 0.0 ? z[j] : 0.0;
-                a[j] = (mode == ORC_MODE_BF16ACT) ? round_bf16(h) : h;
+                if (mode == ORC_MODE_SPLIT_BF16) { double hi = round_bf16(h); h = hi + round_bf16(h - hi); }
+                a[j] = h;
             }
         } else {
             for (int j = 0; j < nout; ++j) o[j] = z[j];

@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "pcc_oracle.c")
 _LIB = os.path.join(_HERE, "libpcc_oracle.so")
 
-MODE_EXACT, MODE_BF16ACT = 0, 1
+MODE_EXACT, MODE_SPLIT = 0, 1
 ORDER_RASTER, ORDER_WAVEFRONT = 0, 1
 OK, E_ARG, E_BLOB, E_CAP, E_STREAM, E_INTERNAL = 0, -1, -2, -3, -4, -6
 

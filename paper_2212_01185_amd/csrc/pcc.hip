@@ -35,7 +35,7 @@ constexpr uint32_t kMailTag = 0x80000000u;
 // More tiles per wave reuse each LDS weight read more often but need more registers
 // (4 tiles only fit with one wave per SIMD).
 struct EncodeVariant { int tiles, threads; };
-constexpr EncodeVariant kEncodeVariants[3] = {{2, 512}, {3, 512}, {4, 256}};
+constexpr EncodeVariant kEncodeVariants[3] = {{1, 512}, {2, 512}, {2, 256}};
 constexpr int kDefaultEncodeVariant = 0;
 
 // status words in device memory
@@ -124,7 +124,7 @@ encode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ img
     const uint32_t groups = (P + 16 * T - 1) / (16 * T);
 
     for (uint32_t grp = blockIdx.x * nwaves + wave; grp < groups; grp += gridDim.x * nwaves) {
-        u32x4_t in[T][1];
+        u32x4_t in[T][1][2];
         uint32_t pix[T];   // the pixel's own bytes r | g<<8 | b<<16
 #pragma unroll
         for (int t = 0; t < T; ++t) {
@@ -152,14 +152,15 @@ encode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ img
                         slots[i] = byte_to_bf16(base[((size_t)rr * W + (c - 2)) * 3 + b]);
                 }
             }
-            in[t][0].x = slots[0] | (slots[1] << 16);
-            in[t][0].y = slots[2] | (slots[3] << 16);
-            in[t][0].z = slots[4] | (slots[5] << 16);
-            in[t][0].w = slots[6] | (slots[7] << 16);
+            in[t][0][0].x = slots[0] | (slots[1] << 16);
+            in[t][0][0].y = slots[2] | (slots[3] << 16);
+            in[t][0][0].z = slots[4] | (slots[5] << 16);
+            in[t][0][0].w = slots[6] | (slots[7] << 16);
+            in[t][0][1] = in[t][0][0];   // unused (layer-1 inputs are exact)
         }
 
         f32x4_t out[T][kL4_OB];
-        mlp_forward<T, 2, 2>(lds + opaque_zero(), lane, in, out);
+        mlp_forward<T, (T == 1 ? 10 : 2), (T == 1 ? 8 : 2)>(lds + opaque_zero(), lane, in, out);
 
 #pragma unroll
         for (int t = 0; t < T; ++t) {
@@ -399,7 +400,7 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
         const bool active = row_ok && c >= 0 && c < W;
 
         // gather C_ij from the ring (zero outside the image)
-        u32x4_t in[1][1];
+        u32x4_t in[1][1][2];
         {
             uint32_t slots[8];
 #pragma unroll
@@ -414,10 +415,11 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
                 const uint32_t px = ring[nl + 2 + dr][colx & 7];
                 slots[i] = ok ? byte_to_bf16((px >> (8 * ch)) & 0xFFu) : 0u;
             }
-            in[0][0].x = slots[0] | (slots[1] << 16);
-            in[0][0].y = slots[2] | (slots[3] << 16);
-            in[0][0].z = slots[4] | (slots[5] << 16);
-            in[0][0].w = slots[6] | (slots[7] << 16);
+            in[0][0][0].x = slots[0] | (slots[1] << 16);
+            in[0][0][0].y = slots[2] | (slots[3] << 16);
+            in[0][0][0].z = slots[4] | (slots[5] << 16);
+            in[0][0][0].w = slots[6] | (slots[7] << 16);
+            in[0][0][1] = in[0][0][0];   // unused (layer-1 inputs are exact)
         }
 
         f32x4_t out[1][kL4_OB];
@@ -671,11 +673,11 @@ int pcc_create(pcc_ctx** out, const void* h_blob, size_t blob_bytes, int hip_dev
     ok = ok && hipMalloc((void**)&ctx->d_status, kStWords * sizeof(int) + sizeof(uint64_t)) == hipSuccess;
     ok = ok && hipHostMalloc((void**)&ctx->h_status, kStWords * sizeof(int) + sizeof(uint64_t), hipHostMallocDefault) == hipSuccess;
     ok = ok && hipMemcpy(ctx->d_model, image.data(), kModelBytes, hipMemcpyHostToDevice) == hipSuccess;
+    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void*>(&encode_kernel<1, 512>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, kModelBytes) == hipSuccess;
     ok = ok && hipFuncSetAttribute(reinterpret_cast<const void*>(&encode_kernel<2, 512>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, kModelBytes) == hipSuccess;
-    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void*>(&encode_kernel<3, 512>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, kModelBytes) == hipSuccess;
-    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void*>(&encode_kernel<4, 256>),
+    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void*>(&encode_kernel<2, 256>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, kModelBytes) == hipSuccess;
     if (const char* e = getenv("PCC_ENCODE_VARIANT")) {
         const int v = atoi(e);
@@ -709,15 +711,15 @@ static int launch_encode(pcc_ctx* ctx, const uint8_t* d_img, int n, int H, int W
     if (blocks > cus) blocks = cus;   // persistent: one workgroup per CU, looping over pixel groups
     switch (ctx->encode_variant) {
         case 0:
-            hipLaunchKernelGGL((encode_kernel<2, 512>), dim3(blocks), dim3(512), kModelBytes, st, ctx->d_model, d_img,
+            hipLaunchKernelGGL((encode_kernel<1, 512>), dim3(blocks), dim3(512), kModelBytes, st, ctx->d_model, d_img,
                                H, W, P, sf, params, bits, ctx->d_status);
             break;
         case 1:
-            hipLaunchKernelGGL((encode_kernel<3, 512>), dim3(blocks), dim3(512), kModelBytes, st, ctx->d_model, d_img,
+            hipLaunchKernelGGL((encode_kernel<2, 512>), dim3(blocks), dim3(512), kModelBytes, st, ctx->d_model, d_img,
                                H, W, P, sf, params, bits, ctx->d_status);
             break;
         default:
-            hipLaunchKernelGGL((encode_kernel<4, 256>), dim3(blocks), dim3(256), kModelBytes, st, ctx->d_model, d_img,
+            hipLaunchKernelGGL((encode_kernel<2, 256>), dim3(blocks), dim3(256), kModelBytes, st, ctx->d_model, d_img,
                                H, W, P, sf, params, bits, ctx->d_status);
             break;
     }

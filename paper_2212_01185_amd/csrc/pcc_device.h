@@ -77,15 +77,19 @@ __host__ __device__ constexpr int head_index(int g, int s) {
 // bf16 helpers
 // ---------------------------------------------------------------------------
 
-// Two fp32 -> packed bf16 (round to nearest even), then ReLU on the packed pair
-// (a bf16 is negative iff its 16 bits are negative as an integer).
-__device__ __forceinline__ uint32_t relu_pack_bf16(float lo, float hi) {
-    f32x2_t v = {lo, hi};
-    bf16x2_t b = __builtin_convertvector(v, bf16x2_t);
-    s16x2_t s = __builtin_bit_cast(s16x2_t, b);
-    s16x2_t z = {0, 0};
-    s = __builtin_elementwise_max(s, z);
-    return __builtin_bit_cast(uint32_t, s);
+// Hidden activations are carried as the sum of two bf16 numbers, a ~= hi + lo with
+// hi = bf16(a), lo = bf16(a - hi) (both round to nearest even): 16 significant
+// bits, so that the bf16 matrix cores reproduce the fp32 network to ~1e-5
+// instead of ~1e-2.  Each weight tile is multiplied with hi and then with lo.
+// Packs two ReLU'd values: returns the hi pair, writes the lo pair.
+__device__ __forceinline__ uint32_t relu_split_bf16(float a0, float a1, uint32_t& lo_pair) {
+    a0 = fmaxf(a0, 0.0f);
+    a1 = fmaxf(a1, 0.0f);
+    const f32x2_t v = {a0, a1};
+    const uint32_t hi = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+    const f32x2_t r = {a0 - __uint_as_float(hi << 16), a1 - __uint_as_float(hi & 0xFFFF0000u)};
+    lo_pair = __builtin_bit_cast(uint32_t, __builtin_convertvector(r, bf16x2_t));
+    return hi;
 }
 
 // bf16 bit pattern of an integer 0..255 (exact).  The 1/256 input scaling is
@@ -101,13 +105,15 @@ __device__ __forceinline__ f32x4_t mfma16(u32x4_t a, u32x4_t b, f32x4_t c) {
 
 // ---------------------------------------------------------------------------
 // The network on T tiles of 16 pixels held by one wave.
-//   in[t]      layer-1 B operand of tile t (8 bf16 per lane)
-//   out[t][ob] raw head outputs, register s = 4*ob + i  <->  head_index(lane>>4, s)
-// Accumulation order per output element: bias, then k-blocks 0,1,2,...
+//   in[t][0][0] layer-1 B operand of tile t (8 bf16 per lane)
+//   out[t][ob]  raw head outputs, register s = 4*ob + i  <->  head_index(lane>>4, s)
+// Accumulation order per output element: bias, then k-blocks 0,1,2,..., each hi then lo.
 // ---------------------------------------------------------------------------
-template <int T, int NOB, int NKB, int OBG>
+// Activations of one layer for T tiles: [tile][k-block][0 = hi, 1 = lo].
+template <int T, int NOB, int NKB, int OBG, bool SPLIT_IN>
 __device__ __forceinline__ void hidden_layer(const uint8_t* __restrict__ w, const float* __restrict__ bias,
-                                             int lane, const u32x4_t (&in)[T][NKB], u32x4_t (&out)[T][NOB / 2]) {
+                                             int lane, const u32x4_t (&in)[T][NKB][2],
+                                             u32x4_t (&out)[T][NOB / 2][2]) {
     static_assert(NOB % OBG == 0 && OBG % 2 == 0, "out-block group must be even and divide the layer");
     const int g = lane >> 4;
 #pragma unroll
@@ -125,19 +131,25 @@ __device__ __forceinline__ void hidden_layer(const uint8_t* __restrict__ w, cons
             for (int j = 0; j < OBG; ++j) {
                 const u32x4_t a = *reinterpret_cast<const u32x4_t*>(w + (((ob0 + j) * NKB + kb) * 64 + lane) * 16);
 #pragma unroll
-                for (int t = 0; t < T; ++t) acc[j][t] = mfma16(a, in[t][kb], acc[j][t]);
+                for (int t = 0; t < T; ++t) {
+                    acc[j][t] = mfma16(a, in[t][kb][0], acc[j][t]);
+                    if (SPLIT_IN) acc[j][t] = mfma16(a, in[t][kb][1], acc[j][t]);
+                }
             }
         }
 #pragma unroll
         for (int j = 0; j < OBG; j += 2) {
 #pragma unroll
             for (int t = 0; t < T; ++t) {
-                u32x4_t p;
-                p.x = relu_pack_bf16(acc[j][t].x, acc[j][t].y);
-                p.y = relu_pack_bf16(acc[j][t].z, acc[j][t].w);
-                p.z = relu_pack_bf16(acc[j + 1][t].x, acc[j + 1][t].y);
-                p.w = relu_pack_bf16(acc[j + 1][t].z, acc[j + 1][t].w);
-                out[t][(ob0 + j) / 2] = p;
+                uint32_t l0, l1, l2, l3;
+                u32x4_t hi, lo;
+                hi.x = relu_split_bf16(acc[j][t].x, acc[j][t].y, l0);
+                hi.y = relu_split_bf16(acc[j][t].z, acc[j][t].w, l1);
+                hi.z = relu_split_bf16(acc[j + 1][t].x, acc[j + 1][t].y, l2);
+                hi.w = relu_split_bf16(acc[j + 1][t].z, acc[j + 1][t].w, l3);
+                lo.x = l0; lo.y = l1; lo.z = l2; lo.w = l3;
+                out[t][(ob0 + j) / 2][0] = hi;
+                out[t][(ob0 + j) / 2][1] = lo;
             }
         }
     }
@@ -145,7 +157,7 @@ __device__ __forceinline__ void hidden_layer(const uint8_t* __restrict__ w, cons
 
 template <int T>
 __device__ __forceinline__ void head_layer(const uint8_t* __restrict__ w, const float* __restrict__ bias, int lane,
-                                           const u32x4_t (&in)[T][kL4_KB], f32x4_t (&out)[T][kL4_OB]) {
+                                           const u32x4_t (&in)[T][kL4_KB][2], f32x4_t (&out)[T][kL4_OB]) {
     const int g = lane >> 4;
 #pragma unroll
     for (int ob = 0; ob < kL4_OB; ++ob) {
@@ -159,22 +171,26 @@ __device__ __forceinline__ void head_layer(const uint8_t* __restrict__ w, const 
         for (int ob = 0; ob < kL4_OB; ++ob) {
             const u32x4_t a = *reinterpret_cast<const u32x4_t*>(w + ((ob * kL4_KB + kb) * 64 + lane) * 16);
 #pragma unroll
-            for (int t = 0; t < T; ++t) out[t][ob] = mfma16(a, in[t][kb], out[t][ob]);
+            for (int t = 0; t < T; ++t) {
+                out[t][ob] = mfma16(a, in[t][kb][0], out[t][ob]);
+                out[t][ob] = mfma16(a, in[t][kb][1], out[t][ob]);
+            }
         }
     }
 }
 
 // T: tiles per wave.  OBG: out-blocks accumulated concurrently (independent
-// MFMA chains in flight = T * OBG).
+// MFMA chains in flight = T * OBG).  in[t][0][0] is the layer-1 operand (exact
+// bytes, no lo part).
 template <int T, int OBG12, int OBG3>
-__device__ __forceinline__ void mlp_forward(const uint8_t* __restrict__ model, int lane, const u32x4_t (&in)[T][1],
-                                            f32x4_t (&out)[T][kL4_OB]) {
-    u32x4_t h1[T][kL2_KB];
-    hidden_layer<T, kL1_OB, kL1_KB, OBG12>(model + kW1Off, reinterpret_cast<const float*>(model + kB1Off), lane, in, h1);
-    u32x4_t h2[T][kL3_KB];
-    hidden_layer<T, kL2_OB, kL2_KB, OBG12>(model + kW2Off, reinterpret_cast<const float*>(model + kB2Off), lane, h1, h2);
-    u32x4_t h3[T][kL4_KB];
-    hidden_layer<T, kL3_OB, kL3_KB, OBG3>(model + kW3Off, reinterpret_cast<const float*>(model + kB3Off), lane, h2, h3);
+__device__ __forceinline__ void mlp_forward(const uint8_t* __restrict__ model, int lane,
+                                            const u32x4_t (&in)[T][1][2], f32x4_t (&out)[T][kL4_OB]) {
+    u32x4_t h1[T][kL2_KB][2];
+    hidden_layer<T, kL1_OB, kL1_KB, OBG12, false>(model + kW1Off, reinterpret_cast<const float*>(model + kB1Off), lane, in, h1);
+    u32x4_t h2[T][kL3_KB][2];
+    hidden_layer<T, kL2_OB, kL2_KB, OBG12, true>(model + kW2Off, reinterpret_cast<const float*>(model + kB2Off), lane, h1, h2);
+    u32x4_t h3[T][kL4_KB][2];
+    hidden_layer<T, kL3_OB, kL3_KB, OBG3, true>(model + kW3Off, reinterpret_cast<const float*>(model + kB3Off), lane, h2, h3);
     head_layer<T>(model + kW4Off, reinterpret_cast<const float*>(model + kB4Off), lane, h3, out);
 }
 

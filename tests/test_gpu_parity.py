@@ -11,12 +11,14 @@ pytestmark = pytest.mark.gpu
 
 torch = pytest.importorskip("torch")
 
-# Raw head outputs: GPU (bf16 products, fp32 accumulation) against the oracle
-# evaluating the same bf16-activation network in fp64.  The bound the task sets.
+# Raw head outputs: GPU (bf16 products of split hi+lo activations, fp32
+# accumulation) against the oracle's exact fp64 network.  2e-3 absolute is the
+# bound set for this path; the expected error is ~1e-4 (16-bit activations,
+# fp32 sums of up to 160 terms).
 PARAM_ATOL = 2e-3
-# Against the oracle's exact (unrounded-activation) network: bf16 activations carry
-# 2^-9 relative error through three layers; reported, loosely bounded.
-PARAM_ATOL_EXACT = 5e-2
+# Against the oracle rounding activations the same way only summation order differs,
+# except where a lo part rounds the other way (one unit of 2^-17 relative).
+PARAM_ATOL_SPLIT = 2e-4
 BITS_RTOL = 1e-3          # bits/pixel within 0.1 %
 CQ_ATOL = 2               # integer CDF counts: fp32 + table-interpolated Phi vs fp64 erfc
 
@@ -64,14 +66,14 @@ def test_params_match_oracle_config0(codec, orc):
     params, bits = codec.pcc_encode_probs(_dev(imgs))
     torch.cuda.synchronize()
     params = params.cpu().numpy().astype(np.float64)[0]
-    want = orc.params_rows(imgs[0], range(64), po.MODE_BF16ACT)
-    err = np.abs(params - want).max()
-    _log("max |params - oracle(bf16 activations)| = %.3g" % err)
-    assert err <= PARAM_ATOL
     exact = orc.params_rows(imgs[0], range(64), po.MODE_EXACT)
     err_exact = np.abs(params - exact).max()
-    _log("max |params - oracle(exact activations)| = %.3g" % err_exact)
-    assert err_exact <= PARAM_ATOL_EXACT
+    _log("max |params - oracle(exact)| = %.3g (mean %.3g)" % (err_exact, np.abs(params - exact).mean()))
+    assert err_exact <= PARAM_ATOL
+    want = orc.params_rows(imgs[0], range(64), po.MODE_SPLIT)
+    err = np.abs(params - want).max()
+    _log("max |params - oracle(split activations)| = %.3g" % err)
+    assert err <= PARAM_ATOL_SPLIT
 
 
 def test_bits_match_oracle_config0(codec, orc):
@@ -79,13 +81,13 @@ def test_bits_match_oracle_config0(codec, orc):
     _, bits = codec.pcc_encode_probs(_dev(imgs))
     torch.cuda.synchronize()
     bits = bits.cpu().numpy().astype(np.float64)
-    _, want = orc.encode(imgs, po.MODE_BF16ACT)
-    _, want_exact = orc.encode(imgs, po.MODE_EXACT)
-    _log("bpp gpu %.5f oracle(bf16act) %.5f oracle(exact) %.5f" % (bits.mean(), want.mean(), want_exact.mean()))
+    _, want = orc.encode(imgs, po.MODE_EXACT)
+    _log("bits/pixel gpu %.5f oracle %.5f" % (bits.mean(), want.mean()))
     assert abs(bits.sum() / want.sum() - 1) <= BITS_RTOL
-    assert abs(bits.sum() / want_exact.sum() - 1) <= BITS_RTOL
-    # per pixel: the same distributions up to a few counts in 65536
-    assert np.abs(bits - want).max() < 0.25
+    # per pixel: the same distributions up to a count or two in 65536, which for the rare
+    # frequencies (1..4) is a visible fraction of a bit
+    assert np.abs(bits - want).mean() < 0.01
+    assert np.abs(bits - want).max() < 3 * np.log2(3.0)
 
 
 def test_roundtrip_config0_and_stream_length(codec, orc):
@@ -101,7 +103,7 @@ def test_roundtrip_config0_and_stream_length(codec, orc):
     _log("stream %d bytes, ideal %.1f bytes, overhead %.0f bits" % (stream.numel(), ideal / 8, over))
     assert lo - 64 <= over <= hi + 64      # the fp32 log2 of the bit count carries a little rounding
     # oracle stream is about as long (different floating point, same model)
-    ostream, _ = orc.encode(imgs, po.MODE_BF16ACT)
+    ostream, _ = orc.encode(imgs, po.MODE_EXACT)
     assert abs(stream.numel() / len(ostream) - 1) <= BITS_RTOL
 
 
@@ -248,7 +250,7 @@ def _sample_check(codec, orc, imgs, n_pixels, n_rows, seed):
     pts += [(int(rng.integers(n)), int(rng.integers(h)), int(rng.integers(w))) for _ in range(n_pixels)]
     idx = torch.tensor(pts, device="cuda")
     got = params[idx[:, 0], idx[:, 1], idx[:, 2]].cpu().numpy().astype(np.float64)
-    want = np.stack([orc.params_at(imgs[i], r, c, po.MODE_BF16ACT) for i, r, c in pts])
+    want = np.stack([orc.params_at(imgs[i], r, c, po.MODE_EXACT) for i, r, c in pts])
     err = np.abs(got - want).max()
     _log("sampled params: max err %.3g over %d pixels" % (err, len(pts)))
     assert err <= PARAM_ATOL
@@ -257,7 +259,7 @@ def _sample_check(codec, orc, imgs, n_pixels, n_rows, seed):
     for _ in range(n_rows):
         i, r = int(rng.integers(n)), int(rng.integers(2, h))
         strip = imgs[i:i + 1, r - 2:r + 1]          # rows r-2..r: the last row sees its true context
-        _, b = orc.encode(strip, po.MODE_BF16ACT)
+        _, b = orc.encode(strip, po.MODE_EXACT)
         tot_o += b[0, 2].sum()
         tot_g += float(bits[i, r].double().sum().item())
     _log("sampled rows: bits gpu %.1f oracle %.1f" % (tot_g, tot_o))
