@@ -111,6 +111,19 @@ int pcc_cdf_tables(pcc_ctx *ctx, const float *d_params, const uint8_t *d_rg, siz
  * coder: d_out [n][H][W][3] uint32, start | (freq - 1) << 16.  Asynchronous. */
 int pcc_copy_intervals(pcc_ctx *ctx, uint32_t *d_out, size_t count, void *hip_stream);
 
+/* Per-kernel timing.  With profiling enabled, pcc_encode and pcc_decode bracket
+ * each kernel they launch with HIP events on the caller's stream; after the
+ * call, pcc_last_timings copies the durations in milliseconds of the last such
+ * call into h_ms[PCC_N_TIMINGS] (kernels that did not run: 0). */
+#define PCC_T_ENCODE_PIXELS 0 /* gather + network + mixture -> (start,freq), all pixels */
+#define PCC_T_ENCODE_RANS 1   /* row-wise rANS */
+#define PCC_T_ENCODE_SCAN 2   /* offsets */
+#define PCC_T_ENCODE_COMPACT 3
+#define PCC_T_DECODE 4        /* wavefront decode kernel */
+#define PCC_N_TIMINGS 5
+int pcc_set_profiling(pcc_ctx *ctx, int enabled);
+int pcc_last_timings(pcc_ctx *ctx, float *h_ms);
+
 const char *pcc_strerror(int code);
 
 #ifdef __cplusplus

@@ -21,8 +21,9 @@ HEAD_OUTPUTS = 60
 
 EXPORTS = (
     "pcc_create", "pcc_destroy", "pcc_stream_bound", "pcc_wavefront_steps", "pcc_encode_probs", "pcc_encode",
-    "pcc_decode", "pcc_cdf_tables", "pcc_copy_intervals", "pcc_strerror",
+    "pcc_decode", "pcc_cdf_tables", "pcc_copy_intervals", "pcc_set_profiling", "pcc_last_timings", "pcc_strerror",
 )
+TIMING_NAMES = ("encode_pixels", "encode_rans", "encode_scan", "encode_compact", "decode")
 
 _lib = None
 
@@ -55,6 +56,10 @@ def load():
     L.pcc_cdf_tables.restype = i32
     L.pcc_copy_intervals.argtypes = [vp, vp, sz, vp]
     L.pcc_copy_intervals.restype = i32
+    L.pcc_set_profiling.argtypes = [vp, i32]
+    L.pcc_set_profiling.restype = i32
+    L.pcc_last_timings.argtypes = [vp, vp]
+    L.pcc_last_timings.restype = i32
     L.pcc_strerror.argtypes = [i32]
     L.pcc_strerror.restype = C.c_char_p
     _lib = L
@@ -154,6 +159,19 @@ class Codec:
         if rc != PCC_OK:
             raise PccError(rc, "pcc_cdf_tables")
         return cq
+
+    def pcc_set_profiling(self, enabled: bool) -> None:
+        rc = load().pcc_set_profiling(self._h, 1 if enabled else 0)
+        if rc != PCC_OK:
+            raise PccError(rc, "pcc_set_profiling")
+
+    def pcc_last_timings(self) -> dict:
+        """Milliseconds per kernel of the last pcc_encode / pcc_decode (profiling must be on)."""
+        arr = (C.c_float * len(TIMING_NAMES))()
+        rc = load().pcc_last_timings(self._h, arr)
+        if rc != PCC_OK:
+            raise PccError(rc, "pcc_last_timings")
+        return dict(zip(TIMING_NAMES, (float(v) for v in arr)))
 
     def pcc_copy_intervals(self, n: int, h: int, w: int, device=None) -> torch.Tensor:
         """(start | (freq-1) << 16) of every sub-pixel of the last pcc_encode: int32 tensor [n, H, W, 3]."""

@@ -520,6 +520,11 @@ struct pcc_ctx {
     size_t sf_count = 0;
     int num_cus = 0;
     int encode_variant = kDefaultEncodeVariant;
+    // optional per-kernel timing
+    bool profiling = false;
+    hipEvent_t ev[2 * PCC_N_TIMINGS] = {};
+    bool ev_used[PCC_N_TIMINGS] = {};
+    float last_ms[PCC_N_TIMINGS] = {};
 };
 
 namespace {
@@ -557,6 +562,25 @@ int ensure_workspace(pcc_ctx* ctx, size_t bytes) {
 }
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+inline void prof_reset(pcc_ctx* ctx) {
+    for (int i = 0; i < PCC_N_TIMINGS; ++i) { ctx->ev_used[i] = false; ctx->last_ms[i] = 0.0f; }
+}
+inline void prof_begin(pcc_ctx* ctx, int which, hipStream_t st) {
+    if (ctx->profiling) (void)hipEventRecord(ctx->ev[2 * which], st);
+}
+inline void prof_end(pcc_ctx* ctx, int which, hipStream_t st) {
+    if (ctx->profiling) { (void)hipEventRecord(ctx->ev[2 * which + 1], st); ctx->ev_used[which] = true; }
+}
+// after the stream has been synchronised
+inline void prof_collect(pcc_ctx* ctx) {
+    if (!ctx->profiling) return;
+    for (int i = 0; i < PCC_N_TIMINGS; ++i)
+        if (ctx->ev_used[i] && hipEventElapsedTime(&ctx->last_ms[i], ctx->ev[2 * i], ctx->ev[2 * i + 1]) != hipSuccess) {
+            (void)hipGetLastError();
+            ctx->last_ms[i] = 0.0f;
+        }
+}
 
 bool dims_ok(int n, int H, int W) {
     if (n < 1 || H < 1 || W < 1) return false;
@@ -698,6 +722,7 @@ void pcc_destroy(pcc_ctx* ctx) {
     if (ctx->d_ws) (void)hipFree(ctx->d_ws);
     if (ctx->d_status) (void)hipFree(ctx->d_status);
     if (ctx->h_status) (void)hipHostFree(ctx->h_status);
+    for (hipEvent_t e : ctx->ev) if (e) (void)hipEventDestroy(e);
     delete ctx;
 }
 
@@ -758,16 +783,26 @@ int pcc_encode(pcc_ctx* ctx, const uint8_t* d_img, int n, int H, int W, uint8_t*
     ctx->sf_count = (size_t)P * 3;
 
     if (hipMemsetAsync(ctx->d_status, 0, kStWords * sizeof(int) + sizeof(uint64_t), st) != hipSuccess) return PCC_E_HIP;
+    prof_reset(ctx);
+    prof_begin(ctx, PCC_T_ENCODE_PIXELS, st);
     rc = launch_encode(ctx, d_img, n, H, W, d_sf, nullptr, nullptr, st);
     if (rc != PCC_OK) return rc;
+    prof_end(ctx, PCC_T_ENCODE_PIXELS, st);
+    prof_begin(ctx, PCC_T_ENCODE_RANS, st);
     hipLaunchKernelGGL(rans_rows_kernel, dim3((rows + 63) / 64), dim3(64), 0, st, d_sf, W, rows, d_slabs, d_rw);
+    prof_end(ctx, PCC_T_ENCODE_RANS, st);
+    prof_begin(ctx, PCC_T_ENCODE_SCAN, st);
     hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), 0, st, d_rw, rows, n, H, W, d_stream, ctx->d_total);
+    prof_end(ctx, PCC_T_ENCODE_SCAN, st);
+    prof_begin(ctx, PCC_T_ENCODE_COMPACT, st);
     hipLaunchKernelGGL(compact_kernel, dim3(rows), dim3(64), 0, st, d_slabs, d_rw, W, rows, d_stream,
                        (uint64_t)cap_bytes, ctx->d_status);
+    prof_end(ctx, PCC_T_ENCODE_COMPACT, st);
     if (hipGetLastError() != hipSuccess) return PCC_E_HIP;
     if (hipMemcpyAsync(ctx->h_status, ctx->d_status, kStWords * sizeof(int) + sizeof(uint64_t), hipMemcpyDeviceToHost,
                        st) != hipSuccess) return PCC_E_HIP;
     if (hipStreamSynchronize(st) != hipSuccess) { (void)hipGetLastError(); return PCC_E_HIP; }
+    prof_collect(ctx);
     if (ctx->h_status[kStErr] != 0) return ctx->h_status[kStErr];
     uint64_t total;
     memcpy(&total, ctx->h_status + kStWords, sizeof(total));
@@ -795,12 +830,16 @@ int pcc_decode(pcc_ctx* ctx, const uint8_t* d_stream, size_t nbytes, int n, int 
     if (hipMemsetAsync(ctx->d_status, 0, kStWords * sizeof(int) + sizeof(uint64_t), st) != hipSuccess) return PCC_E_HIP;
     if (hipMemsetAsync(d_mail, 0, mail_bytes, st) != hipSuccess) return PCC_E_HIP;
     const uint32_t spin_limit = 1u << 22;
+    prof_reset(ctx);
+    prof_begin(ctx, PCC_T_DECODE, st);
     hipLaunchKernelGGL(decode_kernel, dim3((uint32_t)(n * nbands)), dim3(64), kModelBytes + 1024, st, ctx->d_model,
                        d_stream, (uint64_t)nbytes, n, H, W, nbands, d_img_out, d_mail, ctx->d_status, spin_limit);
+    prof_end(ctx, PCC_T_DECODE, st);
     if (hipGetLastError() != hipSuccess) return PCC_E_HIP;
     if (hipMemcpyAsync(ctx->h_status, ctx->d_status, kStWords * sizeof(int), hipMemcpyDeviceToHost, st) != hipSuccess)
         return PCC_E_HIP;
     if (hipStreamSynchronize(st) != hipSuccess) { (void)hipGetLastError(); return PCC_E_HIP; }
+    prof_collect(ctx);
     return ctx->h_status[kStErr];
 }
 
@@ -813,6 +852,25 @@ int pcc_cdf_tables(pcc_ctx* ctx, const float* d_params, const uint8_t* d_rg, siz
     hipLaunchKernelGGL(cdf_tables_kernel, dim3((uint32_t)((threads + 255) / 256)), dim3(256), (kLutEntries + 1) * 8,
                        (hipStream_t)hip_stream, ctx->d_model, d_params, d_rg, count, d_cq);
     return hipGetLastError() == hipSuccess ? PCC_OK : PCC_E_HIP;
+}
+
+int pcc_set_profiling(pcc_ctx* ctx, int enabled) {
+    if (!ctx) return PCC_E_ARG;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return PCC_E_HIP;
+    if (enabled && !ctx->ev[0]) {
+        for (hipEvent_t& e : ctx->ev)
+            if (hipEventCreate(&e) != hipSuccess) { (void)hipGetLastError(); return PCC_E_HIP; }
+    }
+    ctx->profiling = enabled != 0;
+    prof_reset(ctx);
+    return PCC_OK;
+}
+
+int pcc_last_timings(pcc_ctx* ctx, float* h_ms) {
+    if (!ctx || !h_ms) return PCC_E_ARG;
+    for (int i = 0; i < PCC_N_TIMINGS; ++i) h_ms[i] = ctx->last_ms[i];
+    return PCC_OK;
 }
 
 int pcc_copy_intervals(pcc_ctx* ctx, uint32_t* d_out, size_t count, void* hip_stream) {
