@@ -7,8 +7,8 @@
 //                      first into a per-row slab, written backwards
 //   scan_kernel        exclusive prefix sum of row payload sizes, header, offsets
 //   compact_kernel     slabs -> contiguous stream
-//   decode_kernel      persistent wavefront decoder: one wave per band of 16
-//                      rows, step t handles pixel (r, t - 2r) of each row
+//   decode_kernel      persistent wavefront decoder: one workgroup (4 waves) per
+//                      band of 16 rows, step t handles pixel (r, t - 2r) of each row
 //   cdf_tables_kernel  test hook: full integer CDF tables from given parameters
 #include <hip/hip_runtime.h>
 
@@ -283,8 +283,30 @@ compact_kernel(const uint32_t* __restrict__ slabs, const uint32_t* __restrict__ 
 
 // ---------------------------------------------------------------------------
 // wavefront decode
+//
+// One workgroup of 4 waves owns a band of 16 image rows; step t decodes pixel
+// (r, t - 2r) of each row.  Per step:
+//   network   the 16 pixels form one MFMA tile; each wave computes a quarter
+//             of every layer's out-blocks and the layers meet in LDS
+//   search    16 lanes per pixel find the symbol with two 16-way rounds of
+//             Cq evaluations per channel (R, then G given R, then B given R,G)
+//   publish   the pixel goes to the LDS ring (next steps' neighbourhoods), to
+//             the output image and, for the band's last two rows, to a mailbox
+//             in global memory that the band below polls
 // ---------------------------------------------------------------------------
-struct RowReader {          // lives in the lanes of group 0
+constexpr int kDecThreads = 256;
+constexpr int kActBytes = 5 * 2 * 64 * 16;                     // one layer's activations: [k-block][hi,lo][lane][16 B]
+constexpr int kAct0Off = kModelBytes;
+constexpr int kAct1Off = kAct0Off + kActBytes;
+constexpr int kHeadOff = kAct1Off;                              // head outputs [16][64] fp32 reuse the second buffer
+constexpr int kCpOff = kHeadOff + 16 * 64 * 4;                  // mixtures [16][3][5] x (pi, mu, 1/sigma)
+constexpr int kRingOff = kAct1Off + kActBytes;                  // ring [18][8] uint32
+constexpr int kDecMiscOff = kRingOff + 18 * 8 * 4;              // ticket, abort flag
+constexpr int kDecLdsBytes = kDecMiscOff + 64;
+static_assert(kCpOff + 16 * 3 * 5 * 3 * 4 <= kAct1Off + kActBytes, "head outputs and mixtures must fit the second buffer");
+static_assert(kDecLdsBytes <= 160 * 1024, "decode LDS budget");
+
+struct RowReader {          // lives in lane 0 of each pixel's 16-lane group
     uint64_t x;
     const uint32_t* words;  // payload after the 8-byte state
     uint32_t nwords, pos;
@@ -303,34 +325,108 @@ __device__ __forceinline__ void reader_advance(RowReader& rd, uint32_t slot, uin
     }
 }
 
-__global__ void __launch_bounds__(64)
+// One hidden layer, this wave's out-blocks ob = wave, wave+4, wave+8 (< NOB).
+// Same arithmetic per output element as hidden_layer<> in pcc_device.h: bias,
+// then k-blocks in order, each hi then lo; ReLU; split into hi + lo.
+template <int NOB, int NKB, bool SPLIT_IN>
+__device__ __forceinline__ void dec_hidden_layer(const uint8_t* __restrict__ w, const float* __restrict__ bias, int lane,
+                                                 int wave, const u32x4_t (&in)[NKB][2], uint8_t* __restrict__ act_out) {
+    const int g = lane >> 4;
+    constexpr int kSlots = (NOB + 3) / 4;
+    f32x4_t acc[kSlots];
+#pragma unroll
+    for (int s = 0; s < kSlots; ++s) {
+        const int ob = min(wave + 4 * s, NOB - 1);
+        acc[s] = *reinterpret_cast<const f32x4_t*>(bias + 16 * ob + 4 * g);
+    }
+#pragma unroll
+    for (int kb = 0; kb < NKB; ++kb) {
+#pragma unroll
+        for (int s = 0; s < kSlots; ++s) {
+            const int ob = min(wave + 4 * s, NOB - 1);   // a duplicate of the last block where the wave has none: discarded below
+            const u32x4_t a = *reinterpret_cast<const u32x4_t*>(w + ((ob * NKB + kb) * 64 + lane) * 16);
+            acc[s] = mfma16(a, in[kb][0], acc[s]);
+            if (SPLIT_IN) acc[s] = mfma16(a, in[kb][1], acc[s]);
+        }
+    }
+#pragma unroll
+    for (int s = 0; s < kSlots; ++s) {
+        const int ob = wave + 4 * s;
+        if (ob < NOB) {
+            uint32_t l0, l1;
+            const uint32_t h0 = relu_split_bf16(acc[s].x, acc[s].y, l0);
+            const uint32_t h1 = relu_split_bf16(acc[s].z, acc[s].w, l1);
+            // out-block ob is half (ob & 1) of k-block ob/2 of the next layer's operand
+            uint8_t* dst = act_out + (((ob >> 1) * 2) * 64 + lane) * 16 + 8 * (ob & 1);
+            *reinterpret_cast<uint2*>(dst) = make_uint2(h0, h1);
+            *reinterpret_cast<uint2*>(dst + 64 * 16) = make_uint2(l0, l1);
+        }
+    }
+}
+
+template <int NKB>
+__device__ __forceinline__ void dec_load_act(const uint8_t* __restrict__ act, int lane, u32x4_t (&in)[NKB][2]) {
+#pragma unroll
+    for (int kb = 0; kb < NKB; ++kb) {
+        in[kb][0] = *reinterpret_cast<const u32x4_t*>(act + ((kb * 2 + 0) * 64 + lane) * 16);
+        in[kb][1] = *reinterpret_cast<const u32x4_t*>(act + ((kb * 2 + 1) * 64 + lane) * 16);
+    }
+}
+
+// Symbol search by the 16 lanes (j = 0..15) of one pixel: two rounds of 16
+// evaluations.  All lanes of the group return the same x, start, freq.
+__device__ __forceinline__ int group_search(const ChanParams& cp, uint32_t slot, const float2* __restrict__ lut, int lane,
+                                            uint32_t& start, uint32_t& freq) {
+    const int j = lane & 15, base = lane & 48, shift = lane & 48;
+    // round 1: Cq(16 j); lanes 0..b satisfy Cq <= slot (Cq is increasing and Cq(0) = 0)
+    const uint32_t c1 = j == 0 ? 0u : cq_eval(cp, 16 * j, lut);
+    const int cnt1 = __popcll((__ballot(c1 <= slot) >> shift) & 0xFFFFull);
+    const int b = cnt1 - 1;
+    const uint32_t lo1 = __shfl(c1, base + b);
+    const uint32_t hi1 = b < 15 ? (uint32_t)__shfl(c1, base + min(b + 1, 15)) : 65536u;
+    // round 2: Cq(16 b + j)
+    const uint32_t c2 = j == 0 ? lo1 : cq_eval(cp, 16 * b + j, lut);
+    const int cnt2 = __popcll((__ballot(c2 <= slot) >> shift) & 0xFFFFull);
+    start = __shfl(c2, base + cnt2 - 1);
+    const uint32_t nxt = __shfl(c2, base + min(cnt2, 15));
+    freq = (cnt2 < 16 ? nxt : hi1) - start;
+    return 16 * b + cnt2 - 1;
+}
+
+__global__ void __launch_bounds__(kDecThreads)
 decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ stream, uint64_t nbytes, int n, int H,
               int W, int nbands, uint8_t* __restrict__ img_out, uint32_t* mailbox, int* status, uint32_t spin_limit) {
     extern __shared__ __align__(16) uint8_t lds[];
-    uint32_t (*ring)[8] = reinterpret_cast<uint32_t (*)[8]>(lds + kModelBytes);   // [18][8]
-    int* lds_ticket = reinterpret_cast<int*>(lds + kModelBytes + 18 * 8 * 4);
-    const int lane = threadIdx.x;
+    uint8_t* act0 = lds + kAct0Off;
+    uint8_t* act1 = lds + kAct1Off;
+    float* headout = reinterpret_cast<float*>(lds + kHeadOff);      // [16][64], canonical head index
+    float* cpbuf = reinterpret_cast<float*>(lds + kCpOff);          // [16][3][5][3]
+    uint32_t (*ring)[8] = reinterpret_cast<uint32_t (*)[8]>(lds + kRingOff);   // [18][8]
+    int* misc = reinterpret_cast<int*>(lds + kDecMiscOff);          // [0] ticket, [1] abort
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    // network role: pixel nl of the tile, k-slot group g
     const int g = lane >> 4, nl = lane & 15;
+    // search role: pixel q of the band, lane j of its group
+    const int q = 4 * wave + (lane >> 4), j = lane & 15;
 
     // Bands take tickets in start order: a band only ever waits for the band
     // above it, which holds a smaller ticket and is therefore already running.
-    if (lane == 0) *lds_ticket = atomicAdd(&status[kStTicket], 1);
+    if (tid == 0) { misc[0] = atomicAdd(&status[kStTicket], 1); misc[1] = 0; }
     copy_model_to_lds(lds, model);
-    for (int i = lane; i < 18 * 8; i += 64) (&ring[0][0])[i] = 0u;
+    for (int i = tid; i < 18 * 8; i += kDecThreads) (&ring[0][0])[i] = 0u;
     __syncthreads();
-    const int ticket = *lds_ticket;
+    const int ticket = misc[0];
     const int im = ticket / nbands, band = ticket - im * nbands;
     if (im >= n) return;
     const float2* lut = reinterpret_cast<const float2*>(lds + kLutOff);
 
     const int r0 = band * kBandRows;
-    const int row = r0 + nl;
-    const bool row_ok = row < H;
     const uint64_t rows_total = (uint64_t)n * H;
     const uint64_t table = (uint64_t)kStreamHeader + 8ull * (rows_total + 1);
     const uint64_t payload_bytes = nbytes - table;   // host guarantees nbytes >= table
 
-    if (ticket == 0 && lane == 0) {
+    if (ticket == 0 && tid == 0) {
         const uint32_t* hdr = reinterpret_cast<const uint32_t*>(stream);
         const uint64_t last = reinterpret_cast<const uint64_t*>(stream + kStreamHeader)[rows_total];
         if (hdr[0] != kStreamMagic || hdr[1] != 1u || hdr[2] != (uint32_t)n || hdr[3] != (uint32_t)H ||
@@ -338,11 +434,14 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
             set_error(status, PCC_E_STREAM);
     }
 
+    // search role: row of this lane's pixel, its stream reader (lane j == 0 only)
+    const int qrow = r0 + q;
+    const bool qrow_ok = qrow < H;
     RowReader rd;
     rd.x = kRansL; rd.words = nullptr; rd.nwords = 0; rd.pos = 0; rd.w0 = 0; rd.w1 = 0; rd.bad = false;
-    if (g == 0 && row_ok) {
+    if (j == 0 && qrow_ok) {
         const uint64_t* offs = reinterpret_cast<const uint64_t*>(stream + kStreamHeader);
-        const uint64_t rowg = (uint64_t)im * H + row;
+        const uint64_t rowg = (uint64_t)im * H + qrow;
         const uint64_t a = offs[rowg], b = offs[rowg + 1];
         if (a > b || b > payload_bytes || (b - a) < 8 || ((b - a) & 3) != 0 || (a & 3) != 0 ||
             (b - a) > 4ull * slab_words(W)) {
@@ -364,44 +463,47 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
 
     const int last_row = min(r0 + kBandRows - 1, H - 1);
     const int t_begin = 2 * r0, t_end = 2 * last_row + W - 1;
-    bool aborted = false;
+    const bool fetcher = band > 0 && tid < 2;     // thread 0: row r0-2 -> ring row 0; thread 1: row r0-1 -> ring row 1
+    const uint32_t* mail_row = mail_in + (size_t)(tid & 1) * W;
+    uint32_t pf = 0;                              // mailbox word for the next column, requested a step early
 
-    for (int t = t_begin - 1; t <= t_end && !aborted; ++t) {
-        // Pixels of the two rows above the band, column cc = (t - 2 r0) + 1,
-        // published by the band above (t_begin - 1 is a prologue that brings in column 0).
-        const int cc = t - t_begin + 1;
-        if (band > 0 && lane < 2 && cc < W) {
-            const uint32_t* src = mail_in + (size_t)lane * W + cc;
-            uint32_t v = 0, spins = 0;
-            bool fail = false;
-            for (;;) {
-                v = __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                if (v & kMailTag) break;
-                ++spins;
-                if (spins > spin_limit) { set_error(status, PCC_E_INTERNAL); fail = true; break; }
-                if ((spins & 63u) == 0u &&
-                    __hip_atomic_load(&status[kStAbort], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
-                    fail = true;
-                    break;
-                }
-                __builtin_amdgcn_s_sleep(1);
-            }
-            if (fail) {
-                __hip_atomic_store(&status[kStAbort], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                aborted = true;
-            }
-            ring[lane][cc & 7] = v & 0xFFFFFFu;
+    // Bring columns 0 and 1 of the two rows above the band into the ring, then keep
+    // one column ahead: the step at t needs column (t - t_begin) + 1.
+    auto fetch_column = [&](int cc, uint32_t have) -> bool {   // returns false on abort
+        uint32_t v = have, spins = 0;
+        while (!(v & kMailTag)) {
+            v = __hip_atomic_load(mail_row + cc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (v & kMailTag) break;
+            ++spins;
+            if (spins > spin_limit) { set_error(status, PCC_E_INTERNAL); return false; }
+            if ((spins & 63u) == 0u &&
+                __hip_atomic_load(&status[kStAbort], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)
+                return false;
+            __builtin_amdgcn_s_sleep(1);
         }
-        aborted = __ballot(aborted) != 0ull;
-        __syncthreads();
-        if (aborted || t < t_begin) continue;
+        ring[tid & 1][cc & 7] = v & 0xFFFFFFu;
+        return true;
+    };
+    if (fetcher) {
+        bool ok = fetch_column(0, 0u);
+        if (ok && W > 1) ok = fetch_column(1, 0u);
+        if (ok && W > 2) pf = __hip_atomic_load(mail_row + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (!ok) {
+            __hip_atomic_store(&status[kStAbort], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            misc[1] = 1;
+        }
+    }
+    __syncthreads();
 
-        const int c = t - 2 * row;
-        const bool active = row_ok && c >= 0 && c < W;
+    for (int t = t_begin; t <= t_end; ++t) {
+        if (misc[1] != 0) break;                  // uniform: written before the last barrier
+        const uint8_t* mdl = lds + opaque_zero();
 
-        // gather C_ij from the ring (zero outside the image)
-        u32x4_t in[1][1][2];
+        // ---- gather C_ij from the ring (zero outside the image); every wave builds the full tile
+        u32x4_t in1[1][2];
         {
+            const int row = r0 + nl;
+            const int c = t - 2 * row;
             uint32_t slots[8];
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
@@ -415,56 +517,132 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
                 const uint32_t px = ring[nl + 2 + dr][colx & 7];
                 slots[i] = ok ? byte_to_bf16((px >> (8 * ch)) & 0xFFu) : 0u;
             }
-            in[0][0][0].x = slots[0] | (slots[1] << 16);
-            in[0][0][0].y = slots[2] | (slots[3] << 16);
-            in[0][0][0].z = slots[4] | (slots[5] << 16);
-            in[0][0][0].w = slots[6] | (slots[7] << 16);
-            in[0][0][1] = in[0][0][0];   // unused (layer-1 inputs are exact)
+            in1[0][0].x = slots[0] | (slots[1] << 16);
+            in1[0][0].y = slots[2] | (slots[3] << 16);
+            in1[0][0].z = slots[4] | (slots[5] << 16);
+            in1[0][0].w = slots[6] | (slots[7] << 16);
+            in1[0][1] = in1[0][0];   // unused (layer-1 inputs are exact)
         }
 
-        f32x4_t out[1][kL4_OB];
-        mlp_forward<1, 10, 8>(lds + opaque_zero(), lane, in, out);
+        // ---- network, layers meeting in LDS
+        dec_hidden_layer<kL1_OB, kL1_KB, false>(mdl + kW1Off, reinterpret_cast<const float*>(mdl + kB1Off), lane, wave,
+                                                in1, act0);
+        __syncthreads();
+        {
+            u32x4_t in[kL2_KB][2];
+            dec_load_act<kL2_KB>(act0, lane, in);
+            dec_hidden_layer<kL2_OB, kL2_KB, true>(mdl + kW2Off, reinterpret_cast<const float*>(mdl + kB2Off), lane,
+                                                   wave, in, act1);
+        }
+        __syncthreads();
+        {
+            u32x4_t in[kL3_KB][2];
+            dec_load_act<kL3_KB>(act1, lane, in);
+            dec_hidden_layer<kL3_OB, kL3_KB, true>(mdl + kW3Off, reinterpret_cast<const float*>(mdl + kB3Off), lane,
+                                                   wave, in, act0);
+        }
+        __syncthreads();
+        {
+            u32x4_t in[kL4_KB][2];
+            dec_load_act<kL4_KB>(act0, lane, in);
+            const int ob = wave;
+            f32x4_t acc = *reinterpret_cast<const f32x4_t*>(reinterpret_cast<const float*>(mdl + kB4Off) + 16 * ob + 4 * g);
+#pragma unroll
+            for (int kb = 0; kb < kL4_KB; ++kb) {
+                const u32x4_t a = *reinterpret_cast<const u32x4_t*>(mdl + kW4Off + ((ob * kL4_KB + kb) * 64 + lane) * 16);
+                acc = mfma16(a, in[kb][0], acc);
+                acc = mfma16(a, in[kb][1], acc);
+            }
+            const float vv[4] = {acc.x, acc.y, acc.z, acc.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int idx = head_index(g, 4 * ob + i);
+                if (idx >= 0) headout[nl * 64 + idx] = vv[i];
+            }
+        }
+        __syncthreads();
 
-        LaneHead h;
-        lane_head_setup(out[0], lane, h);
+        // ---- mixtures: lane j < 15 of pixel q prepares component j % 5 of channel j / 5
+        if (j < 15) {
+            const int ch = j / 5, k = j - 5 * ch;
+            float raw[15];
+#pragma unroll
+            for (int s = 0; s < 15; ++s) raw[s] = headout[q * 64 + 15 * ch + s];
+            ChanParams all;
+            channel_setup(raw, all);
+            float pk = all.pi[0], mk = all.mu[0], sk = all.isg[0];
+#pragma unroll
+            for (int kk = 1; kk < 5; ++kk) if (k == kk) { pk = all.pi[kk]; mk = all.mu[kk]; sk = all.isg[kk]; }
+            float* dst = cpbuf + ((q * 3 + ch) * 5 + k) * 3;
+            dst[0] = pk; dst[1] = mk; dst[2] = sk;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-        uint32_t start = 0, freq = 1;
-        int sym = 0;
+        const int c = t - 2 * qrow;
+        const bool active = qrow_ok && c >= 0 && c < W;
+        const int leader = lane & 48;
+        auto load_cp = [&](int ch, ChanParams& cp) {
+#pragma unroll
+            for (int k = 0; k < 5; ++k) {
+                const float* src = cpbuf + ((q * 3 + ch) * 5 + k) * 3;
+                cp.pi[k] = src[0]; cp.mu[k] = src[1]; cp.isg[k] = src[2];
+            }
+        };
+        ChanParams cp;
+        uint32_t start, freq;
         // R
-        uint32_t slot = __shfl((uint32_t)rd.x & 0xFFFFu, nl);
-        if (g == 0) sym = cq_search(h.cp, slot, lut, start, freq);
-        if (g == 0 && active) reader_advance(rd, slot, start, freq);
-        const int sr = __shfl(sym, nl);
+        load_cp(0, cp);
+        uint32_t slot = __shfl((uint32_t)rd.x & 0xFFFFu, leader);
+        const int sr = group_search(cp, slot, lut, lane, start, freq);
+        if (j == 0 && active) reader_advance(rd, slot, start, freq);
         const float rhat = (float)sr * (1.0f / 256.0f);
         // G given R
-        if (g == 1) couple_green(h.cp, h.c1, rhat);
-        slot = __shfl((uint32_t)rd.x & 0xFFFFu, nl);
-        if (g == 1) sym = cq_search(h.cp, slot, lut, start, freq);
-        const int sg = __shfl(sym, nl + 16);
+        load_cp(1, cp);
         {
-            const uint32_t st = __shfl(start, nl + 16), fq = __shfl(freq, nl + 16);
-            if (g == 0 && active) reader_advance(rd, slot, st, fq);
+            float alpha[5];
+#pragma unroll
+            for (int k = 0; k < 5; ++k) alpha[k] = headout[q * 64 + 45 + k];
+            couple_green(cp, alpha, rhat);
         }
+        slot = __shfl((uint32_t)rd.x & 0xFFFFu, leader);
+        const int sg = group_search(cp, slot, lut, lane, start, freq);
+        if (j == 0 && active) reader_advance(rd, slot, start, freq);
         const float ghat = (float)sg * (1.0f / 256.0f);
         // B given R, G
-        if (g == 2) couple_blue(h.cp, h.c1, h.c2, rhat, ghat);
-        slot = __shfl((uint32_t)rd.x & 0xFFFFu, nl);
-        if (g == 2) sym = cq_search(h.cp, slot, lut, start, freq);
-        const int sb = __shfl(sym, nl + 32);
+        load_cp(2, cp);
         {
-            const uint32_t st = __shfl(start, nl + 32), fq = __shfl(freq, nl + 32);
-            if (g == 0 && active) reader_advance(rd, slot, st, fq);
+            float beta[5], gamma[5];
+#pragma unroll
+            for (int k = 0; k < 5; ++k) { beta[k] = headout[q * 64 + 50 + k]; gamma[k] = headout[q * 64 + 55 + k]; }
+            couple_blue(cp, beta, gamma, rhat, ghat);
         }
+        slot = __shfl((uint32_t)rd.x & 0xFFFFu, leader);
+        const int sb = group_search(cp, slot, lut, lane, start, freq);
+        if (j == 0 && active) reader_advance(rd, slot, start, freq);
 
-        if (g == 0 && active) {
+        // ---- publish
+        if (j == 0 && active) {
             const uint32_t px = (uint32_t)sr | ((uint32_t)sg << 8) | ((uint32_t)sb << 16);
-            ring[nl + 2][c & 7] = px;
-            uint8_t* o = out_img + ((size_t)row * W + c) * 3;
+            ring[q + 2][c & 7] = px;
+            uint8_t* o = out_img + ((size_t)qrow * W + c) * 3;
             o[0] = (uint8_t)sr; o[1] = (uint8_t)sg; o[2] = (uint8_t)sb;
-            if (nl >= kBandRows - 2)
-                __hip_atomic_store(mail_out + (size_t)(nl - (kBandRows - 2)) * W + c, px | kMailTag, __ATOMIC_RELAXED,
+            if (q >= kBandRows - 2)
+                __hip_atomic_store(mail_out + (size_t)(q - (kBandRows - 2)) * W + c, px | kMailTag, __ATOMIC_RELAXED,
                                    __HIP_MEMORY_SCOPE_AGENT);
             if (c == W - 1 && (rd.bad || rd.x != kRansL || rd.pos != rd.nwords)) set_error(status, PCC_E_STREAM);
+        }
+        // ---- rows above the band: column needed by the next step, and request the one after
+        if (fetcher) {
+            const int cc = t - t_begin + 2;
+            if (cc < W && t < t_end) {
+                if (!fetch_column(cc, pf)) {
+                    __hip_atomic_store(&status[kStAbort], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    misc[1] = 1;
+                }
+                pf = (cc + 1 < W) ? __hip_atomic_load(mail_row + cc + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
+            }
         }
         __syncthreads();
     }
@@ -708,7 +886,7 @@ int pcc_create(pcc_ctx** out, const void* h_blob, size_t blob_bytes, int hip_dev
         if (v >= 0 && v < 3) ctx->encode_variant = v;
     }
     ok = ok && hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_kernel),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, kModelBytes + 1024) == hipSuccess;
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, kDecLdsBytes) == hipSuccess;
     if (!ok) { (void)hipGetLastError(); pcc_destroy(ctx); return PCC_E_HIP; }
     ctx->d_total = reinterpret_cast<uint64_t*>(ctx->d_status + kStWords);
     *out = ctx;
@@ -832,7 +1010,7 @@ int pcc_decode(pcc_ctx* ctx, const uint8_t* d_stream, size_t nbytes, int n, int 
     const uint32_t spin_limit = 1u << 22;
     prof_reset(ctx);
     prof_begin(ctx, PCC_T_DECODE, st);
-    hipLaunchKernelGGL(decode_kernel, dim3((uint32_t)(n * nbands)), dim3(64), kModelBytes + 1024, st, ctx->d_model,
+    hipLaunchKernelGGL(decode_kernel, dim3((uint32_t)(n * nbands)), dim3(kDecThreads), kDecLdsBytes, st, ctx->d_model,
                        d_stream, (uint64_t)nbytes, n, H, W, nbands, d_img_out, d_mail, ctx->d_status, spin_limit);
     prof_end(ctx, PCC_T_DECODE, st);
     if (hipGetLastError() != hipSuccess) return PCC_E_HIP;
