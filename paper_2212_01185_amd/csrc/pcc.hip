@@ -287,70 +287,144 @@ compact_kernel(const uint32_t* __restrict__ slabs, const uint32_t* __restrict__ 
 // One workgroup of 4 waves owns a band of 16 image rows; step t decodes pixel
 // (r, t - 2r) of each row.  Per step:
 //   network   the 16 pixels form one MFMA tile; each wave computes a quarter
-//             of every layer's out-blocks and the layers meet in LDS
+//             of every layer's out-blocks with its weight slices held in
+//             registers for the whole kernel, and the layers meet in LDS
 //   search    16 lanes per pixel find the symbol with two 16-way rounds of
 //             Cq evaluations per channel (R, then G given R, then B given R,G)
 //   publish   the pixel goes to the LDS ring (next steps' neighbourhoods), to
 //             the output image and, for the band's last two rows, to a mailbox
 //             in global memory that the band below polls
 // ---------------------------------------------------------------------------
+#ifdef PCC_PHASE_TIMING
+// Tuning aid (off in normal builds): cycles spent per phase of a decode step,
+// accumulated by thread 0 of the band holding ticket 1 (or 0 if there is one band).
+__device__ unsigned long long g_phase_cycles[16];
+#define PCC_PHASE(k) do { if (timed) { const unsigned long long now_ = clock64(); phase_acc[k] += now_ - phase_t; phase_t = now_; } } while (0)
+#else
+#define PCC_PHASE(k) do { } while (0)
+#endif
 constexpr int kDecThreads = 256;
 constexpr int kActBytes = 5 * 2 * 64 * 16;                     // one layer's activations: [k-block][hi,lo][lane][16 B]
-constexpr int kAct0Off = kModelBytes;
-constexpr int kAct1Off = kAct0Off + kActBytes;
-constexpr int kHeadOff = kAct1Off;                              // head outputs [16][64] fp32 reuse the second buffer
-constexpr int kCpOff = kHeadOff + 16 * 64 * 4;                  // mixtures [16][3][5] x (pi, mu, 1/sigma)
-constexpr int kRingOff = kAct1Off + kActBytes;                  // ring [18][8] uint32
-constexpr int kDecMiscOff = kRingOff + 18 * 8 * 4;              // ticket, abort flag
-constexpr int kDecLdsBytes = kDecMiscOff + 64;
-static_assert(kCpOff + 16 * 3 * 5 * 3 * 4 <= kAct1Off + kActBytes, "head outputs and mixtures must fit the second buffer");
-static_assert(kDecLdsBytes <= 160 * 1024, "decode LDS budget");
+// decode LDS: the normal-CDF table, two activation buffers, head outputs, mixtures, ring
+constexpr int kDLutOff = 0;
+constexpr int kDAct0Off = (kLutEntries + 1) * 8;               // 12,304
+constexpr int kDAct1Off = kDAct0Off + kActBytes;
+constexpr int kDHeadOff = kDAct1Off + kActBytes;               // [16 pixels][4 groups][16] fp32, (group, register) layout
+constexpr int kDCpOff = kDHeadOff + 16 * 64 * 4;               // [16 pixels][3 channels][16] fp32: pi[5], mu[5], a[5], pad
+// Ring of recently decoded pixels as first-layer inputs: [18 rows][16 columns][3] bf16.
+// Rows 0,1 are the two rows above the band.  Column c lives at slots c & 7 and
+// (c & 7) + 8, so the twelve values of columns c-2..c+1 are always contiguous.
+constexpr int kRingRowElems = 16 * 3;
+constexpr int kDRingOff = kDCpOff + 16 * 3 * 16 * 4;
+constexpr int kDMiscOff = kDRingOff + 18 * kRingRowElems * 2;  // ticket, abort flag
+constexpr int kDecLdsBytes = kDMiscOff + 64;
+static_assert(kDAct0Off % 16 == 0 && kDCpOff % 16 == 0, "vector alignment");
 
-struct RowReader {          // lives in lane 0 of each pixel's 16-lane group
+// All-reduce over the 16 lanes of a DPP row by rotations.
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_row(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, false);
+}
+__device__ __forceinline__ uint32_t row_allmax(uint32_t v) {
+    v = max(v, dpp_row<0x121>(v)); v = max(v, dpp_row<0x122>(v));
+    v = max(v, dpp_row<0x124>(v)); v = max(v, dpp_row<0x128>(v));
+    return v;
+}
+__device__ __forceinline__ uint32_t row_allmin(uint32_t v) {
+    v = min(v, dpp_row<0x121>(v)); v = min(v, dpp_row<0x122>(v));
+    v = min(v, dpp_row<0x124>(v)); v = min(v, dpp_row<0x128>(v));
+    return v;
+}
+
+// rANS reader of one row, replicated in the 16 lanes of the pixel's group.  The
+// next 32 stream words sit in registers, lane j holding words base+j and
+// base+16+j, so a renormalisation never waits for memory: the refill issued
+// when a 16-word block is used up is not needed for another 16 words.
+struct RowReader {
     uint64_t x;
     const uint32_t* words;  // payload after the 8-byte state
-    uint32_t nwords, pos;
-    uint32_t w0, w1;        // words[pos], words[pos+1], fetched ahead of use
+    uint32_t nwords, pos;   // pos: words consumed so far
+    uint32_t cur, nxt;      // words[(pos & ~15) + j], words[(pos & ~15) + 16 + j]
     bool bad;
 };
 
-__device__ __forceinline__ void reader_advance(RowReader& rd, uint32_t slot, uint32_t start, uint32_t freq) {
-    rd.x = (uint64_t)freq * (rd.x >> 16) + slot - start;
-    if (rd.x < kRansL) {
+__device__ __forceinline__ void reader_init(RowReader& rd, const uint32_t* payload, uint32_t nwords_total, int j) {
+    rd.x = (uint64_t)payload[0] | ((uint64_t)payload[1] << 32);
+    rd.words = payload + 2;
+    rd.nwords = nwords_total - 2;
+    rd.pos = 0;
+    rd.cur = (uint32_t)j < rd.nwords ? rd.words[j] : 0u;
+    rd.nxt = (uint32_t)j + 16u < rd.nwords ? rd.words[j + 16] : 0u;
+    rd.bad = false;
+    if (rd.x < kRansL || (rd.x >> 63)) { rd.bad = true; rd.x = kRansL; }
+}
+
+__device__ __forceinline__ void reader_advance(RowReader& rd, uint32_t slot, uint32_t start, uint32_t freq, int j,
+                                               bool active) {
+    const uint32_t w = row_allmax((uint32_t)j == (rd.pos & 15u) ? rd.cur : 0u);   // words[pos], in every lane of the group
+    const uint64_t x1 = (uint64_t)freq * (rd.x >> 16) + slot - start;
+    const bool renorm = active && x1 < kRansL;
+    if (active) rd.x = renorm ? ((x1 << 32) | w) : x1;
+    if (renorm) {
         if (rd.pos >= rd.nwords) rd.bad = true;
-        rd.x = (rd.x << 32) | rd.w0;
         rd.pos += 1;
-        rd.w0 = rd.w1;
-        rd.w1 = (rd.pos + 1 < rd.nwords) ? rd.words[rd.pos + 1] : 0u;
+        if ((rd.pos & 15u) == 0u) {
+            rd.cur = rd.nxt;
+            const uint32_t idx = rd.pos + 16u + (uint32_t)j;
+            rd.nxt = idx < rd.nwords ? rd.words[idx] : 0u;
+        }
     }
 }
 
-// One hidden layer, this wave's out-blocks ob = wave, wave+4, wave+8 (< NOB).
-// Same arithmetic per output element as hidden_layer<> in pcc_device.h: bias,
-// then k-blocks in order, each hi then lo; ReLU; split into hi + lo.
-template <int NOB, int NKB, bool SPLIT_IN>
-__device__ __forceinline__ void dec_hidden_layer(const uint8_t* __restrict__ w, const float* __restrict__ bias, int lane,
-                                                 int wave, const u32x4_t (&in)[NKB][2], uint8_t* __restrict__ act_out) {
-    const int g = lane >> 4;
-    constexpr int kSlots = (NOB + 3) / 4;
-    f32x4_t acc[kSlots];
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for
+// every outstanding global access (pixel stores, mailbox traffic, stream-word and
+// mailbox prefetches), which would put HBM latency on the step's critical path
+// five times per step; nothing here hands global data from thread to thread.
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// This wave's weight slices of one layer: out-blocks ob = wave + 4 s.  Where the
+// wave has no such block (ob >= NOB) it holds a copy of the layer's last block
+// and its results are discarded.
+template <int NOB, int NKB, int SLOTS>
+struct WaveLayer {
+    u32x4_t a[SLOTS][NKB];
+    f32x4_t bias[SLOTS];
+    __device__ __forceinline__ void load(const uint8_t* __restrict__ w, const float* __restrict__ b, int lane, int wave) {
 #pragma unroll
-    for (int s = 0; s < kSlots; ++s) {
-        const int ob = min(wave + 4 * s, NOB - 1);
-        acc[s] = *reinterpret_cast<const f32x4_t*>(bias + 16 * ob + 4 * g);
+        for (int s = 0; s < SLOTS; ++s) {
+            const int ob = min(wave + 4 * s, NOB - 1);
+            bias[s] = *reinterpret_cast<const f32x4_t*>(b + 16 * ob + 4 * (lane >> 4));
+#pragma unroll
+            for (int kb = 0; kb < NKB; ++kb)
+                a[s][kb] = *reinterpret_cast<const u32x4_t*>(w + ((ob * NKB + kb) * 64 + lane) * 16);
+        }
     }
+};
+
+// One hidden layer on this wave's out-blocks.  Same arithmetic per output element
+// as hidden_layer<> in pcc_device.h: bias, then k-blocks in order, each hi then
+// lo; ReLU; split into hi + lo.
+template <int NOB, int NKB, int SLOTS, bool SPLIT_IN>
+__device__ __forceinline__ void dec_hidden_layer(const WaveLayer<NOB, NKB, SLOTS>& wl, int lane, int wave,
+                                                 const u32x4_t (&in)[NKB][2], uint8_t* __restrict__ act_out) {
+    f32x4_t acc[SLOTS];
+#pragma unroll
+    for (int s = 0; s < SLOTS; ++s) acc[s] = wl.bias[s];
 #pragma unroll
     for (int kb = 0; kb < NKB; ++kb) {
 #pragma unroll
-        for (int s = 0; s < kSlots; ++s) {
-            const int ob = min(wave + 4 * s, NOB - 1);   // a duplicate of the last block where the wave has none: discarded below
-            const u32x4_t a = *reinterpret_cast<const u32x4_t*>(w + ((ob * NKB + kb) * 64 + lane) * 16);
-            acc[s] = mfma16(a, in[kb][0], acc[s]);
-            if (SPLIT_IN) acc[s] = mfma16(a, in[kb][1], acc[s]);
+        for (int s = 0; s < SLOTS; ++s) acc[s] = mfma16(wl.a[s][kb], in[kb][0], acc[s]);
+        if (SPLIT_IN) {
+#pragma unroll
+            for (int s = 0; s < SLOTS; ++s) acc[s] = mfma16(wl.a[s][kb], in[kb][1], acc[s]);
         }
     }
 #pragma unroll
-    for (int s = 0; s < kSlots; ++s) {
+    for (int s = 0; s < SLOTS; ++s) {
         const int ob = wave + 4 * s;
         if (ob < NOB) {
             uint32_t l0, l1;
@@ -377,19 +451,19 @@ __device__ __forceinline__ void dec_load_act(const uint8_t* __restrict__ act, in
 // evaluations.  All lanes of the group return the same x, start, freq.
 __device__ __forceinline__ int group_search(const ChanParams& cp, uint32_t slot, const float2* __restrict__ lut, int lane,
                                             uint32_t& start, uint32_t& freq) {
-    const int j = lane & 15, base = lane & 48, shift = lane & 48;
+    const int j = lane & 15, shift = lane & 48;
     // round 1: Cq(16 j); lanes 0..b satisfy Cq <= slot (Cq is increasing and Cq(0) = 0)
     const uint32_t c1 = j == 0 ? 0u : cq_eval(cp, 16 * j, lut);
-    const int cnt1 = __popcll((__ballot(c1 <= slot) >> shift) & 0xFFFFull);
-    const int b = cnt1 - 1;
-    const uint32_t lo1 = __shfl(c1, base + b);
-    const uint32_t hi1 = b < 15 ? (uint32_t)__shfl(c1, base + min(b + 1, 15)) : 65536u;
+    const bool p1 = c1 <= slot;
+    const int b = __popcll((__ballot(p1) >> shift) & 0xFFFFull) - 1;
+    const uint32_t lo1 = row_allmax(p1 ? c1 : 0u);           // Cq(16 b)
+    const uint32_t hi1 = row_allmin(p1 ? 65536u : c1);       // Cq(16 b + 16)
     // round 2: Cq(16 b + j)
     const uint32_t c2 = j == 0 ? lo1 : cq_eval(cp, 16 * b + j, lut);
-    const int cnt2 = __popcll((__ballot(c2 <= slot) >> shift) & 0xFFFFull);
-    start = __shfl(c2, base + cnt2 - 1);
-    const uint32_t nxt = __shfl(c2, base + min(cnt2, 15));
-    freq = (cnt2 < 16 ? nxt : hi1) - start;
+    const bool p2 = c2 <= slot;
+    const int cnt2 = __popcll((__ballot(p2) >> shift) & 0xFFFFull);
+    start = row_allmax(p2 ? c2 : 0u);
+    freq = row_allmin(p2 ? hi1 : c2) - start;
     return 16 * b + cnt2 - 1;
 }
 
@@ -397,12 +471,13 @@ __global__ void __launch_bounds__(kDecThreads)
 decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ stream, uint64_t nbytes, int n, int H,
               int W, int nbands, uint8_t* __restrict__ img_out, uint32_t* mailbox, int* status, uint32_t spin_limit) {
     extern __shared__ __align__(16) uint8_t lds[];
-    uint8_t* act0 = lds + kAct0Off;
-    uint8_t* act1 = lds + kAct1Off;
-    float* headout = reinterpret_cast<float*>(lds + kHeadOff);      // [16][64], canonical head index
-    float* cpbuf = reinterpret_cast<float*>(lds + kCpOff);          // [16][3][5][3]
-    uint32_t (*ring)[8] = reinterpret_cast<uint32_t (*)[8]>(lds + kRingOff);   // [18][8]
-    int* misc = reinterpret_cast<int*>(lds + kDecMiscOff);          // [0] ticket, [1] abort
+    float2* lut = reinterpret_cast<float2*>(lds + kDLutOff);
+    uint8_t* act0 = lds + kDAct0Off;
+    uint8_t* act1 = lds + kDAct1Off;
+    float* headout = reinterpret_cast<float*>(lds + kDHeadOff);
+    float* cpbuf = reinterpret_cast<float*>(lds + kDCpOff);
+    uint16_t* ring = reinterpret_cast<uint16_t*>(lds + kDRingOff);   // [18][16][3] bf16
+    int* misc = reinterpret_cast<int*>(lds + kDMiscOff);            // [0] ticket, [1] abort
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     // network role: pixel nl of the tile, k-slot group g
@@ -413,13 +488,26 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
     // Bands take tickets in start order: a band only ever waits for the band
     // above it, which holds a smaller ticket and is therefore already running.
     if (tid == 0) { misc[0] = atomicAdd(&status[kStTicket], 1); misc[1] = 0; }
-    copy_model_to_lds(lds, model);
-    for (int i = tid; i < 18 * 8; i += kDecThreads) (&ring[0][0])[i] = 0u;
+    {
+        const float2* src = reinterpret_cast<const float2*>(model + kLutOff);
+        for (int i = tid; i < kLutEntries + 1; i += kDecThreads) lut[i] = src[i];
+    }
+    for (int i = tid; i < 18 * kRingRowElems; i += kDecThreads) ring[i] = 0;
+
+    // this wave's weights stay in registers
+    WaveLayer<kL1_OB, kL1_KB, 3> wl1;
+    WaveLayer<kL2_OB, kL2_KB, 3> wl2;
+    WaveLayer<kL3_OB, kL3_KB, 2> wl3;
+    WaveLayer<kL4_OB, kL4_KB, 1> wl4;
+    wl1.load(model + kW1Off, reinterpret_cast<const float*>(model + kB1Off), lane, wave);
+    wl2.load(model + kW2Off, reinterpret_cast<const float*>(model + kB2Off), lane, wave);
+    wl3.load(model + kW3Off, reinterpret_cast<const float*>(model + kB3Off), lane, wave);
+    wl4.load(model + kW4Off, reinterpret_cast<const float*>(model + kB4Off), lane, wave);
     __syncthreads();
+
     const int ticket = misc[0];
     const int im = ticket / nbands, band = ticket - im * nbands;
     if (im >= n) return;
-    const float2* lut = reinterpret_cast<const float2*>(lds + kLutOff);
 
     const int r0 = band * kBandRows;
     const uint64_t rows_total = (uint64_t)n * H;
@@ -434,27 +522,20 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
             set_error(status, PCC_E_STREAM);
     }
 
-    // search role: row of this lane's pixel, its stream reader (lane j == 0 only)
+    // search role: row of this lane's pixel and its stream reader (the same in all 16 lanes of the group)
     const int qrow = r0 + q;
     const bool qrow_ok = qrow < H;
     RowReader rd;
-    rd.x = kRansL; rd.words = nullptr; rd.nwords = 0; rd.pos = 0; rd.w0 = 0; rd.w1 = 0; rd.bad = false;
-    if (j == 0 && qrow_ok) {
+    rd.x = kRansL; rd.words = nullptr; rd.nwords = 0; rd.pos = 0; rd.cur = 0; rd.nxt = 0; rd.bad = false;
+    if (qrow_ok) {
         const uint64_t* offs = reinterpret_cast<const uint64_t*>(stream + kStreamHeader);
         const uint64_t rowg = (uint64_t)im * H + qrow;
         const uint64_t a = offs[rowg], b = offs[rowg + 1];
         if (a > b || b > payload_bytes || (b - a) < 8 || ((b - a) & 3) != 0 || (a & 3) != 0 ||
-            (b - a) > 4ull * slab_words(W)) {
+            (b - a) > 4ull * slab_words(W))
             rd.bad = true;
-        } else {
-            const uint32_t* p = reinterpret_cast<const uint32_t*>(stream + table + a);
-            rd.x = (uint64_t)p[0] | ((uint64_t)p[1] << 32);
-            rd.words = p + 2;
-            rd.nwords = (uint32_t)((b - a) / 4) - 2;
-            rd.w0 = rd.nwords > 0 ? rd.words[0] : 0u;
-            rd.w1 = rd.nwords > 1 ? rd.words[1] : 0u;
-            if (rd.x < kRansL || (rd.x >> 63)) { rd.bad = true; rd.x = kRansL; }
-        }
+        else
+            reader_init(rd, reinterpret_cast<const uint32_t*>(stream + table + a), (uint32_t)((b - a) / 4), j);
     }
 
     uint8_t* out_img = img_out + (size_t)im * H * W * 3;
@@ -467,6 +548,14 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
     const uint32_t* mail_row = mail_in + (size_t)(tid & 1) * W;
     uint32_t pf = 0;                              // mailbox word for the next column, requested a step early
 
+    // bf16 of the three channels of pixel word px into both copies of column cc of a ring row
+    auto ring_put = [&](int rrow, int cc, uint32_t px) {
+        uint16_t* d = ring + rrow * kRingRowElems + (cc & 7) * 3;
+        const uint16_t v0 = (uint16_t)byte_to_bf16(px & 0xFFu), v1 = (uint16_t)byte_to_bf16((px >> 8) & 0xFFu),
+                       v2 = (uint16_t)byte_to_bf16((px >> 16) & 0xFFu);
+        d[0] = v0; d[1] = v1; d[2] = v2;
+        d[24] = v0; d[25] = v1; d[26] = v2;
+    };
     // Bring columns 0 and 1 of the two rows above the band into the ring, then keep
     // one column ahead: the step at t needs column (t - t_begin) + 1.
     auto fetch_column = [&](int cc, uint32_t have) -> bool {   // returns false on abort
@@ -481,7 +570,7 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
                 return false;
             __builtin_amdgcn_s_sleep(1);
         }
-        ring[tid & 1][cc & 7] = v & 0xFFFFFFu;
+        ring_put(tid & 1, cc, v);
         return true;
     };
     if (fetcher) {
@@ -493,139 +582,142 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
             misc[1] = 1;
         }
     }
-    __syncthreads();
+    lds_barrier();
 
+    // network role: this lane's eight first-layer inputs are two runs of four
+    // consecutive ring values (row, offset within the 12-value window of columns c-2..c+1)
+    const int gA_row = nl + (g >= 2 ? 1 : 0), gA_off = (g & 1) ? 8 : 0;
+    const int gB_row = nl + (g == 0 ? 0 : (g == 2 ? 1 : 2)), gB_off = (g == 1) ? 0 : 4;
+    const uint16_t* gA = ring + gA_row * kRingRowElems + gA_off;
+    const uint16_t* gB = ring + gB_row * kRingRowElems + gB_off;
+
+#ifdef PCC_PHASE_TIMING
+    const bool timed = tid == 0 && ticket == (nbands * n > 1 ? 1 : 0);
+    unsigned long long phase_acc[16] = {};
+    unsigned long long phase_t = clock64();
+#endif
     for (int t = t_begin; t <= t_end; ++t) {
-        if (misc[1] != 0) break;                  // uniform: written before the last barrier
-        const uint8_t* mdl = lds + opaque_zero();
+        if ((t & 7) == 0 && misc[1] != 0) break;  // uniform: written before the last barrier; a late exit only decodes garbage
+        PCC_PHASE(15);
 
-        // ---- gather C_ij from the ring (zero outside the image); every wave builds the full tile
+        // ---- gather C_ij from the ring (zeros stand for pixels outside the image); every wave builds the full tile
         u32x4_t in1[1][2];
         {
-            const int row = r0 + nl;
-            const int c = t - 2 * row;
-            uint32_t slots[8];
+            const int c = t - 2 * (r0 + nl);
+            const int w0 = ((c - 2) & 7) * 3;
+            uint32_t v[8];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                int dr, b;
-                bool used;
-                slot_source(g, i, dr, b, used);
-                const int pc = (b * 11) >> 5;               // neighbour column index 0..3
-                const int colx = c - 2 + pc;
-                const int ch = b - 3 * pc;
-                const bool ok = used && (row + dr) >= 0 && colx >= 0 && colx < W;
-                const uint32_t px = ring[nl + 2 + dr][colx & 7];
-                slots[i] = ok ? byte_to_bf16((px >> (8 * ch)) & 0xFFu) : 0u;
-            }
-            in1[0][0].x = slots[0] | (slots[1] << 16);
-            in1[0][0].y = slots[2] | (slots[3] << 16);
-            in1[0][0].z = slots[4] | (slots[5] << 16);
-            in1[0][0].w = slots[6] | (slots[7] << 16);
+            for (int i = 0; i < 4; ++i) { v[i] = gA[w0 + i]; v[4 + i] = gB[w0 + i]; }
+            // one batch of LDS reads
+            asm volatile("" : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]), "+v"(v[4]), "+v"(v[5]), "+v"(v[6]), "+v"(v[7]));
+            in1[0][0].x = v[0] | (v[1] << 16);
+            in1[0][0].y = v[2] | (v[3] << 16);
+            in1[0][0].z = v[4] | (v[5] << 16);
+            in1[0][0].w = v[6] | (v[7] << 16);
             in1[0][1] = in1[0][0];   // unused (layer-1 inputs are exact)
         }
+        PCC_PHASE(0);
 
         // ---- network, layers meeting in LDS
-        dec_hidden_layer<kL1_OB, kL1_KB, false>(mdl + kW1Off, reinterpret_cast<const float*>(mdl + kB1Off), lane, wave,
-                                                in1, act0);
-        __syncthreads();
+        dec_hidden_layer<kL1_OB, kL1_KB, 3, false>(wl1, lane, wave, in1, act0);
+        lds_barrier();
+        PCC_PHASE(1);
         {
             u32x4_t in[kL2_KB][2];
             dec_load_act<kL2_KB>(act0, lane, in);
-            dec_hidden_layer<kL2_OB, kL2_KB, true>(mdl + kW2Off, reinterpret_cast<const float*>(mdl + kB2Off), lane,
-                                                   wave, in, act1);
+            dec_hidden_layer<kL2_OB, kL2_KB, 3, true>(wl2, lane, wave, in, act1);
         }
-        __syncthreads();
+        lds_barrier();
+        PCC_PHASE(2);
         {
             u32x4_t in[kL3_KB][2];
             dec_load_act<kL3_KB>(act1, lane, in);
-            dec_hidden_layer<kL3_OB, kL3_KB, true>(mdl + kW3Off, reinterpret_cast<const float*>(mdl + kB3Off), lane,
-                                                   wave, in, act0);
+            dec_hidden_layer<kL3_OB, kL3_KB, 2, true>(wl3, lane, wave, in, act0);
         }
-        __syncthreads();
+        lds_barrier();
+        PCC_PHASE(3);
         {
             u32x4_t in[kL4_KB][2];
             dec_load_act<kL4_KB>(act0, lane, in);
-            const int ob = wave;
-            f32x4_t acc = *reinterpret_cast<const f32x4_t*>(reinterpret_cast<const float*>(mdl + kB4Off) + 16 * ob + 4 * g);
+            f32x4_t acc = wl4.bias[0];
 #pragma unroll
             for (int kb = 0; kb < kL4_KB; ++kb) {
-                const u32x4_t a = *reinterpret_cast<const u32x4_t*>(mdl + kW4Off + ((ob * kL4_KB + kb) * 64 + lane) * 16);
-                acc = mfma16(a, in[kb][0], acc);
-                acc = mfma16(a, in[kb][1], acc);
+                acc = mfma16(wl4.a[0][kb], in[kb][0], acc);
+                acc = mfma16(wl4.a[0][kb], in[kb][1], acc);
             }
-            const float vv[4] = {acc.x, acc.y, acc.z, acc.w};
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int idx = head_index(g, 4 * ob + i);
-                if (idx >= 0) headout[nl * 64 + idx] = vv[i];
-            }
+            // registers s = 4 wave + i of group g, kept in (group, register) order
+            *reinterpret_cast<f32x4_t*>(headout + nl * 64 + g * 16 + 4 * wave) = acc;
         }
-        __syncthreads();
+        lds_barrier();
+        PCC_PHASE(4);
 
         // ---- mixtures: lane j < 15 of pixel q prepares component j % 5 of channel j / 5
         if (j < 15) {
             const int ch = j / 5, k = j - 5 * ch;
-            float raw[15];
-#pragma unroll
-            for (int s = 0; s < 15; ++s) raw[s] = headout[q * 64 + 15 * ch + s];
+            const f32x4_t* src = reinterpret_cast<const f32x4_t*>(headout + q * 64 + ch * 16);
+            const f32x4_t v0 = src[0], v1 = src[1], v2 = src[2], v3 = src[3];
+            const float raw[15] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w, v2.x, v2.y, v2.z, v2.w, v3.x, v3.y, v3.z};
             ChanParams all;
             channel_setup(raw, all);
-            float pk = all.pi[0], mk = all.mu[0], sk = all.isg[0];
+            float pk = all.pi[0], mk = all.mu[0], ak = all.a[0];
 #pragma unroll
-            for (int kk = 1; kk < 5; ++kk) if (k == kk) { pk = all.pi[kk]; mk = all.mu[kk]; sk = all.isg[kk]; }
-            float* dst = cpbuf + ((q * 3 + ch) * 5 + k) * 3;
-            dst[0] = pk; dst[1] = mk; dst[2] = sk;
+            for (int kk = 1; kk < 5; ++kk) if (k == kk) { pk = all.pi[kk]; mk = all.mu[kk]; ak = all.a[kk]; }
+            float* dst = cpbuf + (q * 3 + ch) * 16 + k;
+            dst[0] = pk; dst[5] = mk; dst[10] = ak;
         }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
         __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
+
+        // everything the three searches need, in one batch of LDS reads
+        ChanParams cpr, cpg, cpb;
+        float alpha[5], beta[5], gamma[5];
+        {
+            auto load_cp = [&](int ch, ChanParams& cp) {
+                const f32x4_t* src = reinterpret_cast<const f32x4_t*>(cpbuf + (q * 3 + ch) * 16);
+                const f32x4_t v0 = src[0], v1 = src[1], v2 = src[2], v3 = src[3];
+                cp.pi[0] = v0.x; cp.pi[1] = v0.y; cp.pi[2] = v0.z; cp.pi[3] = v0.w; cp.pi[4] = v1.x;
+                cp.mu[0] = v1.y; cp.mu[1] = v1.z; cp.mu[2] = v1.w; cp.mu[3] = v2.x; cp.mu[4] = v2.y;
+                cp.a[0] = v2.z; cp.a[1] = v2.w; cp.a[2] = v3.x; cp.a[3] = v3.y; cp.a[4] = v3.z;
+            };
+            load_cp(0, cpr); load_cp(1, cpg); load_cp(2, cpb);
+            const float* hq = headout + q * 64;
+            const f32x4_t* g3 = reinterpret_cast<const f32x4_t*>(hq + 48);
+            const f32x4_t c0 = g3[0], c1 = g3[1], c2 = g3[2];
+            alpha[0] = hq[16 + 15]; alpha[1] = c0.x; alpha[2] = c0.y; alpha[3] = c0.z; alpha[4] = c0.w;
+            beta[0] = hq[32 + 15]; beta[1] = c1.x; beta[2] = c1.y; beta[3] = c1.z; beta[4] = c1.w;
+            gamma[0] = c2.x; gamma[1] = c2.y; gamma[2] = c2.z; gamma[3] = c2.w; gamma[4] = hq[48 + 12];
+        }
+        PCC_PHASE(5);
 
         const int c = t - 2 * qrow;
         const bool active = qrow_ok && c >= 0 && c < W;
-        const int leader = lane & 48;
-        auto load_cp = [&](int ch, ChanParams& cp) {
-#pragma unroll
-            for (int k = 0; k < 5; ++k) {
-                const float* src = cpbuf + ((q * 3 + ch) * 5 + k) * 3;
-                cp.pi[k] = src[0]; cp.mu[k] = src[1]; cp.isg[k] = src[2];
-            }
-        };
-        ChanParams cp;
         uint32_t start, freq;
         // R
-        load_cp(0, cp);
-        uint32_t slot = __shfl((uint32_t)rd.x & 0xFFFFu, leader);
-        const int sr = group_search(cp, slot, lut, lane, start, freq);
-        if (j == 0 && active) reader_advance(rd, slot, start, freq);
+        uint32_t slot = (uint32_t)rd.x & 0xFFFFu;
+        const int sr = group_search(cpr, slot, lut, lane, start, freq);
+        reader_advance(rd, slot, start, freq, j, active);
         const float rhat = (float)sr * (1.0f / 256.0f);
+        PCC_PHASE(6);
         // G given R
-        load_cp(1, cp);
-        {
-            float alpha[5];
-#pragma unroll
-            for (int k = 0; k < 5; ++k) alpha[k] = headout[q * 64 + 45 + k];
-            couple_green(cp, alpha, rhat);
-        }
-        slot = __shfl((uint32_t)rd.x & 0xFFFFu, leader);
-        const int sg = group_search(cp, slot, lut, lane, start, freq);
-        if (j == 0 && active) reader_advance(rd, slot, start, freq);
+        couple_green(cpg, alpha, rhat);
+        slot = (uint32_t)rd.x & 0xFFFFu;
+        const int sg = group_search(cpg, slot, lut, lane, start, freq);
+        reader_advance(rd, slot, start, freq, j, active);
         const float ghat = (float)sg * (1.0f / 256.0f);
+        PCC_PHASE(7);
         // B given R, G
-        load_cp(2, cp);
-        {
-            float beta[5], gamma[5];
-#pragma unroll
-            for (int k = 0; k < 5; ++k) { beta[k] = headout[q * 64 + 50 + k]; gamma[k] = headout[q * 64 + 55 + k]; }
-            couple_blue(cp, beta, gamma, rhat, ghat);
-        }
-        slot = __shfl((uint32_t)rd.x & 0xFFFFu, leader);
-        const int sb = group_search(cp, slot, lut, lane, start, freq);
-        if (j == 0 && active) reader_advance(rd, slot, start, freq);
+        couple_blue(cpb, beta, gamma, rhat, ghat);
+        slot = (uint32_t)rd.x & 0xFFFFu;
+        const int sb = group_search(cpb, slot, lut, lane, start, freq);
+        reader_advance(rd, slot, start, freq, j, active);
+        PCC_PHASE(8);
 
         // ---- publish
         if (j == 0 && active) {
             const uint32_t px = (uint32_t)sr | ((uint32_t)sg << 8) | ((uint32_t)sb << 16);
-            ring[q + 2][c & 7] = px;
+            ring_put(q + 2, c, px);
+            if (c == W - 1) ring_put(q + 2, W, 0u);   // the column right of the image reads as zero
             uint8_t* o = out_img + ((size_t)qrow * W + c) * 3;
             o[0] = (uint8_t)sr; o[1] = (uint8_t)sg; o[2] = (uint8_t)sb;
             if (q >= kBandRows - 2)
@@ -636,6 +728,7 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
         // ---- rows above the band: column needed by the next step, and request the one after
         if (fetcher) {
             const int cc = t - t_begin + 2;
+            if (cc == W) ring_put(tid & 1, W, 0u);    // the column right of the image reads as zero
             if (cc < W && t < t_end) {
                 if (!fetch_column(cc, pf)) {
                     __hip_atomic_store(&status[kStAbort], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -644,8 +737,13 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
                 pf = (cc + 1 < W) ? __hip_atomic_load(mail_row + cc + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
             }
         }
-        __syncthreads();
+        PCC_PHASE(9);
+        lds_barrier();
+        PCC_PHASE(10);
     }
+#ifdef PCC_PHASE_TIMING
+    if (timed) for (int k = 0; k < 16; ++k) g_phase_cycles[k] = phase_acc[k];
+#endif
 }
 
 // ---------------------------------------------------------------------------
@@ -1050,6 +1148,13 @@ int pcc_last_timings(pcc_ctx* ctx, float* h_ms) {
     for (int i = 0; i < PCC_N_TIMINGS; ++i) h_ms[i] = ctx->last_ms[i];
     return PCC_OK;
 }
+
+#ifdef PCC_PHASE_TIMING
+int pcc_debug_phase_cycles(unsigned long long* h_out16) {
+    return hipMemcpyFromSymbol(h_out16, HIP_SYMBOL(pcc::g_phase_cycles), 16 * sizeof(unsigned long long)) == hipSuccess
+               ? PCC_OK : PCC_E_HIP;
+}
+#endif
 
 int pcc_copy_intervals(pcc_ctx* ctx, uint32_t* d_out, size_t count, void* hip_stream) {
     if (!ctx || !d_out) return PCC_E_ARG;

@@ -200,7 +200,7 @@ __device__ __forceinline__ void mlp_forward(const uint8_t* __restrict__ model, i
 struct ChanParams {
     float pi[5];   // mixture weights, softmax of the logits
     float mu[5];   // means, units of 1/256 of the grey range
-    float isg[5];  // 1 / sigma
+    float a[5];    // 128 / sigma: table steps per unit of (edge - mu)
 };
 
 constexpr float kLog2e = 1.4426950408889634f;
@@ -220,7 +220,7 @@ __device__ __forceinline__ void channel_setup(const float (&raw)[15], ChanParams
         cp.pi[k] = e[k] * inv;
         cp.mu[k] = raw[5 + k];
         const float ls = fminf(fmaxf(raw[10 + k], -8.0f), 4.0f);   // sigma = exp(clamp(log sigma, -8, 4))
-        cp.isg[k] = __builtin_amdgcn_exp2f(-(ls * kLog2e));
+        cp.a[k] = __builtin_amdgcn_exp2f(-(ls * kLog2e)) * kLutScale;
     }
 }
 
@@ -237,22 +237,28 @@ __device__ __forceinline__ void couple_blue(ChanParams& cp, const float (&beta)[
 
 // Integer CDF at the lower edge of bin e (grey level e - 0.5), 1 <= e <= 255:
 //   Cq(e) = e + min(floor(65280 * sum_k pi_k Phi(z_k)), 65280),  z_k = ((e-0.5)/256 - mu_k) / sigma_k.
-// Phi is a table with linear interpolation: entries are multiples of 2^-24 and
-// the stored forward differences are exact, so one fma per lookup is
-// non-decreasing in z; with pi_k >= 0 every later step (fma, floor) keeps that,
-// hence Cq is strictly increasing in e and every symbol has frequency >= 1.
+// Phi is a table with linear interpolation at coordinate t = 128 z + 768,
+// clamped to the table.  Entries are multiples of 2^-24 and the stored forward
+// differences are exact, so one fma per lookup is non-decreasing in z; with
+// pi_k >= 0 every later step (fma, floor) keeps that, hence Cq is strictly
+// increasing in e and every symbol has frequency >= 1.
 __device__ __forceinline__ uint32_t cq_eval(const ChanParams& cp, int e, const float2* __restrict__ lut) {
     const float edge = (float)(2 * e - 1) * (1.0f / 512.0f);
+    float t[5];
+    float2 td[5];
+#pragma unroll
+    for (int k = 0; k < 5; ++k) {
+        t[k] = __builtin_amdgcn_fmed3f(__builtin_fmaf(edge - cp.mu[k], cp.a[k], kLutBias), 0.0f, kLutMax);
+        td[k] = lut[(int)t[k]];                                // t >= 0: truncation is floor
+    }
+    // Scheduling only: all five table reads are in flight before the first is
+    // used (one LDS latency per evaluation instead of five).
+    asm volatile("" : "+v"(td[0].x), "+v"(td[0].y), "+v"(td[1].x), "+v"(td[1].y), "+v"(td[2].x), "+v"(td[2].y),
+                      "+v"(td[3].x), "+v"(td[3].y), "+v"(td[4].x), "+v"(td[4].y));
     float acc = 0.0f;
 #pragma unroll
     for (int k = 0; k < 5; ++k) {
-        const float z = (edge - cp.mu[k]) * cp.isg[k];
-        float t = __builtin_fmaf(z, kLutScale, kLutBias);
-        t = fminf(fmaxf(t, 0.0f), kLutMax);
-        const float fi = floorf(t);
-        const float fr = t - fi;
-        const float2 td = lut[(int)fi];
-        const float phi = __builtin_fmaf(fr, td.y, td.x);
+        const float phi = __builtin_fmaf(__builtin_amdgcn_fractf(t[k]), td[k].y, td[k].x);
         acc = __builtin_fmaf(cp.pi[k], phi, acc);
     }
     const float v = fminf(floorf(acc * 65280.0f), 65280.0f);
@@ -263,23 +269,6 @@ __device__ __forceinline__ uint32_t cq_full(const ChanParams& cp, int e, const f
     if (e <= 0) return 0u;
     if (e >= 256) return 65536u;
     return cq_eval(cp, e, lut);
-}
-
-// Largest x in [0,255] with Cq(x) <= slot, by bisection; also returns Cq(x) and
-// the frequency Cq(x+1) - Cq(x).
-__device__ __forceinline__ int cq_search(const ChanParams& cp, uint32_t slot, const float2* __restrict__ lut,
-                                         uint32_t& start, uint32_t& freq) {
-    int lo = 0, hi = 256;
-    uint32_t clo = 0u, chi = 65536u;
-#pragma unroll 1
-    for (int it = 0; it < 8; ++it) {
-        const int mid = (lo + hi) >> 1;
-        const uint32_t c = cq_eval(cp, mid, lut);
-        if (c <= slot) { lo = mid; clo = c; } else { hi = mid; chi = c; }
-    }
-    start = clo;
-    freq = chi - clo;
-    return lo;
 }
 
 // ---------------------------------------------------------------------------
