@@ -199,33 +199,108 @@ encode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ img
 }
 
 // ---------------------------------------------------------------------------
-// rANS encode, one lane per row
+// rANS encode, one lane per row.  A workgroup is one wave owning 64 rows; the
+// rows' (start, freq) words are staged through LDS in chunks of 64 symbols
+// (coalesced reads, next chunk in flight while the current one is coded), so
+// the serial chain per row never waits for memory.
 // ---------------------------------------------------------------------------
-__global__ void __launch_bounds__(64)
+constexpr int kRansRows = 64;
+constexpr int kRansChunk = 64;
+// Padding symbol (start 0, frequency 2^16): pushing it leaves the state unchanged
+// and never renormalises, so every chunk can be coded as a full one.
+constexpr uint32_t kRansNop = 0xFFFF0000u;
+
+// 1/f in fp64 for 1 <= f < 2^17: hardware estimate plus two Newton steps
+// (relative error ~2^-52).  Independent of the coder state, so several of these
+// are computed ahead of the serial chain.
+__device__ __forceinline__ double rans_recip(uint32_t f32) {
+    const double fd = (double)f32;
+    double rf = __builtin_amdgcn_rcp(fd);
+    rf = __builtin_fma(__builtin_fma(-fd, rf, 1.0), rf, rf);
+    rf = __builtin_fma(__builtin_fma(-fd, rf, 1.0), rf, rf);
+    return rf;
+}
+
+// x <- C(x, (start, f)) with an exact x / f for x < 2^47 * f: the fp64 quotient
+// estimate is within one of the truth, so the remainder x - q f lies in (-f, 2f)
+// and its low 32 bits decide the correction.  Branch-free.
+__device__ __forceinline__ void rans_push(uint64_t& x, uint32_t f, uint32_t start, double rf) {
+    const double xd = __builtin_fma((double)(uint32_t)(x >> 32), 4294967296.0, (double)(uint32_t)x);
+    // round(xd * rf) read off the mantissa after adding 2^52 (the quotient is below 2^47)
+    const double qd = __builtin_fma(xd, rf, 4503599627370496.0);
+    uint64_t q = (uint64_t)__double_as_longlong(qd) & 0x000FFFFFFFFFFFFFull;
+    int32_t rem = (int32_t)((uint32_t)x - (uint32_t)q * f);
+    const int32_t neg = rem < 0 ? 1 : 0, over = rem >= (int32_t)f ? 1 : 0;
+    rem += neg ? (int32_t)f : 0;
+    rem -= over ? (int32_t)f : 0;
+    q += (uint64_t)(int64_t)(over - neg);
+    x = (q << 16) + (uint64_t)((uint32_t)rem + start);
+}
+
+__global__ void __launch_bounds__(kRansRows)
 rans_rows_kernel(const uint32_t* __restrict__ sf, int W, uint32_t rows, uint32_t* __restrict__ slabs,
                  uint32_t* __restrict__ row_words) {
-    const uint32_t row = blockIdx.x * blockDim.x + threadIdx.x;
-    if (row >= rows) return;
+    __shared__ uint32_t buf[2][kRansRows][kRansChunk + 1];
+    const int lane = threadIdx.x;
+    const uint32_t row0 = blockIdx.x * kRansRows;
+    const uint32_t row = row0 + lane;
+    const uint32_t nsym = 3u * (uint32_t)W;
+    const int nchunks = (int)((nsym + kRansChunk - 1) / kRansChunk);
+    const uint32_t live_rows = min((uint32_t)kRansRows, rows - row0);
     const size_t sw = slab_words(W);
-    const uint32_t* s = sf + (size_t)row * W * 3;
-    uint32_t* slab = slabs + (size_t)row * sw;
+    uint32_t* slab = slabs + (size_t)min(row, rows - 1) * sw;
     size_t wp = sw;
     uint64_t x = kRansL;
-    for (int i = 3 * W - 1; i >= 0; --i) {
-        const uint32_t v = s[i];
-        const uint64_t start = v & 0xFFFFu, f = (uint64_t)(v >> 16) + 1u;
-        if (x >= (f << 47)) { slab[--wp] = (uint32_t)x; x >>= 32; }
-        // exact x / f for x < 2^47 * f <= 2^64: fp64 estimate (error < 1) and one correction
-        const double rf = 1.0 / (double)f;
-        uint64_t q = (uint64_t)((double)x * rf);
-        int64_t rem = (int64_t)(x - q * f);
-        if (rem < 0) { q -= 1; rem += (int64_t)f; }
-        else if (rem >= (int64_t)f) { q += 1; rem -= (int64_t)f; }
-        x = (q << 16) + (uint64_t)rem + start;
+
+    uint32_t pre[kRansRows];   // chunk being fetched: element r is symbol k*64 + lane of row row0 + r
+    auto fetch = [&](int k) {
+        const uint32_t idx = (uint32_t)k * kRansChunk + lane;
+#pragma unroll
+        for (int r = 0; r < kRansRows; ++r)
+            pre[r] = ((uint32_t)r < live_rows && idx < nsym) ? sf[(size_t)(row0 + r) * nsym + idx] : kRansNop;
+    };
+    auto stage = [&](int b) {
+#pragma unroll
+        for (int r = 0; r < kRansRows; ++r) buf[b][r][lane] = pre[r];
+    };
+    fetch(nchunks - 1);
+    stage((nchunks - 1) & 1);
+    __syncthreads();
+    for (int k = nchunks - 1; k >= 0; --k) {
+        if (k > 0) fetch(k - 1);
+        if (row < rows) {
+            constexpr int kU = 8;   // reciprocals of the next 8 symbols are computed side by side
+            for (int i0 = kRansChunk; i0 > 0; i0 -= kU) {
+                uint32_t v[kU];
+                double rf[kU];
+#pragma unroll
+                for (int u = 0; u < kU; ++u) {
+                    v[u] = buf[k & 1][lane][i0 - 1 - u];
+                    rf[u] = rans_recip((v[u] >> 16) + 1u);
+                }
+                // scheduling only: the eight reciprocals are finished before the serial chain starts
+                asm volatile("" : "+v"(rf[0]), "+v"(rf[1]), "+v"(rf[2]), "+v"(rf[3]), "+v"(rf[4]), "+v"(rf[5]), "+v"(rf[6]), "+v"(rf[7]));
+#pragma unroll
+                for (int u = 0; u < kU; ++u) {
+                    const uint32_t start = v[u] & 0xFFFFu, f = (v[u] >> 16) + 1u;
+                    // renormalise when x >= f * 2^47; the word is stored either way and only
+                    // kept (wp moves) when it was due: no branch on the serial chain
+                    const bool emit = (uint32_t)(x >> 47) >= f;
+                    slab[wp - 1] = (uint32_t)x;
+                    wp -= emit ? 1 : 0;
+                    x = emit ? (x >> 32) : x;
+                    rans_push(x, f, start, rf[u]);
+                }
+            }
+        }
+        if (k > 0) stage((k - 1) & 1);
+        __syncthreads();
     }
-    slab[--wp] = (uint32_t)(x >> 32);
-    slab[--wp] = (uint32_t)x;
-    row_words[row] = (uint32_t)(sw - wp);
+    if (row < rows) {
+        slab[--wp] = (uint32_t)(x >> 32);
+        slab[--wp] = (uint32_t)x;
+        row_words[row] = (uint32_t)(sw - wp);
+    }
 }
 
 // Single workgroup: offsets[k] = 4 * sum_{j<k} row_words[j]; header; total size.
@@ -1065,7 +1140,8 @@ int pcc_encode(pcc_ctx* ctx, const uint8_t* d_img, int n, int H, int W, uint8_t*
     if (rc != PCC_OK) return rc;
     prof_end(ctx, PCC_T_ENCODE_PIXELS, st);
     prof_begin(ctx, PCC_T_ENCODE_RANS, st);
-    hipLaunchKernelGGL(rans_rows_kernel, dim3((rows + 63) / 64), dim3(64), 0, st, d_sf, W, rows, d_slabs, d_rw);
+    hipLaunchKernelGGL(rans_rows_kernel, dim3((rows + kRansRows - 1) / kRansRows), dim3(kRansRows), 0, st, d_sf, W, rows,
+                       d_slabs, d_rw);
     prof_end(ctx, PCC_T_ENCODE_RANS, st);
     prof_begin(ctx, PCC_T_ENCODE_SCAN, st);
     hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), 0, st, d_rw, rows, n, H, W, d_stream, ctx->d_total);
