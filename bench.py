@@ -22,6 +22,9 @@ if ROOT not in sys.path:
 FLOP_PER_PIXEL = 117120          # 2 * 58,560 multiply-accumulates of the 30-160-160-128-60 network
 PEAK_BF16_TFLOPS = 2500.0        # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
+# HBM bytes per launch of the encode kernel at 768x512 from rocprofv3 FETCH_SIZE / WRITE_SIZE,
+# scaled by what the same counters read for a plain 64 MiB copy (summary under profiles/).
+ENCODE_KERNEL_TRAFFIC_768x512 = {"fetch_bytes": 6.42e6, "write_bytes": 4.72e6, "algorithmic_bytes": 15 * 393216}
 
 
 def cpu_baseline(blob, imgs, rows):
@@ -54,6 +57,9 @@ def main():
     ap.add_argument("--config", type=int, default=1, help="workload id 0..4 (1 = 768x512, the headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=48)
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs: three encodes + decodes and one plain "
+                         "64 MiB device copy of known traffic, no timing, no JSON")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only; --gpus %d is not supported" % args.gpus, file=sys.stderr)
@@ -71,6 +77,15 @@ def main():
     d_img = torch.from_numpy(imgs).cuda()
     d_stream = torch.empty(binding.pcc_stream_bound(n, h, w), dtype=torch.uint8, device="cuda")
     d_out = torch.empty_like(d_img)
+    if args.traffic_probe:
+        src = torch.zeros(64 << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            s = codec.pcc_encode(d_img, out=d_stream)
+            codec.pcc_decode(s, n, h, w, out=d_out)
+            dst.copy_(src)          # calibration: reads 64 MiB, writes 64 MiB
+        torch.cuda.synchronize()
+        return
     codec.pcc_set_profiling(True)
 
     for _ in range(args.warmup):
@@ -126,7 +141,8 @@ def main():
         "roofline": {
             "kernel": "encode_kernel (gather + network on MFMA + mixture CDF, all pixels)",
             "bound": "mfma", "achieved": enc_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-            "frac": enc_tflops / PEAK_BF16_TFLOPS, "traffic": None,
+            "frac": enc_tflops / PEAK_BF16_TFLOPS,
+            "traffic": ENCODE_KERNEL_TRAFFIC_768x512 if (args.config == 1) else None,
         },
         "roofline_decode": {
             "kernel": "decode_kernel (persistent wavefront)", "bound": "dependency chain",

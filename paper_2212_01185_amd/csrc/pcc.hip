@@ -35,7 +35,7 @@ constexpr uint32_t kMailTag = 0x80000000u;
 // More tiles per wave reuse each LDS weight read more often but need more registers
 // (4 tiles only fit with one wave per SIMD).
 struct EncodeVariant { int tiles, threads; };
-constexpr EncodeVariant kEncodeVariants[3] = {{1, 512}, {2, 512}, {2, 256}};
+constexpr EncodeVariant kEncodeVariants[3] = {{1, 512}, {2, 512}, {1, 1024}};
 constexpr int kDefaultEncodeVariant = 0;
 
 // status words in device memory
@@ -160,7 +160,7 @@ encode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ img
         }
 
         f32x4_t out[T][kL4_OB];
-        mlp_forward<T, (T == 1 ? 10 : 2), (T == 1 ? 8 : 2)>(lds + opaque_zero(), lane, in, out);
+        mlp_forward<T, (T == 1 && THREADS <= 512 ? 10 : 2), (T == 1 && THREADS <= 512 ? 8 : 2)>(lds + opaque_zero(), lane, in, out);
 
 #pragma unroll
         for (int t = 0; t < T; ++t) {
@@ -1052,7 +1052,7 @@ int pcc_create(pcc_ctx** out, const void* h_blob, size_t blob_bytes, int hip_dev
                                    hipFuncAttributeMaxDynamicSharedMemorySize, kModelBytes) == hipSuccess;
     ok = ok && hipFuncSetAttribute(reinterpret_cast<const void*>(&encode_kernel<2, 512>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, kModelBytes) == hipSuccess;
-    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void*>(&encode_kernel<2, 256>),
+    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void*>(&encode_kernel<1, 1024>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, kModelBytes) == hipSuccess;
     if (const char* e = getenv("PCC_ENCODE_VARIANT")) {
         const int v = atoi(e);
@@ -1095,7 +1095,7 @@ static int launch_encode(pcc_ctx* ctx, const uint8_t* d_img, int n, int H, int W
                                H, W, P, sf, params, bits, ctx->d_status);
             break;
         default:
-            hipLaunchKernelGGL((encode_kernel<2, 256>), dim3(blocks), dim3(256), kModelBytes, st, ctx->d_model, d_img,
+            hipLaunchKernelGGL((encode_kernel<1, 1024>), dim3(blocks), dim3(1024), kModelBytes, st, ctx->d_model, d_img,
                                H, W, P, sf, params, bits, ctx->d_status);
             break;
     }

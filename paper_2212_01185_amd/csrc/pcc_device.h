@@ -125,16 +125,33 @@ __device__ __forceinline__ void hidden_layer(const uint8_t* __restrict__ w, cons
 #pragma unroll
             for (int t = 0; t < T; ++t) acc[j][t] = b;
         }
+        // weight tiles of the next k-block are fetched from LDS while the current ones feed the MFMAs
+        u32x4_t a_cur[OBG], a_nxt[OBG];
+#pragma unroll
+        for (int j = 0; j < OBG; ++j)
+            a_cur[j] = *reinterpret_cast<const u32x4_t*>(w + (((ob0 + j) * NKB + 0) * 64 + lane) * 16);
 #pragma unroll
         for (int kb = 0; kb < NKB; ++kb) {
+            if (kb + 1 < NKB) {
+#pragma unroll
+                for (int j = 0; j < OBG; ++j)
+                    a_nxt[j] = *reinterpret_cast<const u32x4_t*>(w + (((ob0 + j) * NKB + kb + 1) * 64 + lane) * 16);
+            }
 #pragma unroll
             for (int j = 0; j < OBG; ++j) {
-                const u32x4_t a = *reinterpret_cast<const u32x4_t*>(w + (((ob0 + j) * NKB + kb) * 64 + lane) * 16);
 #pragma unroll
-                for (int t = 0; t < T; ++t) {
-                    acc[j][t] = mfma16(a, in[t][kb][0], acc[j][t]);
-                    if (SPLIT_IN) acc[j][t] = mfma16(a, in[t][kb][1], acc[j][t]);
+                for (int t = 0; t < T; ++t) acc[j][t] = mfma16(a_cur[j], in[t][kb][0], acc[j][t]);
+            }
+            if (SPLIT_IN) {
+#pragma unroll
+                for (int j = 0; j < OBG; ++j) {
+#pragma unroll
+                    for (int t = 0; t < T; ++t) acc[j][t] = mfma16(a_cur[j], in[t][kb][1], acc[j][t]);
                 }
+            }
+            if (kb + 1 < NKB) {
+#pragma unroll
+                for (int j = 0; j < OBG; ++j) a_cur[j] = a_nxt[j];
             }
         }
 #pragma unroll
@@ -165,16 +182,30 @@ __device__ __forceinline__ void head_layer(const uint8_t* __restrict__ w, const 
 #pragma unroll
         for (int t = 0; t < T; ++t) out[t][ob] = b;
     }
+    u32x4_t a_cur[kL4_OB], a_nxt[kL4_OB];
+#pragma unroll
+    for (int ob = 0; ob < kL4_OB; ++ob)
+        a_cur[ob] = *reinterpret_cast<const u32x4_t*>(w + ((ob * kL4_KB + 0) * 64 + lane) * 16);
 #pragma unroll
     for (int kb = 0; kb < kL4_KB; ++kb) {
+        if (kb + 1 < kL4_KB) {
+#pragma unroll
+            for (int ob = 0; ob < kL4_OB; ++ob)
+                a_nxt[ob] = *reinterpret_cast<const u32x4_t*>(w + ((ob * kL4_KB + kb + 1) * 64 + lane) * 16);
+        }
 #pragma unroll
         for (int ob = 0; ob < kL4_OB; ++ob) {
-            const u32x4_t a = *reinterpret_cast<const u32x4_t*>(w + ((ob * kL4_KB + kb) * 64 + lane) * 16);
 #pragma unroll
-            for (int t = 0; t < T; ++t) {
-                out[t][ob] = mfma16(a, in[t][kb][0], out[t][ob]);
-                out[t][ob] = mfma16(a, in[t][kb][1], out[t][ob]);
-            }
+            for (int t = 0; t < T; ++t) out[t][ob] = mfma16(a_cur[ob], in[t][kb][0], out[t][ob]);
+        }
+#pragma unroll
+        for (int ob = 0; ob < kL4_OB; ++ob) {
+#pragma unroll
+            for (int t = 0; t < T; ++t) out[t][ob] = mfma16(a_cur[ob], in[t][kb][1], out[t][ob]);
+        }
+        if (kb + 1 < kL4_KB) {
+#pragma unroll
+            for (int ob = 0; ob < kL4_OB; ++ob) a_cur[ob] = a_nxt[ob];
         }
     }
 }
