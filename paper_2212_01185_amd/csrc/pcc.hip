@@ -36,7 +36,7 @@ constexpr uint32_t kMailTag = 0x80000000u;
 // (4 tiles only fit with one wave per SIMD).
 struct EncodeVariant { int tiles, threads; };
 constexpr EncodeVariant kEncodeVariants[3] = {{1, 512}, {2, 512}, {1, 1024}};
-constexpr int kDefaultEncodeVariant = 0;
+constexpr int kDefaultEncodeVariant = 1;
 
 // status words in device memory
 enum { kStErr = 0, kStAbort = 1, kStTicket = 2, kStWords = 4 };
@@ -126,12 +126,14 @@ encode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ img
     for (uint32_t grp = blockIdx.x * nwaves + wave; grp < groups; grp += gridDim.x * nwaves) {
         u32x4_t in[T][1][2];
         uint32_t pix[T];   // the pixel's own bytes r | g<<8 | b<<16
+        // This lane's eight first-layer inputs are two runs of four consecutive image bytes:
+        // (row offset, byte offset within the 12-byte window of columns c-2..c+1).
+        const int drA = (g < 2) ? -2 : -1, offA = (g & 1) ? 8 : 0;
+        const int drB = (g == 0) ? -2 : (g == 2 ? -1 : 0), offB = (g == 1) ? 0 : 4;
 #pragma unroll
         for (int t = 0; t < T; ++t) {
             const uint32_t p = grp * (16 * T) + 16 * t + nl;
-            uint32_t slots[8];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) slots[i] = 0;
+            uint32_t runA = 0, runB = 0;
             pix[t] = 0;
             if (p < P) {
                 const uint32_t rowg = p / (uint32_t)W;
@@ -139,23 +141,40 @@ encode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ img
                 const uint32_t im = rowg / (uint32_t)H;
                 const int r = (int)(rowg - im * (uint32_t)H);
                 const uint8_t* base = img + (size_t)im * H * W * 3;
-                const uint8_t* me = base + ((size_t)r * W + c) * 3;
-                pix[t] = (uint32_t)me[0] | ((uint32_t)me[1] << 8) | ((uint32_t)me[2] << 16);
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    int dr, b;
-                    bool used;
-                    slot_source(g, i, dr, b, used);
-                    const int rr = r + dr;
-                    const int cc = c - 2 + ((b * 11) >> 5);
-                    if (used && rr >= 0 && cc >= 0 && cc < W)
-                        slots[i] = byte_to_bf16(base[((size_t)rr * W + (c - 2)) * 3 + b]);
+                const int me = (r * W + c) * 3;
+                if (p + 1 < P) {
+                    uint32_t v;
+                    __builtin_memcpy(&v, base + me, 4);       // unaligned dword; the fourth byte is the next pixel's
+                    pix[t] = v & 0xFFFFFFu;
+                } else {
+                    pix[t] = (uint32_t)base[me] | ((uint32_t)base[me + 1] << 8) | ((uint32_t)base[me + 2] << 16);
                 }
+                // a run is read with one load when all its bytes lie in the image, byte by byte at the borders
+                auto load_run = [&](int dr, int off) -> uint32_t {
+                    const int rr = r + dr;
+                    const int col0 = c - 2 + (off >> 2);          // the run touches columns col0 and col0 + 1
+                    const int at = (rr * W + (c - 2)) * 3 + off;
+                    uint32_t v = 0;
+                    if (rr >= 0 && col0 >= 0 && col0 + 1 < W) {
+                        __builtin_memcpy(&v, base + at, 4);
+                    } else if (rr >= 0) {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const int col = c - 2 + (((off + i) * 11) >> 5);
+                            if (col >= 0 && col < W) v |= (uint32_t)base[at + i] << (8 * i);
+                        }
+                    }
+                    return v;
+                };
+                runA = load_run(drA, offA);
+                runB = load_run(drB, offB);
             }
-            in[t][0][0].x = slots[0] | (slots[1] << 16);
-            in[t][0][0].y = slots[2] | (slots[3] << 16);
-            in[t][0][0].z = slots[4] | (slots[5] << 16);
-            in[t][0][0].w = slots[6] | (slots[7] << 16);
+            // bytes -> bf16 (exact): the upper halves of the fp32 conversions, packed in pairs
+            const uint32_t sel = 0x07060302u;
+            in[t][0][0].x = __builtin_amdgcn_perm(__float_as_uint((float)((runA >> 8) & 0xFFu)), __float_as_uint((float)(runA & 0xFFu)), sel);
+            in[t][0][0].y = __builtin_amdgcn_perm(__float_as_uint((float)(runA >> 24)), __float_as_uint((float)((runA >> 16) & 0xFFu)), sel);
+            in[t][0][0].z = __builtin_amdgcn_perm(__float_as_uint((float)((runB >> 8) & 0xFFu)), __float_as_uint((float)(runB & 0xFFu)), sel);
+            in[t][0][0].w = __builtin_amdgcn_perm(__float_as_uint((float)(runB >> 24)), __float_as_uint((float)((runB >> 16) & 0xFFu)), sel);
             in[t][0][1] = in[t][0][0];   // unused (layer-1 inputs are exact)
         }
 
@@ -936,7 +955,8 @@ inline void prof_collect(pcc_ctx* ctx) {
 bool dims_ok(int n, int H, int W) {
     if (n < 1 || H < 1 || W < 1) return false;
     const uint64_t P = (uint64_t)n * H * W;
-    return P < (1ull << 31) && (uint64_t)W < (1u << 24) && (uint64_t)n * H < (1ull << 31);
+    return P < (1ull << 31) && (uint64_t)W < (1u << 24) && (uint64_t)n * H < (1ull << 31) &&
+           (uint64_t)H * W * 3 < (1ull << 31);   // byte offsets within one image are 32-bit
 }
 
 }  // namespace

@@ -119,12 +119,9 @@ __device__ __forceinline__ void hidden_layer(const uint8_t* __restrict__ w, cons
 #pragma unroll
     for (int ob0 = 0; ob0 < NOB; ob0 += OBG) {
         f32x4_t acc[OBG][T];
+        f32x4_t bv[OBG];   // the bias is the C operand of each chain's first MFMA
 #pragma unroll
-        for (int j = 0; j < OBG; ++j) {
-            const f32x4_t b = *reinterpret_cast<const f32x4_t*>(bias + 16 * (ob0 + j) + 4 * g);
-#pragma unroll
-            for (int t = 0; t < T; ++t) acc[j][t] = b;
-        }
+        for (int j = 0; j < OBG; ++j) bv[j] = *reinterpret_cast<const f32x4_t*>(bias + 16 * (ob0 + j) + 4 * g);
         // weight tiles of the next k-block are fetched from LDS while the current ones feed the MFMAs
         u32x4_t a_cur[OBG], a_nxt[OBG];
 #pragma unroll
@@ -140,7 +137,7 @@ __device__ __forceinline__ void hidden_layer(const uint8_t* __restrict__ w, cons
 #pragma unroll
             for (int j = 0; j < OBG; ++j) {
 #pragma unroll
-                for (int t = 0; t < T; ++t) acc[j][t] = mfma16(a_cur[j], in[t][kb][0], acc[j][t]);
+                for (int t = 0; t < T; ++t) acc[j][t] = mfma16(a_cur[j], in[t][kb][0], kb == 0 ? bv[j] : acc[j][t]);
             }
             if (SPLIT_IN) {
 #pragma unroll
@@ -176,12 +173,9 @@ template <int T>
 __device__ __forceinline__ void head_layer(const uint8_t* __restrict__ w, const float* __restrict__ bias, int lane,
                                            const u32x4_t (&in)[T][kL4_KB][2], f32x4_t (&out)[T][kL4_OB]) {
     const int g = lane >> 4;
+    f32x4_t bv[kL4_OB];
 #pragma unroll
-    for (int ob = 0; ob < kL4_OB; ++ob) {
-        const f32x4_t b = *reinterpret_cast<const f32x4_t*>(bias + 16 * ob + 4 * g);
-#pragma unroll
-        for (int t = 0; t < T; ++t) out[t][ob] = b;
-    }
+    for (int ob = 0; ob < kL4_OB; ++ob) bv[ob] = *reinterpret_cast<const f32x4_t*>(bias + 16 * ob + 4 * g);
     u32x4_t a_cur[kL4_OB], a_nxt[kL4_OB];
 #pragma unroll
     for (int ob = 0; ob < kL4_OB; ++ob)
@@ -196,7 +190,7 @@ __device__ __forceinline__ void head_layer(const uint8_t* __restrict__ w, const 
 #pragma unroll
         for (int ob = 0; ob < kL4_OB; ++ob) {
 #pragma unroll
-            for (int t = 0; t < T; ++t) out[t][ob] = mfma16(a_cur[ob], in[t][kb][0], out[t][ob]);
+            for (int t = 0; t < T; ++t) out[t][ob] = mfma16(a_cur[ob], in[t][kb][0], kb == 0 ? bv[ob] : out[t][ob]);
         }
 #pragma unroll
         for (int ob = 0; ob < kL4_OB; ++ob) {
