@@ -27,14 +27,15 @@
  * "PCCW", version 1, n_layers, dims[8], K, neighbourhood size, wavefront delay
  * per row, activation id, distribution id}, then per layer W[out][in] and
  * b[out] as fp32.  This library accepts the shape 30 -> 160 -> 160 -> 128 -> 60,
- * ReLU, K = 5 Gaussian components, the 10-pixel neighbourhood {rows r-2, r-1 at
+ * ReLU, K = 5 components that are Gaussian (distribution id 0, Eq. (1)) or
+ * logistic (id 1, Eq. (8)), the 10-pixel neighbourhood {rows r-2, r-1 at
  * columns c-2..c+1; row r at c-2, c-1} and delay 2; weights must be exactly
  * representable in bf16 (biases are fp32).  Head layout o[60]: for each of
  * R,G,B: 5 mixture logits, 5 means, 5 log-sigmas (units of 1/256 of the grey
  * range); then 5 alphas, 5 betas, 5 gammas of Eq. (3)-(4).
  *
  * Stream (device memory): 8 little-endian uint32 words {magic "PCC1", version
- * 1, n, H, W, K | nbhd<<8 | delay<<16 | 16<<24, 0, 0}, uint64 offsets[n*H+1]
+ * 1, n, H, W, K | nbhd<<8 | delay<<16 | 16<<24, distribution id, 0}, uint64 offsets[n*H+1]
  * (relative to the end of that table), then one rANS payload per image row:
  * 8-byte initial decoder state, then 32-bit words in the order the decoder
  * reads them.  Streams written by this library are read by this library; the

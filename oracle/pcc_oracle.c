@@ -55,6 +55,7 @@ typedef struct {
     int K;      /* mixture components */
     int nbhd;   /* neighbourhood size in pixels */
     int delay;  /* wavefront step = delay*r + c */
+    int dist;   /* component distribution: 0 Gaussian (Eq. (1)), 1 logistic (Eq. (8)) */
     double *W[ORC_MAX_LAYERS]; /* [out][in] */
     double *b[ORC_MAX_LAYERS];
 } orc_model;
@@ -102,7 +103,8 @@ int orc_model_create(const void *blob, size_t nbytes, orc_model **out) {
     m->nbhd = (int)rd32(p + 48);
     m->delay = (int)rd32(p + 52);
     uint32_t act = rd32(p + 56), dist = rd32(p + 60);
-    if (m->K < 1 || m->K > ORC_MAX_K || m->nbhd != 10 || m->delay != 2 || act != 0 || dist != 0 ||
+    m->dist = (int)dist;
+    if (m->K < 1 || m->K > ORC_MAX_K || m->nbhd != 10 || m->delay != 2 || act != 0 || dist > 1 ||
         m->dims[0] != 3 * m->nbhd || m->dims[m->n_layers] != 12 * m->K) { free(m); return ORC_E_BLOB; }
     size_t need = 64;
     for (int l = 0; l < m->n_layers; ++l) need += 4 * ((size_t)m->dims[l] * m->dims[l + 1] + m->dims[l + 1]);
@@ -219,11 +221,12 @@ void orc_mixture(const orc_model *m, const double *o, int ch, int r, int g,
 
 /* Mixture CDF at the lower edge of bin e, i.e. at grey level e - 0.5 (Eq. (1)
  * sums pi_i [F(x+0.5) - F(x-0.5)], so the pmf of x is mixcdf(x+1) - mixcdf(x)). */
-static double mixcdf(int K, const double *pi, const double *mu, const double *sigma, int e) {
+static double mixcdf(int dist, int K, const double *pi, const double *mu, const double *sigma, int e) {
     double F = 0.0;
     for (int k = 0; k < K; ++k) {
         double z = ((e - 0.5) / 256.0 - mu[k]) / sigma[k];
-        F += pi[k] * 0.5 * erfc(-z / sqrt(2.0));
+        /* standard normal CDF, or the logistic CDF of Eq. (8) with scale s = sigma */
+        F += pi[k] * (dist == 0 ? 0.5 * erfc(-z / sqrt(2.0)) : 1.0 / (1.0 + exp(-z)));
     }
     return F;
 }
@@ -234,10 +237,10 @@ static double mixcdf(int K, const double *pi, const double *mu, const double *si
  *                                                    take the mass beyond the range)
  *   Cq(e) = e + min(floor(F(e) * 65280), 65280)      for 1 <= e <= 255
  * so every symbol has frequency >= 1 whenever F is non-decreasing in e. */
-static uint32_t cq_at(int K, const double *pi, const double *mu, const double *sigma, int e) {
+static uint32_t cq_at(int dist, int K, const double *pi, const double *mu, const double *sigma, int e) {
     if (e <= 0) return 0;
     if (e >= 256) return 65536;
-    double v = floor(mixcdf(K, pi, mu, sigma, e) * 65280.0);
+    double v = floor(mixcdf(dist, K, pi, mu, sigma, e) * 65280.0);
     if (v > 65280.0) v = 65280.0;
     if (v < 0.0) v = 0.0;
     return (uint32_t)e + (uint32_t)v;
@@ -248,7 +251,7 @@ static uint32_t cq_at(int K, const double *pi, const double *mu, const double *s
 int orc_cdf_table(const orc_model *m, const double *o, int ch, int r, int g, uint32_t *cq) {
     double pi[ORC_MAX_K], mu[ORC_MAX_K], sigma[ORC_MAX_K];
     orc_mixture(m, o, ch, r, g, pi, mu, sigma);
-    for (int e = 0; e <= 256; ++e) cq[e] = cq_at(m->K, pi, mu, sigma, e);
+    for (int e = 0; e <= 256; ++e) cq[e] = cq_at(m->dist, m->K, pi, mu, sigma, e);
     for (int e = 0; e < 256; ++e) if (cq[e + 1] <= cq[e]) return ORC_E_INTERNAL;
     return ORC_OK;
 }
@@ -258,7 +261,7 @@ static void sym_interval(const orc_model *m, const double *o, int ch, int r, int
                          uint32_t *start, uint32_t *freq) {
     double pi[ORC_MAX_K], mu[ORC_MAX_K], sigma[ORC_MAX_K];
     orc_mixture(m, o, ch, r, g, pi, mu, sigma);
-    uint32_t lo = cq_at(m->K, pi, mu, sigma, x), hi = cq_at(m->K, pi, mu, sigma, x + 1);
+    uint32_t lo = cq_at(m->dist, m->K, pi, mu, sigma, x), hi = cq_at(m->dist, m->K, pi, mu, sigma, x + 1);
     *start = lo;
     *freq = hi - lo;
 }
@@ -268,8 +271,8 @@ void orc_pmf(const orc_model *m, const double *o, int ch, int r, int g, double *
     double pi[ORC_MAX_K], mu[ORC_MAX_K], sigma[ORC_MAX_K];
     orc_mixture(m, o, ch, r, g, pi, mu, sigma);
     for (int x = 0; x < 256; ++x) {
-        double lo = x == 0 ? 0.0 : mixcdf(m->K, pi, mu, sigma, x);
-        double hi = x == 255 ? 1.0 : mixcdf(m->K, pi, mu, sigma, x + 1);
+        double lo = x == 0 ? 0.0 : mixcdf(m->dist, m->K, pi, mu, sigma, x);
+        double hi = x == 255 ? 1.0 : mixcdf(m->dist, m->K, pi, mu, sigma, x + 1);
         p256[x] = hi - lo;
     }
 }
@@ -345,7 +348,7 @@ int orc_rans_decode_tables(const uint8_t *payload, size_t nbytes, const uint32_t
 /* ------------------------------------------------------------------ container */
 
 /* Stream: 8 little-endian uint32 header words (magic "PCC1", version 1, n, H,
- * W, K | nbhd<<8 | delay<<16 | 16<<24 (CDF bits), 0, 0), then uint64
+ * W, K | nbhd<<8 | delay<<16 | 16<<24 (CDF bits), distribution id, 0), then uint64
  * offsets[n*H + 1] of the row payloads relative to the end of the offset
  * table, then the payloads back to back (each a multiple of 4 bytes). */
 #define STREAM_MAGIC 0x31434350u
@@ -377,7 +380,7 @@ int orc_encode(const orc_model *m, const uint8_t *img, int n, int H, int W, int 
     if (!start || !freq) { free(start); free(freq); return ORC_E_INTERNAL; }
     wr32(stream, STREAM_MAGIC); wr32(stream + 4, 1); wr32(stream + 8, (uint32_t)n);
     wr32(stream + 12, (uint32_t)H); wr32(stream + 16, (uint32_t)W); wr32(stream + 20, model_tag(m));
-    wr32(stream + 24, 0); wr32(stream + 28, 0);
+    wr32(stream + 24, (uint32_t)m->dist); wr32(stream + 28, 0);
     size_t off = 0;
     int rc = ORC_OK;
     double o[ORC_MAX_WIDTH];
@@ -425,7 +428,8 @@ int orc_decode(const orc_model *m, const uint8_t *stream, size_t nbytes, int n, 
     size_t table = STREAM_HEADER + 8 * (rows + 1);
     if (nbytes < table) return ORC_E_STREAM;
     if (rd32(stream) != STREAM_MAGIC || rd32(stream + 4) != 1 || rd32(stream + 8) != (uint32_t)n ||
-        rd32(stream + 12) != (uint32_t)H || rd32(stream + 16) != (uint32_t)W || rd32(stream + 20) != model_tag(m))
+        rd32(stream + 12) != (uint32_t)H || rd32(stream + 16) != (uint32_t)W || rd32(stream + 20) != model_tag(m) ||
+        rd32(stream + 24) != (uint32_t)m->dist)
         return ORC_E_STREAM;
     rans_dec *dec = (rans_dec *)malloc(rows * sizeof(rans_dec));
     if (!dec) return ORC_E_INTERNAL;

@@ -86,7 +86,7 @@ struct LaneHead {
     float c2[5];  // gamma (group 2)
 };
 
-__device__ __forceinline__ void lane_head_setup(const f32x4_t (&o)[kL4_OB], int lane, LaneHead& h) {
+__device__ __forceinline__ void lane_head_setup(const f32x4_t (&o)[kL4_OB], int lane, float lut_scale, LaneHead& h) {
     float v[16];
 #pragma unroll
     for (int ob = 0; ob < kL4_OB; ++ob) {
@@ -100,7 +100,7 @@ __device__ __forceinline__ void lane_head_setup(const f32x4_t (&o)[kL4_OB], int 
     float raw[15];
 #pragma unroll
     for (int s = 0; s < 15; ++s) raw[s] = v[s];
-    channel_setup(raw, h.cp);
+    channel_setup(raw, lut_scale, h.cp);
     h.c1[0] = v[15];
 #pragma unroll
     for (int k = 1; k < 5; ++k) h.c1[k] = (g == 1) ? x3[k - 1] : x3[3 + k];
@@ -119,6 +119,7 @@ encode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ img
     copy_model_to_lds(lds, model);
     __syncthreads();
     const float2* lut = reinterpret_cast<const float2*>(lds + kLutOff);
+    const float lut_scale = *reinterpret_cast<const float*>(lds + kLutScaleOff);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
     const int g = lane >> 4, nl = lane & 15;
     const uint32_t groups = (P + 16 * T - 1) / (16 * T);
@@ -197,7 +198,7 @@ encode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ img
                 }
             }
             LaneHead h;
-            lane_head_setup(out[t], lane, h);
+            lane_head_setup(out[t], lane, lut_scale, h);
             const float rhat = (float)(pix[t] & 0xFF) * (1.0f / 256.0f);
             const float ghat = (float)((pix[t] >> 8) & 0xFF) * (1.0f / 256.0f);
             if (g == 1) couple_green(h.cp, h.c1, rhat);
@@ -324,8 +325,8 @@ rans_rows_kernel(const uint32_t* __restrict__ sf, int W, uint32_t rows, uint32_t
 
 // Single workgroup: offsets[k] = 4 * sum_{j<k} row_words[j]; header; total size.
 __global__ void __launch_bounds__(1024)
-scan_kernel(const uint32_t* __restrict__ row_words, uint32_t rows, int n, int H, int W, uint8_t* __restrict__ stream,
-            uint64_t* __restrict__ total_bytes) {
+scan_kernel(const uint32_t* __restrict__ row_words, uint32_t rows, int n, int H, int W, uint32_t dist,
+            uint8_t* __restrict__ stream, uint64_t* __restrict__ total_bytes) {
     __shared__ uint64_t part[1024];
     __shared__ uint64_t carry;
     uint64_t* offsets = reinterpret_cast<uint64_t*>(stream + kStreamHeader);
@@ -333,7 +334,7 @@ scan_kernel(const uint32_t* __restrict__ row_words, uint32_t rows, int n, int H,
         carry = 0;
         uint32_t* hdr = reinterpret_cast<uint32_t*>(stream);
         hdr[0] = kStreamMagic; hdr[1] = 1; hdr[2] = (uint32_t)n; hdr[3] = (uint32_t)H; hdr[4] = (uint32_t)W;
-        hdr[5] = kModelTag; hdr[6] = 0; hdr[7] = 0;
+        hdr[5] = kModelTag; hdr[6] = dist; hdr[7] = 0;
     }
     __syncthreads();
     for (uint32_t base = 0; base < rows; base += 1024) {
@@ -563,7 +564,8 @@ __device__ __forceinline__ int group_search(const ChanParams& cp, uint32_t slot,
 
 __global__ void __launch_bounds__(kDecThreads)
 decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ stream, uint64_t nbytes, int n, int H,
-              int W, int nbands, uint8_t* __restrict__ img_out, uint32_t* mailbox, int* status, uint32_t spin_limit) {
+              int W, int nbands, uint32_t dist, uint8_t* __restrict__ img_out, uint32_t* mailbox, int* status,
+              uint32_t spin_limit) {
     extern __shared__ __align__(16) uint8_t lds[];
     float2* lut = reinterpret_cast<float2*>(lds + kDLutOff);
     uint8_t* act0 = lds + kDAct0Off;
@@ -602,6 +604,7 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
     const int ticket = misc[0];
     const int im = ticket / nbands, band = ticket - im * nbands;
     if (im >= n) return;
+    const float lut_scale = *reinterpret_cast<const float*>(model + kLutScaleOff);
 
     const int r0 = band * kBandRows;
     const uint64_t rows_total = (uint64_t)n * H;
@@ -612,7 +615,7 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
         const uint32_t* hdr = reinterpret_cast<const uint32_t*>(stream);
         const uint64_t last = reinterpret_cast<const uint64_t*>(stream + kStreamHeader)[rows_total];
         if (hdr[0] != kStreamMagic || hdr[1] != 1u || hdr[2] != (uint32_t)n || hdr[3] != (uint32_t)H ||
-            hdr[4] != (uint32_t)W || hdr[5] != kModelTag || last != payload_bytes)
+            hdr[4] != (uint32_t)W || hdr[5] != kModelTag || hdr[6] != dist || last != payload_bytes)
             set_error(status, PCC_E_STREAM);
     }
 
@@ -752,7 +755,7 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
             const f32x4_t v0 = src[0], v1 = src[1], v2 = src[2], v3 = src[3];
             const float raw[15] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w, v2.x, v2.y, v2.z, v2.w, v3.x, v3.y, v3.z};
             ChanParams all;
-            channel_setup(raw, all);
+            channel_setup(raw, lut_scale, all);
             float pk = all.pi[0], mk = all.mu[0], ak = all.a[0];
 #pragma unroll
             for (int kk = 1; kk < 5; ++kk) if (k == kk) { pk = all.pi[kk]; mk = all.mu[kk]; ak = all.a[kk]; }
@@ -859,7 +862,7 @@ cdf_tables_kernel(const uint8_t* __restrict__ model, const float* __restrict__ p
     float raw[15];
     for (int s = 0; s < 15; ++s) raw[s] = o[15 * ch + s];
     ChanParams cp;
-    channel_setup(raw, cp);
+    channel_setup(raw, *reinterpret_cast<const float*>(model + kLutScaleOff), cp);
     const float rhat = (float)rg[2 * p] * (1.0f / 256.0f), ghat = (float)rg[2 * p + 1] * (1.0f / 256.0f);
     float c1[5], c2[5];
     for (int k = 0; k < 5; ++k) { c1[k] = ch == 1 ? o[45 + k] : o[50 + k]; c2[k] = o[55 + k]; }
@@ -889,6 +892,7 @@ struct pcc_ctx {
     uint32_t* d_sf = nullptr;
     size_t sf_count = 0;
     int num_cus = 0;
+    uint32_t dist = 0;             // written to / checked against stream header word 6
     int encode_variant = kDefaultEncodeVariant;
     // optional per-kernel timing
     bool profiling = false;
@@ -992,7 +996,8 @@ int pcc_create(pcc_ctx** out, const void* h_blob, size_t blob_bytes, int hip_dev
     static const int dims[5] = {30, 160, 160, 128, 60};
     if (blob_bytes < 64 || rd32(p) != kBlobMagic || rd32(p + 4) != 1u || rd32(p + 8) != 4u) return PCC_E_BLOB;
     for (int i = 0; i < 5; ++i) if (rd32(p + 12 + 4 * i) != (uint32_t)dims[i]) return PCC_E_BLOB;
-    if (rd32(p + 44) != 5u || rd32(p + 48) != 10u || rd32(p + 52) != 2u || rd32(p + 56) != 0u || rd32(p + 60) != 0u)
+    const uint32_t dist = rd32(p + 60);   // 0 = Gaussian mixture (Eq. (1)), 1 = logistic mixture (Eq. (8))
+    if (rd32(p + 44) != 5u || rd32(p + 48) != 10u || rd32(p + 52) != 2u || rd32(p + 56) != 0u || dist > 1u)
         return PCC_E_BLOB;
     size_t need = 64;
     for (int l = 0; l < 4; ++l) need += 4 * ((size_t)dims[l] * dims[l + 1] + dims[l + 1]);
@@ -1041,13 +1046,18 @@ int pcc_create(pcc_ctx** out, const void* h_blob, size_t blob_bytes, int hip_dev
             b[s] = (o >= 0 && o < dims[l + 1]) ? Bat(l, o) : 0.0f;
         }
     }
-    // Normal CDF table in units of 2^-24 so that forward differences are exact in fp32.
+    // Component CDF table in units of 2^-24 so that forward differences are exact in fp32.
     float* lut = reinterpret_cast<float*>(image.data() + kLutOff);
+    const double lut_scale = dist == 0 ? (double)kLutScaleGaussian : (double)kLutScaleLogistic;
+    *reinterpret_cast<float*>(image.data() + kLutScaleOff) = (float)lut_scale;
     std::vector<double> tq(kLutEntries + 1);
     for (int i = 0; i < kLutEntries; ++i) {
-        const double z = (i - 768) / 128.0;
-        tq[i] = nearbyint(0.5 * erfc(-z / sqrt(2.0)) * 16777216.0);
+        const double z = (i - 768) / lut_scale;
+        const double F = dist == 0 ? 0.5 * erfc(-z / sqrt(2.0)) : 1.0 / (1.0 + exp(-z));
+        tq[i] = nearbyint(F * 16777216.0);
     }
+    tq[0] = 0.0;
+    tq[kLutEntries - 1] = 16777216.0;
     tq[kLutEntries] = tq[kLutEntries - 1];
     for (int i = 0; i < kLutEntries; ++i) {
         lut[2 * i] = (float)(tq[i] / 16777216.0);
@@ -1061,6 +1071,7 @@ int pcc_create(pcc_ctx** out, const void* h_blob, size_t blob_bytes, int hip_dev
     pcc_ctx* ctx = new (std::nothrow) pcc_ctx();
     if (!ctx) return PCC_E_INTERNAL;
     ctx->device = hip_device;
+    ctx->dist = dist;
     hipDeviceProp_t prop;
     bool ok = hipGetDeviceProperties(&prop, hip_device) == hipSuccess;
     if (ok) ctx->num_cus = prop.multiProcessorCount;
@@ -1164,7 +1175,7 @@ int pcc_encode(pcc_ctx* ctx, const uint8_t* d_img, int n, int H, int W, uint8_t*
                        d_slabs, d_rw);
     prof_end(ctx, PCC_T_ENCODE_RANS, st);
     prof_begin(ctx, PCC_T_ENCODE_SCAN, st);
-    hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), 0, st, d_rw, rows, n, H, W, d_stream, ctx->d_total);
+    hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), 0, st, d_rw, rows, n, H, W, ctx->dist, d_stream, ctx->d_total);
     prof_end(ctx, PCC_T_ENCODE_SCAN, st);
     prof_begin(ctx, PCC_T_ENCODE_COMPACT, st);
     hipLaunchKernelGGL(compact_kernel, dim3(rows), dim3(64), 0, st, d_slabs, d_rw, W, rows, d_stream,
@@ -1205,7 +1216,7 @@ int pcc_decode(pcc_ctx* ctx, const uint8_t* d_stream, size_t nbytes, int n, int 
     prof_reset(ctx);
     prof_begin(ctx, PCC_T_DECODE, st);
     hipLaunchKernelGGL(decode_kernel, dim3((uint32_t)(n * nbands)), dim3(kDecThreads), kDecLdsBytes, st, ctx->d_model,
-                       d_stream, (uint64_t)nbytes, n, H, W, nbands, d_img_out, d_mail, ctx->d_status, spin_limit);
+                       d_stream, (uint64_t)nbytes, n, H, W, nbands, ctx->dist, d_img_out, d_mail, ctx->d_status, spin_limit);
     prof_end(ctx, PCC_T_DECODE, st);
     if (hipGetLastError() != hipSuccess) return PCC_E_HIP;
     if (hipMemcpyAsync(ctx->h_status, ctx->d_status, kStWords * sizeof(int), hipMemcpyDeviceToHost, st) != hipSuccess)

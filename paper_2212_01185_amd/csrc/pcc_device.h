@@ -43,12 +43,16 @@ constexpr int kB2Off = kB1Off + 160 * 4;
 constexpr int kB3Off = kB2Off + 160 * 4;
 constexpr int kB4Off = kB3Off + 128 * 4;
 constexpr int kLutOff = kB4Off + 64 * 4;
-// Normal-CDF table: Phi at z = (i - 768)/128, i = 0..1536, as (value, forward difference).
+// CDF table of the mixture's component distribution: F at z = (i - 768)/scale,
+// i = 0..1536, as (value, forward difference).  scale = 128 for the Gaussian
+// (|z| <= 6), 44 for the logistic of Eq. (8) (|z| <= 17.45, heavier tails).
 constexpr int kLutEntries = 1537;
-constexpr float kLutScale = 128.0f;
+constexpr float kLutScaleGaussian = 128.0f;
+constexpr float kLutScaleLogistic = 44.0f;
 constexpr float kLutBias = 768.0f;
 constexpr float kLutMax = 1536.0f;
-constexpr int kModelBytes = kLutOff + (kLutEntries + 1) * 8;  // 133,136 (multiple of 16)
+constexpr int kLutScaleOff = kLutOff + (kLutEntries + 1) * 8;  // one float: table steps per unit of z
+constexpr int kModelBytes = kLutScaleOff + 16;                // 133,152 (multiple of 16)
 static_assert(kWeightBytes == 118784, "weight image size");
 static_assert(kModelBytes % 16 == 0, "model image must be copyable in 16-byte pieces");
 
@@ -225,13 +229,13 @@ __device__ __forceinline__ void mlp_forward(const uint8_t* __restrict__ model, i
 struct ChanParams {
     float pi[5];   // mixture weights, softmax of the logits
     float mu[5];   // means, units of 1/256 of the grey range
-    float a[5];    // 128 / sigma: table steps per unit of (edge - mu)
+    float a[5];    // table scale / sigma: table steps per unit of (edge - mu)
 };
 
 constexpr float kLog2e = 1.4426950408889634f;
 
 // raw[0..4] logits, raw[5..9] means, raw[10..14] log-sigmas of one channel.
-__device__ __forceinline__ void channel_setup(const float (&raw)[15], ChanParams& cp) {
+__device__ __forceinline__ void channel_setup(const float (&raw)[15], float lut_scale, ChanParams& cp) {
     float m = raw[0];
 #pragma unroll
     for (int k = 1; k < 5; ++k) m = fmaxf(m, raw[k]);
@@ -245,7 +249,7 @@ __device__ __forceinline__ void channel_setup(const float (&raw)[15], ChanParams
         cp.pi[k] = e[k] * inv;
         cp.mu[k] = raw[5 + k];
         const float ls = fminf(fmaxf(raw[10 + k], -8.0f), 4.0f);   // sigma = exp(clamp(log sigma, -8, 4))
-        cp.a[k] = __builtin_amdgcn_exp2f(-(ls * kLog2e)) * kLutScale;
+        cp.a[k] = __builtin_amdgcn_exp2f(-(ls * kLog2e)) * lut_scale;
     }
 }
 
@@ -262,7 +266,7 @@ __device__ __forceinline__ void couple_blue(ChanParams& cp, const float (&beta)[
 
 // Integer CDF at the lower edge of bin e (grey level e - 0.5), 1 <= e <= 255:
 //   Cq(e) = e + min(floor(65280 * sum_k pi_k Phi(z_k)), 65280),  z_k = ((e-0.5)/256 - mu_k) / sigma_k.
-// Phi is a table with linear interpolation at coordinate t = 128 z + 768,
+// F (Phi, or the logistic CDF) is a table with linear interpolation at coordinate t = scale * z + 768,
 // clamped to the table.  Entries are multiples of 2^-24 and the stored forward
 // differences are exact, so one fma per lookup is non-decreasing in z; with
 // pi_k >= 0 every later step (fma, floor) keeps that, hence Cq is strictly

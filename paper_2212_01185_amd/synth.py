@@ -181,9 +181,9 @@ def pack_blob(layers, k=DEFAULT_K, nbhd=DEFAULT_NBHD, delay=DEFAULT_DELAY,
     return b"".join(out)
 
 
-def make_blob(seed: int = 0, sharp: bool = False) -> bytes:
+def make_blob(seed: int = 0, sharp: bool = False, dist: int = DIST_GAUSSIAN) -> bytes:
     """The weight blob every workload uses (seed 0, default shape)."""
-    return pack_blob(make_weights(seed, DEFAULT_DIMS, sharp=sharp))
+    return pack_blob(make_weights(seed, DEFAULT_DIMS, sharp=sharp), dist=dist)
 
 
 def param_count(dims) -> int:

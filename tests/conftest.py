@@ -34,3 +34,15 @@ def orc(blob):
 def orc_sharp(sharp_blob):
     from oracle import pcc_oracle
     return pcc_oracle.Oracle(sharp_blob)
+
+
+@pytest.fixture(scope="session")
+def logistic_blob():
+    from paper_2212_01185_amd import synth
+    return synth.make_blob(0, dist=synth.DIST_LOGISTIC)
+
+
+@pytest.fixture(scope="session")
+def orc_logistic(logistic_blob):
+    from oracle import pcc_oracle
+    return pcc_oracle.Oracle(logistic_blob)

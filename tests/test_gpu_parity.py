@@ -38,6 +38,14 @@ def codec(blob):
 
 
 @pytest.fixture(scope="module")
+def codec_logistic(logistic_blob):
+    from paper_2212_01185_amd import binding
+    c = binding.Codec(logistic_blob, 0)
+    yield c
+    c.close()
+
+
+@pytest.fixture(scope="module")
 def codec_sharp(sharp_blob):
     from paper_2212_01185_amd import binding
     c = binding.Codec(sharp_blob, 0)
@@ -109,14 +117,14 @@ def test_roundtrip_config0_and_stream_length(codec, orc):
 
 # ----------------------------------------------------------------- integer work, bit exact
 
-def _expected_stream(imgs_shape, intervals):
+def _expected_stream(imgs_shape, intervals, dist=0):
     """Assemble the container from oracle-coded rows of the given (start, freq) pairs."""
     n, h, w, _ = imgs_shape
     sf = intervals.reshape(n * h, 3 * w).astype(np.uint32)
     payloads = [po.rans_encode(row & 0xFFFF, (row >> 16) + 1) for row in sf]
     offs = np.concatenate([[0], np.cumsum([len(p) for p in payloads])]).astype("<u8")
     tag = 5 | (10 << 8) | (2 << 16) | (16 << 24)
-    head = struct.pack("<8I", 0x31434350, 1, n, h, w, tag, 0, 0)
+    head = struct.pack("<8I", 0x31434350, 1, n, h, w, tag, dist, 0)
     return head + offs.tobytes() + b"".join(payloads)
 
 
@@ -160,6 +168,49 @@ def test_cdf_tables_against_oracle(codec, orc):
             worst = max(worst, int(np.abs(cq[i, ch] - want).max()))
     _log("max |Cq_gpu - Cq_oracle| = %d counts" % worst)
     assert worst <= CQ_ATOL
+
+
+# ----------------------------------------------------------------- logistic mixture (Eq. (8))
+
+def test_logistic_mixture(codec, codec_logistic, orc_logistic):
+    from paper_2212_01185_amd import binding
+    rng = np.random.default_rng(15)
+    heads = [rng.normal(0, s, 60) for s in (0.1, 0.5, 1.0, 3.0) for _ in range(30)]
+    for mu in (0.0, 0.5, 100.5 / 256, -3.0, 4.0):
+        for ls in (-20.0, -8.0, -4.0, 0.0, 4.0, 20.0):
+            o = np.zeros(60)
+            o[5:10] = o[20:25] = o[35:40] = mu
+            o[10:15] = o[25:30] = o[40:45] = ls
+            heads.append(o)
+    heads = np.asarray(heads, dtype=np.float32)
+    rg = rng.integers(0, 256, (len(heads), 2), dtype=np.uint8)
+    cq = codec_logistic.pcc_cdf_tables(_dev(heads), _dev(rg))
+    torch.cuda.synchronize()
+    cq = cq.cpu().numpy().astype(np.int64)
+    assert (cq[:, :, 0] == 0).all() and (cq[:, :, 256] == 65536).all() and (np.diff(cq, axis=2) >= 1).all()
+    worst = 0
+    for i, o in enumerate(heads.astype(np.float64)):
+        for ch in range(3):
+            want = orc_logistic.cdf_table(o, ch, int(rg[i, 0]), int(rg[i, 1])).astype(np.int64)
+            worst = max(worst, int(np.abs(cq[i, ch] - want).max()))
+    _log("logistic: max |Cq_gpu - Cq_oracle| = %d counts" % worst)
+    assert worst <= CQ_ATOL + 1      # coarser table step (1/44 in z) than the Gaussian's
+    # bits and round trip on the 64x64 workload
+    imgs = synth.make_batch(0)
+    _, bits = codec_logistic.pcc_encode_probs(_dev(imgs))
+    _, want = orc_logistic.encode(imgs, po.MODE_EXACT)
+    got = float(bits.double().sum().item())
+    _log("logistic bits/pixel gpu %.5f oracle %.5f" % (got / 4096, want.sum() / 4096))
+    assert abs(got / want.sum() - 1) <= BITS_RTOL
+    stream, out = _roundtrip(codec_logistic, imgs)
+    np.testing.assert_array_equal(out, imgs)
+    stream = codec_logistic.pcc_encode(_dev(imgs))       # the decode above reused the workspace
+    iv = codec_logistic.pcc_copy_intervals(1, 64, 64).cpu().numpy().view(np.uint32)
+    assert stream.cpu().numpy().tobytes() == _expected_stream(imgs.shape, iv, dist=1)
+    # the Gaussian-mixture model refuses the logistic stream
+    with pytest.raises(binding.PccError) as e:
+        codec.pcc_decode(stream, 1, 64, 64)
+    assert e.value.code == binding.PCC_E_STREAM
 
 
 # ----------------------------------------------------------------- round trips: edge shapes

@@ -269,6 +269,45 @@ def test_degenerate_sigmas(orc):
     assert f[0] > 30000 and f[255] > 30000 and f[1:255].max() <= 3
 
 
+# ----------------------------------------------------------------- logistic mixture, Eq. (8)
+
+def test_logistic_single_component_against_scipy(orc_logistic):
+    """Eq. (8): F(x; mu, s) = 1 / (1 + exp(-(x - mu)/s)), in grey-level units mu = 256 mu_hat, s = 256 sigma_hat."""
+    rng = np.random.default_rng(17)
+    for _ in range(20):
+        mu_hat, ls = rng.uniform(-0.2, 1.2), rng.uniform(-6, 0)
+        o = np.zeros(60)
+        o[30:35] = [60.0, -60, -60, -60, -60]       # channel B, first component only
+        o[35] = mu_hat
+        o[40] = ls
+        mu, s = 256 * mu_hat, 256 * np.exp(ls)
+        x = np.arange(256)
+        p = scipy.stats.logistic.cdf(x + 0.5, loc=mu, scale=s) - scipy.stats.logistic.cdf(x - 0.5, loc=mu, scale=s)
+        got = orc_logistic.pmf(o, 2)
+        np.testing.assert_allclose(got[1:255], p[1:255], atol=1e-13)
+        assert abs(got[0] - scipy.stats.logistic.cdf(0.5, loc=mu, scale=s)) < 1e-13
+        assert abs(got[255] - scipy.stats.logistic.sf(254.5, loc=mu, scale=s)) < 1e-13
+        e = np.arange(1, 256)
+        want = e + np.floor(65280 * scipy.special.expit(((e - 0.5) / 256 - mu_hat) / np.exp(ls))).astype(np.int64)
+        cq = orc_logistic.cdf_table(o, 2).astype(np.int64)
+        assert np.abs(cq[1:256] - want).max() <= 1 and (cq[1:256] != want).mean() < 0.01
+        f = np.diff(cq)
+        assert f.min() >= 1 and f.sum() == 65536
+
+
+def test_logistic_differs_from_gaussian_and_roundtrips(orc, orc_logistic):
+    rng = np.random.default_rng(18)
+    o = rng.normal(0, 1, 60)
+    assert (orc.cdf_table(o, 0) != orc_logistic.cdf_table(o, 0)).any()
+    imgs = synth.make_image(6, synth.ImageSpec(13, 9, 3, 2.0, 5.0))[None]
+    stream, bits = orc_logistic.encode(imgs)
+    np.testing.assert_array_equal(orc_logistic.decode(stream, 1, 9, 13, order=po.ORDER_WAVEFRONT), imgs)
+    np.testing.assert_array_equal(orc_logistic.decode(stream, 1, 9, 13, order=po.ORDER_RASTER), imgs)
+    # a Gaussian-mixture model must refuse a logistic-mixture stream
+    with pytest.raises(po.OracleError):
+        orc.decode(stream, 1, 9, 13)
+
+
 # ----------------------------------------------------------------- rANS
 
 def _random_tables(rng, nsym):
