@@ -562,7 +562,12 @@ __device__ __forceinline__ int group_search(const ChanParams& cp, uint32_t slot,
     return 16 * b + cnt2 - 1;
 }
 
-__global__ void __launch_bounds__(kDecThreads)
+// MINBLOCKS = 1: all registers to one workgroup per CU (lowest latency per step; used when
+// every band gets a CU of its own).  MINBLOCKS = 2: two workgroups share a CU (a few
+// spills, ~15 % slower per step, but the second band fills the first one's stalls; used
+// when there are more bands than CUs).
+template <int MINBLOCKS>
+__global__ void __launch_bounds__(kDecThreads, MINBLOCKS)
 decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ stream, uint64_t nbytes, int n, int H,
               int W, int nbands, uint32_t dist, uint8_t* __restrict__ img_out, uint32_t* mailbox, int* status,
               uint32_t spin_limit) {
@@ -1089,7 +1094,9 @@ int pcc_create(pcc_ctx** out, const void* h_blob, size_t blob_bytes, int hip_dev
         const int v = atoi(e);
         if (v >= 0 && v < 3) ctx->encode_variant = v;
     }
-    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_kernel),
+    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_kernel<1>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, kDecLdsBytes) == hipSuccess;
+    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_kernel<2>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, kDecLdsBytes) == hipSuccess;
     if (!ok) { (void)hipGetLastError(); pcc_destroy(ctx); return PCC_E_HIP; }
     ctx->d_total = reinterpret_cast<uint64_t*>(ctx->d_status + kStWords);
@@ -1215,8 +1222,14 @@ int pcc_decode(pcc_ctx* ctx, const uint8_t* d_stream, size_t nbytes, int n, int 
     const uint32_t spin_limit = 1u << 22;
     prof_reset(ctx);
     prof_begin(ctx, PCC_T_DECODE, st);
-    hipLaunchKernelGGL(decode_kernel, dim3((uint32_t)(n * nbands)), dim3(kDecThreads), kDecLdsBytes, st, ctx->d_model,
-                       d_stream, (uint64_t)nbytes, n, H, W, nbands, ctx->dist, d_img_out, d_mail, ctx->d_status, spin_limit);
+    const uint32_t grid = (uint32_t)(n * nbands);
+    const uint32_t cus = ctx->num_cus > 0 ? (uint32_t)ctx->num_cus : 256u;
+    if (grid <= cus)
+        hipLaunchKernelGGL(decode_kernel<1>, dim3(grid), dim3(kDecThreads), kDecLdsBytes, st, ctx->d_model, d_stream,
+                           (uint64_t)nbytes, n, H, W, nbands, ctx->dist, d_img_out, d_mail, ctx->d_status, spin_limit);
+    else
+        hipLaunchKernelGGL(decode_kernel<2>, dim3(grid), dim3(kDecThreads), kDecLdsBytes, st, ctx->d_model, d_stream,
+                           (uint64_t)nbytes, n, H, W, nbands, ctx->dist, d_img_out, d_mail, ctx->d_status, spin_limit);
     prof_end(ctx, PCC_T_DECODE, st);
     if (hipGetLastError() != hipSuccess) return PCC_E_HIP;
     if (hipMemcpyAsync(ctx->h_status, ctx->d_status, kStWords * sizeof(int), hipMemcpyDeviceToHost, st) != hipSuccess)
