@@ -56,15 +56,25 @@ typedef struct {
     int nbhd;   /* neighbourhood size in pixels */
     int delay;  /* wavefront step = delay*r + c */
     int dist;   /* component distribution: 0 Gaussian (Eq. (1)), 1 logistic (Eq. (8)) */
+    int act;    /* 0 ReLU, 1 LeakyReLU with slope 0.01 */
     double *W[ORC_MAX_LAYERS]; /* [out][in] */
     double *b[ORC_MAX_LAYERS];
 } orc_model;
 
 /* Causal neighbourhood (Sec. III-A, Fig. 1), raster order, (row offset, column
- * offset).  Ten pixels: rows r-2 and r-1 at columns c-2..c+1, row r at c-2,c-1. */
+ * offset).  Ten pixels: rows r-2 and r-1 at columns c-2..c+1, row r at c-2,c-1
+ * (the measured workloads).  Twelve pixels: the unmasked taps of the paper's
+ * 5x5 first layer (Sec. III-B), rows r-2 and r-1 at columns c-2..c+2, row r at
+ * c-2,c-1; the figure is lost, the count follows from the printed parameter
+ * numbers (37 C = (12 taps x 3 channels + 1 bias) C) and from the three
+ * upper-right pixels the diagonal variant cannot use (Sec. III-C). */
 static const int NBHD10[10][2] = {
     {-2, -2}, {-2, -1}, {-2, 0}, {-2, 1},
     {-1, -2}, {-1, -1}, {-1, 0}, {-1, 1},
+    {0, -2}, {0, -1}};
+static const int NBHD12[12][2] = {
+    {-2, -2}, {-2, -1}, {-2, 0}, {-2, 1}, {-2, 2},
+    {-1, -2}, {-1, -1}, {-1, 0}, {-1, 1}, {-1, 2},
     {0, -2}, {0, -1}};
 
 static uint32_t rd32(const uint8_t *p) {
@@ -104,7 +114,10 @@ int orc_model_create(const void *blob, size_t nbytes, orc_model **out) {
     m->delay = (int)rd32(p + 52);
     uint32_t act = rd32(p + 56), dist = rd32(p + 60);
     m->dist = (int)dist;
-    if (m->K < 1 || m->K > ORC_MAX_K || m->nbhd != 10 || m->delay != 2 || act != 0 || dist > 1 ||
+    m->act = (int)act;
+    /* the wavefront delay per row is the neighbourhood's right reach + 1: Eq. (6) with h = reach */
+    if (m->K < 1 || m->K > ORC_MAX_K || !((m->nbhd == 10 && m->delay == 2) || (m->nbhd == 12 && m->delay == 3)) ||
+        act > 1 || dist > 1 ||
         m->dims[0] != 3 * m->nbhd || m->dims[m->n_layers] != 12 * m->K) { free(m); return ORC_E_BLOB; }
     size_t need = 64;
     for (int l = 0; l < m->n_layers; ++l) need += 4 * ((size_t)m->dims[l] * m->dims[l + 1] + m->dims[l + 1]);
@@ -130,8 +143,9 @@ int orc_model_create(const void *blob, size_t nbytes, orc_model **out) {
  * by 1/256 is this build's choice; the paper does not state one. */
 void orc_gather(const orc_model *m, const uint8_t *img, int H, int W, int r, int c, double *u) {
     (void)H;
+    const int (*nb)[2] = m->nbhd == 10 ? NBHD10 : NBHD12;
     for (int j = 0; j < m->nbhd; ++j) {
-        int rr = r + NBHD10[j][0], cc = c + NBHD10[j][1];
+        int rr = r + nb[j][0], cc = c + nb[j][1];
         for (int ch = 0; ch < 3; ++ch) {
             double v = 0.0;
             if (rr >= 0 && cc >= 0 && cc < W) v = img[((size_t)rr * W + cc) * 3 + ch] / 256.0;
@@ -151,8 +165,8 @@ static double round_bf16(double x) {
 }
 
 /* The probability network as a fully connected stack on C_ij (Sec. III-B with
- * the equivalence of Sec. III-C, second paragraph): ReLU between layers, none
- * after the last.  Mode EXACT is the definition.  Mode SPLIT_BF16 rounds every
+ * the equivalence of Sec. III-C, second paragraph): ReLU (or the paper's
+ * LeakyReLU, slope 0.01 -- the paper gives none) between layers, none after the last.  Mode EXACT is the definition.  Mode SPLIT_BF16 rounds every
  * hidden activation a to hi + lo with hi = bf16(a), lo = bf16(a - hi), i.e. to
  * about 16 significant bits -- the representation the matrix-core path feeds
  * to its bf16 multipliers; it exists to show how little that rounding moves
@@ -169,7 +183,7 @@ void orc_mlp(const orc_model *m, const double *u, int mode, double *o) {
         }
         if (l + 1 < m->n_layers) {
             for (int j = 0; j < nout; ++j) {
-                double h = z[j] > 0.0 ? z[j] : 0.0;
+                double h = z[j] > 0.0 ? z[j] : (m->act == 1 ? 0.01 * z[j] : 0.0);
                 if (mode == ORC_MODE_SPLIT_BF16) { double hi = round_bf16(h); h = hi + round_bf16(h - hi); }
                 a[j] = h;
             }

@@ -130,6 +130,13 @@ DEFAULT_K = 5
 DEFAULT_NBHD = 10
 DEFAULT_DELAY = 2
 
+# the paper's own network (Sec. III-B and the hyper-parameter table of Sec. IV-E): first layer on the
+# 12 unmasked taps of a 5x5 window, four more layers of 128 filters, LeakyReLU, K = 3 mixtures
+PAPER_DIMS = (36, 128, 128, 128, 128, 36)
+PAPER_K = 3
+PAPER_NBHD = 12
+PAPER_DELAY = 3
+
 
 def round_to_bf16(x: np.ndarray) -> np.ndarray:
     """Round float32 values to the nearest bf16 (ties to even); result stays float32."""
@@ -184,6 +191,12 @@ def pack_blob(layers, k=DEFAULT_K, nbhd=DEFAULT_NBHD, delay=DEFAULT_DELAY,
 def make_blob(seed: int = 0, sharp: bool = False, dist: int = DIST_GAUSSIAN) -> bytes:
     """The weight blob every workload uses (seed 0, default shape)."""
     return pack_blob(make_weights(seed, DEFAULT_DIMS, sharp=sharp), dist=dist)
+
+
+def make_paper_blob(seed: int = 0, sharp: bool = False, dist: int = DIST_GAUSSIAN) -> bytes:
+    """A weight blob of the paper's network shape (He-initialised: no trained weights exist here)."""
+    return pack_blob(make_weights(seed, PAPER_DIMS, sharp=sharp), k=PAPER_K, nbhd=PAPER_NBHD, delay=PAPER_DELAY,
+                     act=ACT_LEAKY, dist=dist)
 
 
 def param_count(dims) -> int:

@@ -46,3 +46,21 @@ def logistic_blob():
 def orc_logistic(logistic_blob):
     from oracle import pcc_oracle
     return pcc_oracle.Oracle(logistic_blob)
+
+
+@pytest.fixture(scope="session")
+def paper_blob():
+    from paper_2212_01185_amd import synth
+    return synth.make_paper_blob(0)
+
+
+@pytest.fixture(scope="session")
+def paper_sharp_blob():
+    from paper_2212_01185_amd import synth
+    return synth.make_paper_blob(0, sharp=True)
+
+
+@pytest.fixture(scope="session")
+def orc_paper(paper_blob):
+    from oracle import pcc_oracle
+    return pcc_oracle.Oracle(paper_blob)

@@ -308,6 +308,75 @@ def test_logistic_differs_from_gaussian_and_roundtrips(orc, orc_logistic):
         orc.decode(stream, 1, 9, 13)
 
 
+# ----------------------------------------------------------------- the paper's own network shape
+
+OFFSETS12 = [(-2, -2), (-2, -1), (-2, 0), (-2, 1), (-2, 2), (-1, -2), (-1, -1), (-1, 0), (-1, 1), (-1, 2),
+             (0, -2), (0, -1)]
+
+
+def test_paper_network_blob(paper_blob, orc_paper):
+    # the printed 58,917 of the reference setting (K=3, C=128, L=5) is this fully connected count plus one
+    assert synth.param_count(synth.PAPER_DIMS) + 1 == 58917
+    assert len(paper_blob) == 64 + 4 * 58916
+    assert orc_paper.dims == list(synth.PAPER_DIMS) and orc_paper.K == 3
+
+
+@pytest.mark.parametrize("h,w", [(1, 1), (1, 7), (7, 1), (3, 2), (5, 9)])
+def test_paper_neighbourhood_schedules(h, w):
+    """Wavefront with delay 3 (Eq. (6), h = 2) is causal for the 12-pixel neighbourhood; the diagonal
+    order r + c (Eq. (7)) leaves exactly the three upper-right pixels undecoded (Sec. III-C)."""
+    for r in range(h):
+        for c in range(w):
+            for dr, dc in OFFSETS12:
+                if 0 <= r + dr < h and 0 <= c + dc < w:
+                    assert 3 * (r + dr) + (c + dc) < 3 * r + c
+    late = [(dr, dc) for dr, dc in OFFSETS12 if dr + dc >= 0]
+    assert sorted(late) == [(-2, 2), (-1, 1), (-1, 2)]
+    assert po.wavefront_steps(h, w, 3) == w + 3 * (h - 1)
+    d = 512
+    assert po.wavefront_steps(d, d, 3) == 4 * d - 3 and 2 * d - 1 == 1023
+
+
+def test_paper_gather_and_leaky_mlp(orc_paper, paper_blob):
+    rng = np.random.default_rng(21)
+    img = rng.integers(0, 256, size=(5, 6, 3), dtype=np.uint8)
+    pad = np.zeros((5 + 2, 6 + 4, 3), dtype=np.float64)
+    pad[2:, 2:-2] = img / 256.0
+    for r in range(5):
+        for c in range(6):
+            want = np.concatenate([pad[r + 2 + dr, c + 2 + dc] for dr, dc in OFFSETS12])
+            np.testing.assert_array_equal(orc_paper.gather(img, r, c), want)
+    arr = np.frombuffer(paper_blob[64:], dtype="<f4")
+    layers, pos = [], 0
+    for i, o in zip(synth.PAPER_DIMS[:-1], synth.PAPER_DIMS[1:]):
+        w = arr[pos:pos + i * o].reshape(o, i).astype(np.float64); pos += i * o
+        b = arr[pos:pos + o].astype(np.float64); pos += o
+        layers.append((w, b))
+    for _ in range(10):
+        u = rng.integers(0, 256, 36) / 256.0
+        a = u
+        for i, (w, b) in enumerate(layers):
+            a = w @ a + b
+            if i < 4:
+                a = np.where(a > 0, a, 0.01 * a)
+        np.testing.assert_allclose(orc_paper.mlp(u), a, rtol=0, atol=1e-12)
+        assert (orc_paper.mlp(u) != 0).all()
+
+
+def test_paper_network_roundtrip(orc_paper):
+    rng = np.random.default_rng(22)
+    for imgs in (rng.integers(0, 256, (1, 1, 1, 3), dtype=np.uint8), rng.integers(0, 256, (2, 4, 7, 3), dtype=np.uint8),
+                 np.zeros((1, 5, 5, 3), dtype=np.uint8), synth.make_image(7, synth.ImageSpec(17, 9, 3, 2.0, 6.0))[None]):
+        n, h, w, _ = imgs.shape
+        stream, bits = orc_paper.encode(imgs)
+        np.testing.assert_array_equal(orc_paper.decode(stream, n, h, w, order=po.ORDER_RASTER), imgs)
+        np.testing.assert_array_equal(orc_paper.decode(stream, n, h, w, order=po.ORDER_WAVEFRONT), imgs)
+        for ch in range(3):
+            o = orc_paper.params_at(imgs[0], h - 1, w - 1)
+            f = np.diff(orc_paper.cdf_table(o, ch, 3, 200).astype(np.int64))
+            assert f.min() >= 1 and f.sum() == 65536
+
+
 # ----------------------------------------------------------------- rANS
 
 def _random_tables(rng, nsym):
