@@ -6,6 +6,11 @@ pixels through gather, network, mixture CDF, row-rANS, stream assembly, then the
 wavefront decoder), inputs and outputs resident in HBM.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1] [--no-cpu-baseline]
+                  [--network workload|paper] [--image WxH]
+
+--network paper runs the paper's own network shape (12-pixel neighbourhood, 36-128x4-36, LeakyReLU, K=3,
+delay 3) instead of the measured workloads' one; --image 512x512 gives the image size of the paper's run-time
+table.  Neither is the headline: the driver's default run is config 1 with the workload network.
 """
 from __future__ import annotations
 
@@ -19,7 +24,12 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-FLOP_PER_PIXEL = 117120          # 2 * 58,560 multiply-accumulates of the 30-160-160-128-60 network
+# 2 * multiply-accumulates per pixel: 30-160-160-128-60 (58,560) and 36-128-128-128-128-36 (58,368)
+FLOP_PER_PIXEL_BY_NET = {"workload": 117120, "paper": 116736}
+NET_NAME = {"workload": "He-init 30-160-160-128-60 network, ReLU, K=5, 10-pixel neighbourhood",
+            "paper": "He-init 36-128-128-128-128-36 network, LeakyReLU, K=3, 12-pixel neighbourhood"}
+# paper, Table II: 512x512, wavefront, RTX 2080 + i7-9700: encode 3.10 s, decode 26.26 s
+PAPER_512_STEP_SECONDS = 3.10 + 26.26
 PEAK_BF16_TFLOPS = 2500.0        # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch of the encode kernel at 768x512 from rocprofv3 FETCH_SIZE / WRITE_SIZE,
@@ -57,6 +67,8 @@ def main():
     ap.add_argument("--config", type=int, default=1, help="workload id 0..4 (1 = 768x512, the headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=48)
+    ap.add_argument("--network", choices=("workload", "paper"), default="workload")
+    ap.add_argument("--image", default=None, help="WxH of one synthetic image instead of a numbered config")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs: three encodes + decodes and one plain "
                          "64 MiB device copy of known traffic, no timing, no JSON")
@@ -69,8 +81,15 @@ def main():
     import torch
     from paper_2212_01185_amd import binding, synth
 
-    blob = synth.make_blob(0)
-    imgs = synth.make_batch(args.config)
+    FLOP_PER_PIXEL = FLOP_PER_PIXEL_BY_NET[args.network]
+    blob = synth.make_blob(0) if args.network == "workload" else synth.make_paper_blob(0)
+    if args.image:
+        iw, ih = (int(v) for v in args.image.lower().split("x"))
+        imgs = synth.make_image(0, synth.ImageSpec(iw, ih, 32, 8.0, 64.0))[None]
+        wl_name = "1 x %dx%d" % (iw, ih)
+    else:
+        imgs = synth.make_batch(args.config)
+        wl_name = "config %d: %d x %dx%d" % (args.config, imgs.shape[0], imgs.shape[2], imgs.shape[1])
     n, h, w, _ = imgs.shape
     pixels = n * h * w
     codec = binding.Codec(blob, 0)
@@ -119,7 +138,9 @@ def main():
     ms_per_step = (t1 - t0) / k * 1e3
     kern = {name: acc[name] / k for name in acc}       # ms per launch
     stream_bytes = int(s.numel())
-    steps_wave = binding.pcc_wavefront_steps(h, w)
+    steps_wave = binding.pcc_wavefront_steps(h, w, codec.delay)
+    headline = args.network == "workload" and not args.image and args.config == 1
+    paper_case = args.network == "paper" and (n, h, w) == (1, 512, 512)
 
     enc_tflops = FLOP_PER_PIXEL * pixels / (kern["encode_pixels"] * 1e-3) / 1e12
     result = {
@@ -127,10 +148,11 @@ def main():
         "value": pixels / (ms_per_step * 1e-3) / 1e6,
         "unit": "MPix/s (one step = encode + wavefront decode of every pixel)",
         "n_gpus": 1, "steps": k, "warmup": args.warmup, "ms_per_step": ms_per_step,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "higher_is_better": True, "scaling": "weak",
+        # only the paper's own case (its network shape, its 512x512 image size; its machine was an RTX 2080)
+        "vs_baseline": (pixels / (ms_per_step * 1e-3)) / (512 * 512 / PAPER_512_STEP_SECONDS) if paper_case else None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "config %d: %d x %dx%d RGB uint8, seeded blobs+gradient+noise, He-init 30-160-160-128-60 network, K=5"
-                               % (args.config, n, w, h),
+        "config": {"workload": "%s RGB uint8, seeded blobs+gradient+noise, %s" % (wl_name, NET_NAME[args.network]),
                    "pixels": pixels, "wavefront_steps": steps_wave, "stream_bytes": stream_bytes,
                    "bpsp": 8.0 * stream_bytes / (3 * pixels)},
         "encode_MPix_s": pixels / (t_enc / k) / 1e6,
@@ -142,7 +164,7 @@ def main():
             "kernel": "encode_kernel (gather + network on MFMA + mixture CDF, all pixels)",
             "bound": "mfma", "achieved": enc_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
             "frac": enc_tflops / PEAK_BF16_TFLOPS,
-            "traffic": ENCODE_KERNEL_TRAFFIC_768x512 if (args.config == 1) else None,
+            "traffic": ENCODE_KERNEL_TRAFFIC_768x512 if headline else None,
         },
         "roofline_decode": {
             "kernel": "decode_kernel (persistent wavefront)", "bound": "dependency chain",

@@ -26,13 +26,19 @@
  * Weight blob (host memory): 16 little-endian uint32 header words {magic
  * "PCCW", version 1, n_layers, dims[8], K, neighbourhood size, wavefront delay
  * per row, activation id, distribution id}, then per layer W[out][in] and
- * b[out] as fp32.  This library accepts the shape 30 -> 160 -> 160 -> 128 -> 60,
- * ReLU, K = 5 components that are Gaussian (distribution id 0, Eq. (1)) or
- * logistic (id 1, Eq. (8)), the 10-pixel neighbourhood {rows r-2, r-1 at
- * columns c-2..c+1; row r at c-2, c-1} and delay 2; weights must be exactly
- * representable in bf16 (biases are fp32).  Head layout o[60]: for each of
- * R,G,B: 5 mixture logits, 5 means, 5 log-sigmas (units of 1/256 of the grey
- * range); then 5 alphas, 5 betas, 5 gammas of Eq. (3)-(4).
+ * b[out] as fp32.  Weights must be exactly representable in bf16 (biases are
+ * fp32); components are Gaussian (distribution id 0, Eq. (1)) or logistic
+ * (id 1, Eq. (8)).  This library accepts two network shapes:
+ *   - 30 -> 160 -> 160 -> 128 -> 60, ReLU (activation id 0), K = 5, the
+ *     10-pixel neighbourhood {rows r-2, r-1 at columns c-2..c+1; row r at
+ *     c-2, c-1}, delay 2 (the measured workloads);
+ *   - 36 -> 128 -> 128 -> 128 -> 128 -> 36, LeakyReLU with slope 0.01 (id 1),
+ *     K = 3, the 12-pixel neighbourhood {rows r-2, r-1 at columns c-2..c+2;
+ *     row r at c-2, c-1}, delay 3 (the network of Sec. III-B with the
+ *     hyper-parameters of Sec. IV-E).
+ * Head layout o[12 K]: for each of R,G,B: K mixture logits, K means, K
+ * log-sigmas (units of 1/256 of the grey range); then K alphas, K betas,
+ * K gammas of Eq. (3)-(4).
  *
  * Stream (device memory): 8 little-endian uint32 words {magic "PCC1", version
  * 1, n, H, W, K | nbhd<<8 | delay<<16 | 16<<24, distribution id, 0}, uint64 offsets[n*H+1]
@@ -61,7 +67,7 @@ extern "C" {
 #define PCC_E_INTERNAL (-6) /* zero frequency or bounded device wait expired */
 #define PCC_E_UNIMPL (-7)
 
-#define PCC_HEAD_OUTPUTS 60
+#define PCC_HEAD_OUTPUTS 60 /* of the 30-160-160-128-60 network; in general pcc_model_info()[0] */
 
 typedef struct pcc_ctx pcc_ctx;
 
@@ -73,13 +79,19 @@ void pcc_destroy(pcc_ctx *ctx);
 /* Upper bound in bytes of the stream pcc_encode writes for n images of H x W. */
 size_t pcc_stream_bound(int n, int H, int W);
 
-/* Number of wavefront passes for an H x W image: Eq. (6) with a right reach of
- * one column, T = W + 2 (H - 1). */
-long pcc_wavefront_steps(int H, int W);
+/* Number of wavefront passes for an H x W image when each row trails the row
+ * above by `delay` columns (right reach of the neighbourhood + 1): Eq. (6)
+ * generalised, T = W + delay (H - 1).  0 for non-positive arguments. */
+long pcc_wavefront_steps(int H, int W, int delay);
+
+/* Shape of the network the ctx was created with, h_info[6] (host): head
+ * outputs per pixel (12 K), K, neighbourhood size, delay, distribution id,
+ * number of layers. */
+int pcc_model_info(const pcc_ctx *ctx, int *h_info);
 
 /* Network evaluation for every pixel (Sec. III-C first paragraph: at the
  * encoder all pixels are known and are processed in parallel).
- *   d_params [n][H][W][60] fp32: raw head outputs in the head layout above.
+ *   d_params [n][H][W][12 K] fp32: raw head outputs in the head layout above.
  *   d_bits   [n][H][W] fp32 or NULL: -log2 of the quantised joint probability
  *            of the pixel's true (r,g,b), i.e. its term of the loss Eq. (5).
  * Asynchronous: returns after the launch. */
@@ -94,7 +106,7 @@ int pcc_encode(pcc_ctx *ctx, const uint8_t *d_img, int n, int H, int W,
                uint8_t *d_stream, size_t cap_bytes, size_t *h_nbytes_out, void *hip_stream);
 
 /* Wavefront decoder (Sec. III-C): pass t decodes every pixel (r, c) with
- * 2r + c = t.  d_img_out [n][H][W][3] is fully overwritten.  Synchronises
+ * delay * r + c = t.  d_img_out [n][H][W][3] is fully overwritten.  Synchronises
  * hip_stream before returning (the device status word is read back).  On
  * PCC_E_STREAM the image content is unspecified. */
 int pcc_decode(pcc_ctx *ctx, const uint8_t *d_stream, size_t nbytes, int n, int H, int W,
@@ -103,7 +115,7 @@ int pcc_decode(pcc_ctx *ctx, const uint8_t *d_stream, size_t nbytes, int n, int 
 /* Test hooks (not on the hot path). */
 
 /* Eq. (1)-(4) + integer CDF rule alone: from given head outputs d_params
- * [count][60] and the conditioning sub-pixels d_rg [count][2] (r, g) write the
+ * [count][12 K] and the conditioning sub-pixels d_rg [count][2] (r, g) write the
  * full tables d_cq [count][3][257] (uint32).  Asynchronous. */
 int pcc_cdf_tables(pcc_ctx *ctx, const float *d_params, const uint8_t *d_rg, size_t count,
                    uint32_t *d_cq, void *hip_stream);

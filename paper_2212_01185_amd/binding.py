@@ -17,10 +17,10 @@ LIB_PATH = os.path.join(_HERE, "libpcc.so")
 
 PCC_OK = 0
 PCC_E_ARG, PCC_E_BLOB, PCC_E_CAP, PCC_E_STREAM, PCC_E_HIP, PCC_E_INTERNAL, PCC_E_UNIMPL = -1, -2, -3, -4, -5, -6, -7
-HEAD_OUTPUTS = 60
+HEAD_OUTPUTS = 60          # of the 30-160-160-128-60 network; a Codec knows its own (head_outputs)
 
 EXPORTS = (
-    "pcc_create", "pcc_destroy", "pcc_stream_bound", "pcc_wavefront_steps", "pcc_encode_probs", "pcc_encode",
+    "pcc_create", "pcc_destroy", "pcc_stream_bound", "pcc_wavefront_steps", "pcc_model_info", "pcc_encode_probs", "pcc_encode",
     "pcc_decode", "pcc_cdf_tables", "pcc_copy_intervals", "pcc_set_profiling", "pcc_last_timings", "pcc_strerror",
 )
 TIMING_NAMES = ("encode_pixels", "encode_rans", "encode_scan", "encode_compact", "decode")
@@ -44,8 +44,10 @@ def load():
     L.pcc_destroy.restype = None
     L.pcc_stream_bound.argtypes = [i32, i32, i32]
     L.pcc_stream_bound.restype = sz
-    L.pcc_wavefront_steps.argtypes = [i32, i32]
+    L.pcc_wavefront_steps.argtypes = [i32, i32, i32]
     L.pcc_wavefront_steps.restype = C.c_long
+    L.pcc_model_info.argtypes = [vp, vp]
+    L.pcc_model_info.restype = i32
     L.pcc_encode_probs.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp]
     L.pcc_encode_probs.restype = i32
     L.pcc_encode.argtypes = [vp, vp, i32, i32, i32, vp, sz, C.POINTER(sz), vp]
@@ -80,8 +82,8 @@ def pcc_stream_bound(n: int, h: int, w: int) -> int:
     return int(load().pcc_stream_bound(n, h, w))
 
 
-def pcc_wavefront_steps(h: int, w: int) -> int:
-    return int(load().pcc_wavefront_steps(h, w))
+def pcc_wavefront_steps(h: int, w: int, delay: int = 2) -> int:
+    return int(load().pcc_wavefront_steps(h, w, delay))
 
 
 def _stream_handle():
@@ -105,6 +107,16 @@ class Codec:
         if rc != PCC_OK:
             self._h = C.c_void_p()
             raise PccError(rc, "pcc_create")
+        info = self.pcc_model_info()
+        self.head_outputs, self.k, self.nbhd, self.delay, self.dist, self.n_layers = info
+
+    def pcc_model_info(self):
+        """(head outputs, K, neighbourhood size, delay, distribution id, layers) of the loaded network."""
+        arr = (C.c_int * 6)()
+        rc = load().pcc_model_info(self._h, arr)
+        if rc != PCC_OK:
+            raise PccError(rc, "pcc_model_info")
+        return tuple(int(v) for v in arr)
 
     def close(self):
         if self._h and self._h.value:
@@ -119,7 +131,7 @@ class Codec:
 
     def pcc_encode_probs(self, img: torch.Tensor, want_bits: bool = True):
         n, h, w = _check_img(img)
-        params = torch.empty((n, h, w, HEAD_OUTPUTS), dtype=torch.float32, device=img.device)
+        params = torch.empty((n, h, w, self.head_outputs), dtype=torch.float32, device=img.device)
         bits = torch.empty((n, h, w), dtype=torch.float32, device=img.device) if want_bits else None
         rc = load().pcc_encode_probs(self._h, img.data_ptr(), n, h, w, params.data_ptr(),
                                      bits.data_ptr() if want_bits else None, _stream_handle())
@@ -150,9 +162,10 @@ class Codec:
         return out
 
     def pcc_cdf_tables(self, params: torch.Tensor, rg: torch.Tensor) -> torch.Tensor:
-        """params float32 [count, 60], rg uint8 [count, 2] -> uint32-valued int32 tensor [count, 3, 257]."""
+        """params float32 [count, 12 K], rg uint8 [count, 2] -> uint32-valued int32 tensor [count, 3, 257]."""
         count = int(params.shape[0])
-        assert params.dtype == torch.float32 and params.is_cuda and params.is_contiguous() and params.shape[1] == 60
+        assert params.dtype == torch.float32 and params.is_cuda and params.is_contiguous()
+        assert params.shape[1] == self.head_outputs
         assert rg.dtype == torch.uint8 and rg.is_cuda and rg.is_contiguous() and tuple(rg.shape) == (count, 2)
         cq = torch.empty((count, 3, 257), dtype=torch.int32, device=params.device)
         rc = load().pcc_cdf_tables(self._h, params.data_ptr(), rg.data_ptr(), count, cq.data_ptr(), _stream_handle())

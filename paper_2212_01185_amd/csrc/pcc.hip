@@ -1,6 +1,6 @@
 // libpcc: kernels and C ABI (see include/pcc.h for the contract).
 //
-// Kernels
+// Kernels (templated on the network description, see pcc_device.h)
 //   encode_kernel      gather + network (MFMA) + mixture -> (start,freq) of the
 //                      true sub-pixels, all pixels in parallel
 //   rans_rows_kernel   one lane per image row: push the row's symbols last to
@@ -8,7 +8,7 @@
 //   scan_kernel        exclusive prefix sum of row payload sizes, header, offsets
 //   compact_kernel     slabs -> contiguous stream
 //   decode_kernel      persistent wavefront decoder: one workgroup (4 waves) per
-//                      band of 16 rows, step t handles pixel (r, t - 2r) of each row
+//                      band of 16 rows, step t handles pixel (r, t - delay*r) of each row
 //   cdf_tables_kernel  test hook: full integer CDF tables from given parameters
 #include <hip/hip_runtime.h>
 
@@ -18,6 +18,7 @@
 #include <string.h>
 
 #include <new>
+#include <type_traits>
 #include <vector>
 
 #include "pcc.h"
@@ -28,12 +29,14 @@ namespace pcc {
 constexpr uint32_t kBlobMagic = 0x57434350u;    // "PCCW"
 constexpr uint32_t kStreamMagic = 0x31434350u;  // "PCC1"
 constexpr int kStreamHeader = 32;
-constexpr uint32_t kModelTag = 5u | (10u << 8) | (2u << 16) | (16u << 24);
 constexpr int kBandRows = 16;
 constexpr uint32_t kMailTag = 0x80000000u;
+
+template <class Net>
+constexpr uint32_t model_tag() { return (uint32_t)Net::K | ((uint32_t)Net::kNbhd << 8) | ((uint32_t)Net::kDelay << 16) | (16u << 24); }
+
 // Encode kernel variants: tiles of 16 pixels per wave per iteration x threads per workgroup.
-// More tiles per wave reuse each LDS weight read more often but need more registers
-// (4 tiles only fit with one wave per SIMD).
+// More tiles per wave reuse each LDS weight read more often but need more registers.
 struct EncodeVariant { int tiles, threads; };
 constexpr EncodeVariant kEncodeVariants[3] = {{1, 512}, {2, 512}, {1, 1024}};
 constexpr int kDefaultEncodeVariant = 1;
@@ -58,83 +61,96 @@ __device__ __forceinline__ uint32_t opaque_zero() {
     return z;
 }
 
-__device__ __forceinline__ void copy_model_to_lds(uint8_t* lds, const uint8_t* __restrict__ model) {
-    const uint4* src = reinterpret_cast<const uint4*>(model);
-    uint4* dst = reinterpret_cast<uint4*>(lds);
-    for (int i = threadIdx.x; i < kModelBytes / 16; i += blockDim.x) dst[i] = src[i];
+__device__ __forceinline__ void copy_to_lds(uint8_t* lds, const uint8_t* __restrict__ src, int bytes) {
+    const uint4* s = reinterpret_cast<const uint4*>(src);
+    uint4* d = reinterpret_cast<uint4*>(lds);
+    for (int i = threadIdx.x; i < bytes / 16; i += blockDim.x) d[i] = s[i];
 }
 
-// Source of slot i of lane group g in the first-layer operand: row offset and
-// byte within the row's neighbour run (which starts at column c-2).
-__device__ __forceinline__ void slot_source(int g, int i, int& dr, int& b, bool& used) {
-    if (i < 4) {
-        dr = (g < 2) ? -2 : -1;
-        b = (g & 1) ? 8 + i : i;
-        used = true;
-    } else {
-        dr = (g & 1) ? 0 : ((g == 0) ? -2 : -1);
-        b = (g == 1) ? i - 4 : i;
-        used = !(g == 3 && i >= 6);
+// Lane group and register (g * kHeadSlots + s) that hold canonical head output c.
+template <class Net>
+__host__ __device__ constexpr int head_slot(int c) {
+    for (int g = 0; g < 4; ++g)
+        for (int s = 0; s < Layout<Net>::kHeadSlots; ++s)
+            if (Net::head_index(g, s) == c) return g * Layout<Net>::kHeadSlots + s;
+    return -1;
+}
+
+// Compile-time loop: f(std::integral_constant<int, I>) for I = 0 .. N-1.
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
     }
 }
 
 // Raw head registers of one lane after the network -> mixture of "its" channel
-// (lane groups 0,1,2 = R,G,B) with the coupling coefficients pulled from group 3.
+// (lane groups 0,1,2 = R,G,B) with the coupling coefficients it needs.
+template <class Net>
 struct LaneHead {
-    ChanParams cp;
-    float c1[5];  // alpha (group 1) or beta (group 2)
-    float c2[5];  // gamma (group 2)
+    ChanParams<Net::K> cp;
+    float c1[Net::K];  // alpha (group 1) or beta (group 2)
+    float c2[Net::K];  // gamma (group 2)
 };
 
-__device__ __forceinline__ void lane_head_setup(const f32x4_t (&o)[kL4_OB], int lane, float lut_scale, LaneHead& h) {
-    float v[16];
+template <class Net>
+__device__ __forceinline__ void lane_head_setup(const f32x4_t (&o)[Layout<Net>::kHeadOB], int lane, float lut_scale,
+                                                LaneHead<Net>& h) {
+    constexpr int K = Net::K, HS = Layout<Net>::kHeadSlots;
+    float v[HS];
 #pragma unroll
-    for (int ob = 0; ob < kL4_OB; ++ob) {
+    for (int ob = 0; ob < Layout<Net>::kHeadOB; ++ob) {
         v[4 * ob + 0] = o[ob].x; v[4 * ob + 1] = o[ob].y; v[4 * ob + 2] = o[ob].z; v[4 * ob + 3] = o[ob].w;
     }
-    const int g = lane >> 4;
-    const int src = (lane & 15) + 48;
-    float x3[13];
+    const int g = lane >> 4, nl = lane & 15;
+    float raw[3 * K];
 #pragma unroll
-    for (int s = 0; s < 13; ++s) x3[s] = __shfl(v[s], src);
-    float raw[15];
-#pragma unroll
-    for (int s = 0; s < 15; ++s) raw[s] = v[s];
-    channel_setup(raw, lut_scale, h.cp);
-    h.c1[0] = v[15];
-#pragma unroll
-    for (int k = 1; k < 5; ++k) h.c1[k] = (g == 1) ? x3[k - 1] : x3[3 + k];
-#pragma unroll
-    for (int k = 0; k < 5; ++k) h.c2[k] = x3[8 + k];
+    for (int s = 0; s < 3 * K; ++s) raw[s] = v[s];
+    channel_setup<K>(raw, lut_scale, h.cp);
+    // Coupling coefficients alpha_k = head[9K+k] (needed by group 1), beta_k = head[10K+k] and
+    // gamma_k = head[11K+k] (group 2): the lane's own register where its group holds the value,
+    // else pulled from the lane of the same pixel in the group that does.
+    static_for<0, K>([&](auto kc) {
+        constexpr int k = decltype(kc)::value;
+        constexpr int sa = head_slot<Net>(9 * K + k), sb = head_slot<Net>(10 * K + k), sc = head_slot<Net>(11 * K + k);
+        static_assert(sa >= 0 && sb >= 0 && sc >= 0, "every head output has a register");
+        float va, vb, vc;
+        if constexpr (sa / HS == 1) va = v[sa % HS]; else va = __shfl(v[sa % HS], nl + 16 * (sa / HS));
+        if constexpr (sb / HS == 2) vb = v[sb % HS]; else vb = __shfl(v[sb % HS], nl + 16 * (sb / HS));
+        if constexpr (sc / HS == 2) vc = v[sc % HS]; else vc = __shfl(v[sc % HS], nl + 16 * (sc / HS));
+        h.c1[k] = (g == 1) ? va : vb;
+        h.c2[k] = vc;
+    });
 }
 
 // ---------------------------------------------------------------------------
 // encode: all pixels in parallel
 // ---------------------------------------------------------------------------
-template <int T, int THREADS>
+template <class Net, int T, int THREADS>
 __global__ void __launch_bounds__(THREADS)
 encode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ img, int H, int W, uint32_t P,
               uint32_t* __restrict__ sf, float* __restrict__ params, float* __restrict__ bits, int* status) {
+    using Lay = Layout<Net>;
+    constexpr int K = Net::K, KB0 = Net::kb(0), HEAD = Net::dim(Net::kLayers);
     extern __shared__ __align__(16) uint8_t lds[];
-    copy_model_to_lds(lds, model);
+    copy_to_lds(lds, model, Lay::kModelBytes);
     __syncthreads();
-    const float2* lut = reinterpret_cast<const float2*>(lds + kLutOff);
-    const float lut_scale = *reinterpret_cast<const float*>(lds + kLutScaleOff);
+    const float2* lut = reinterpret_cast<const float2*>(lds + Lay::kLutOff);
+    const float lut_scale = *reinterpret_cast<const float*>(lds + Lay::kLutScaleOff);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
     const int g = lane >> 4, nl = lane & 15;
     const uint32_t groups = (P + 16 * T - 1) / (16 * T);
 
     for (uint32_t grp = blockIdx.x * nwaves + wave; grp < groups; grp += gridDim.x * nwaves) {
-        u32x4_t in[T][1][2];
+        u32x4_t in[T][KB0][2];
         uint32_t pix[T];   // the pixel's own bytes r | g<<8 | b<<16
-        // This lane's eight first-layer inputs are two runs of four consecutive image bytes:
-        // (row offset, byte offset within the 12-byte window of columns c-2..c+1).
-        const int drA = (g < 2) ? -2 : -1, offA = (g & 1) ? 8 : 0;
-        const int drB = (g == 0) ? -2 : (g == 2 ? -1 : 0), offB = (g == 1) ? 0 : 4;
 #pragma unroll
         for (int t = 0; t < T; ++t) {
             const uint32_t p = grp * (16 * T) + 16 * t + nl;
-            uint32_t runA = 0, runB = 0;
+            uint32_t runs[KB0][2];
+#pragma unroll
+            for (int kbi = 0; kbi < KB0; ++kbi) { runs[kbi][0] = 0; runs[kbi][1] = 0; }
             pix[t] = 0;
             if (p < P) {
                 const uint32_t rowg = p / (uint32_t)W;
@@ -150,37 +166,43 @@ encode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ img
                 } else {
                     pix[t] = (uint32_t)base[me] | ((uint32_t)base[me + 1] << 8) | ((uint32_t)base[me + 2] << 16);
                 }
-                // a run is read with one load when all its bytes lie in the image, byte by byte at the borders
-                auto load_run = [&](int dr, int off) -> uint32_t {
-                    const int rr = r + dr;
-                    const int col0 = c - 2 + (off >> 2);          // the run touches columns col0 and col0 + 1
-                    const int at = (rr * W + (c - 2)) * 3 + off;
-                    uint32_t v = 0;
-                    if (rr >= 0 && col0 >= 0 && col0 + 1 < W) {
-                        __builtin_memcpy(&v, base + at, 4);
-                    } else if (rr >= 0) {
+                // This lane's first-layer inputs are runs of four consecutive image bytes; a run is
+                // read with one load when all its bytes lie in the image, byte by byte at the borders.
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            const int col = c - 2 + (((off + i) * 11) >> 5);
-                            if (col >= 0 && col < W) v |= (uint32_t)base[at + i] << (8 * i);
+                for (int kbi = 0; kbi < KB0; ++kbi) {
+#pragma unroll
+                    for (int half = 0; half < 2; ++half) {
+                        int dr = 0, off = 0;
+                        if (!Net::run_desc(kbi, g, half, dr, off)) continue;
+                        const int rr = r + dr;
+                        const int at = (rr * W + (c - 2)) * 3 + off;
+                        const int col_first = c - 2 + ((off * 11) >> 5), col_last = c - 2 + (((off + 3) * 11) >> 5);
+                        uint32_t v = 0;
+                        if (rr >= 0 && col_first >= 0 && col_last < W) {
+                            __builtin_memcpy(&v, base + at, 4);
+                        } else if (rr >= 0) {
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) {
+                                const int col = c - 2 + (((off + i) * 11) >> 5);
+                                if (col >= 0 && col < W) v |= (uint32_t)base[at + i] << (8 * i);
+                            }
                         }
+                        runs[kbi][half] = v;
                     }
-                    return v;
-                };
-                runA = load_run(drA, offA);
-                runB = load_run(drB, offB);
+                }
             }
-            // bytes -> bf16 (exact): the upper halves of the fp32 conversions, packed in pairs
-            const uint32_t sel = 0x07060302u;
-            in[t][0][0].x = __builtin_amdgcn_perm(__float_as_uint((float)((runA >> 8) & 0xFFu)), __float_as_uint((float)(runA & 0xFFu)), sel);
-            in[t][0][0].y = __builtin_amdgcn_perm(__float_as_uint((float)(runA >> 24)), __float_as_uint((float)((runA >> 16) & 0xFFu)), sel);
-            in[t][0][0].z = __builtin_amdgcn_perm(__float_as_uint((float)((runB >> 8) & 0xFFu)), __float_as_uint((float)(runB & 0xFFu)), sel);
-            in[t][0][0].w = __builtin_amdgcn_perm(__float_as_uint((float)(runB >> 24)), __float_as_uint((float)((runB >> 16) & 0xFFu)), sel);
-            in[t][0][1] = in[t][0][0];   // unused (layer-1 inputs are exact)
+#pragma unroll
+            for (int kbi = 0; kbi < KB0; ++kbi) {
+                uint32_t a, b, c2, d;
+                run_to_bf16(runs[kbi][0], a, b);
+                run_to_bf16(runs[kbi][1], c2, d);
+                in[t][kbi][0].x = a; in[t][kbi][0].y = b; in[t][kbi][0].z = c2; in[t][kbi][0].w = d;
+                in[t][kbi][1] = in[t][kbi][0];   // unused (layer-1 inputs are exact)
+            }
         }
 
-        f32x4_t out[T][kL4_OB];
-        mlp_forward<T, (T == 1 && THREADS <= 512 ? 10 : 2), (T == 1 && THREADS <= 512 ? 8 : 2)>(lds + opaque_zero(), lane, in, out);
+        f32x4_t out[T][Lay::kHeadOB];
+        mlp_from<Net, T, (T == 1 && THREADS <= 512), 0>(lds + opaque_zero(), lane, in, out);
 
 #pragma unroll
         for (int t = 0; t < T; ++t) {
@@ -188,24 +210,24 @@ encode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ img
             const bool live = p < P;
             if (params != nullptr && live) {
 #pragma unroll
-                for (int ob = 0; ob < kL4_OB; ++ob) {
+                for (int ob = 0; ob < Lay::kHeadOB; ++ob) {
                     const float vv[4] = {out[t][ob].x, out[t][ob].y, out[t][ob].z, out[t][ob].w};
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
-                        const int idx = head_index(g, 4 * ob + i);
-                        if (idx >= 0) params[(size_t)p * PCC_HEAD_OUTPUTS + idx] = vv[i];
+                        const int idx = Net::head_index(g, 4 * ob + i);
+                        if (idx >= 0) params[(size_t)p * HEAD + idx] = vv[i];
                     }
                 }
             }
-            LaneHead h;
-            lane_head_setup(out[t], lane, lut_scale, h);
+            LaneHead<Net> h;
+            lane_head_setup<Net>(out[t], lane, lut_scale, h);
             const float rhat = (float)(pix[t] & 0xFF) * (1.0f / 256.0f);
             const float ghat = (float)((pix[t] >> 8) & 0xFF) * (1.0f / 256.0f);
-            if (g == 1) couple_green(h.cp, h.c1, rhat);
-            if (g == 2) couple_blue(h.cp, h.c1, h.c2, rhat, ghat);
+            if (g == 1) couple_green<K>(h.cp, h.c1, rhat);
+            if (g == 2) couple_blue<K>(h.cp, h.c1, h.c2, rhat, ghat);
             const int x = (int)((pix[t] >> (8 * (g & 3))) & 0xFF);   // group 3 reads the zero top byte
-            const uint32_t lo = cq_full(h.cp, x, lut);
-            const uint32_t hi = cq_full(h.cp, x + 1, lut);
+            const uint32_t lo = cq_full<K>(h.cp, x, lut);
+            const uint32_t hi = cq_full<K>(h.cp, x + 1, lut);
             uint32_t freq = hi - lo;
             if (g < 3 && live && (hi <= lo || freq > 65536u)) { set_error(status, PCC_E_INTERNAL); freq = 1; }
             if (sf != nullptr && g < 3 && live) sf[(size_t)p * 3 + g] = lo | ((freq - 1u) << 16);
@@ -325,7 +347,7 @@ rans_rows_kernel(const uint32_t* __restrict__ sf, int W, uint32_t rows, uint32_t
 
 // Single workgroup: offsets[k] = 4 * sum_{j<k} row_words[j]; header; total size.
 __global__ void __launch_bounds__(1024)
-scan_kernel(const uint32_t* __restrict__ row_words, uint32_t rows, int n, int H, int W, uint32_t dist,
+scan_kernel(const uint32_t* __restrict__ row_words, uint32_t rows, int n, int H, int W, uint32_t tag, uint32_t dist,
             uint8_t* __restrict__ stream, uint64_t* __restrict__ total_bytes) {
     __shared__ uint64_t part[1024];
     __shared__ uint64_t carry;
@@ -334,7 +356,7 @@ scan_kernel(const uint32_t* __restrict__ row_words, uint32_t rows, int n, int H,
         carry = 0;
         uint32_t* hdr = reinterpret_cast<uint32_t*>(stream);
         hdr[0] = kStreamMagic; hdr[1] = 1; hdr[2] = (uint32_t)n; hdr[3] = (uint32_t)H; hdr[4] = (uint32_t)W;
-        hdr[5] = kModelTag; hdr[6] = dist; hdr[7] = 0;
+        hdr[5] = tag; hdr[6] = dist; hdr[7] = 0;
     }
     __syncthreads();
     for (uint32_t base = 0; base < rows; base += 1024) {
@@ -380,7 +402,8 @@ compact_kernel(const uint32_t* __restrict__ slabs, const uint32_t* __restrict__ 
 // wavefront decode
 //
 // One workgroup of 4 waves owns a band of 16 image rows; step t decodes pixel
-// (r, t - 2r) of each row.  Per step:
+// (r, t - delay * r) of each row (delay = right reach of the neighbourhood + 1).
+// Per step:
 //   network   the 16 pixels form one MFMA tile; each wave computes a quarter
 //             of every layer's out-blocks with its weight slices held in
 //             registers for the whole kernel, and the layers meet in LDS
@@ -390,30 +413,37 @@ compact_kernel(const uint32_t* __restrict__ slabs, const uint32_t* __restrict__ 
 //             the output image and, for the band's last two rows, to a mailbox
 //             in global memory that the band below polls
 // ---------------------------------------------------------------------------
-#ifdef PCC_PHASE_TIMING
-// Tuning aid (off in normal builds): cycles spent per phase of a decode step,
-// accumulated by thread 0 of the band holding ticket 1 (or 0 if there is one band).
-__device__ unsigned long long g_phase_cycles[16];
-#define PCC_PHASE(k) do { if (timed) { const unsigned long long now_ = clock64(); phase_acc[k] += now_ - phase_t; phase_t = now_; } } while (0)
-#else
-#define PCC_PHASE(k) do { } while (0)
-#endif
 constexpr int kDecThreads = 256;
-constexpr int kActBytes = 5 * 2 * 64 * 16;                     // one layer's activations: [k-block][hi,lo][lane][16 B]
-// decode LDS: the normal-CDF table, two activation buffers, head outputs, mixtures, ring
-constexpr int kDLutOff = 0;
-constexpr int kDAct0Off = (kLutEntries + 1) * 8;               // 12,304
-constexpr int kDAct1Off = kDAct0Off + kActBytes;
-constexpr int kDHeadOff = kDAct1Off + kActBytes;               // [16 pixels][4 groups][16] fp32, (group, register) layout
-constexpr int kDCpOff = kDHeadOff + 16 * 64 * 4;               // [16 pixels][3 channels][16] fp32: pi[5], mu[5], a[5], pad
-// Ring of recently decoded pixels as first-layer inputs: [18 rows][16 columns][3] bf16.
-// Rows 0,1 are the two rows above the band.  Column c lives at slots c & 7 and
-// (c & 7) + 8, so the twelve values of columns c-2..c+1 are always contiguous.
-constexpr int kRingRowElems = 16 * 3;
-constexpr int kDRingOff = kDCpOff + 16 * 3 * 16 * 4;
-constexpr int kDMiscOff = kDRingOff + 18 * kRingRowElems * 2;  // ticket, abort flag
-constexpr int kDecLdsBytes = kDMiscOff + 64;
-static_assert(kDAct0Off % 16 == 0 && kDCpOff % 16 == 0, "vector alignment");
+
+// decode LDS: the CDF table, two activation buffers, head outputs, mixtures, ring
+template <class Net>
+struct DecLds {
+    static constexpr int max_kb() {
+        int m = 0;
+        for (int l = 1; l < Net::kLayers; ++l) m = Net::kb(l) > m ? Net::kb(l) : m;
+        return m;
+    }
+    static constexpr int kHS = Layout<Net>::kHeadSlots;
+    static constexpr int kActBytes = max_kb() * 2 * 64 * 16;           // one layer's activations: [k-block][hi,lo][lane][16 B]
+    static constexpr int kLutOff = 0;
+    static constexpr int kAct0Off = (kLutEntries + 1) * 8;
+    static constexpr int kAct1Off = kAct0Off + kActBytes;
+    static constexpr int kHeadOff = kAct1Off + kActBytes;              // [16 pixels][4 groups][kHS] fp32, (group, register) layout
+    static constexpr int kCpOff = kHeadOff + 16 * 4 * kHS * 4;         // [16 pixels][3 channels][16] fp32: pi[K], mu[K], a[K], pad
+    // Ring of recently decoded pixels as first-layer inputs: [18 rows][2 * kRingCols columns][3] bf16.
+    // Rows 0,1 are the two rows above the band.  Column c lives at slots c mod kRingCols and
+    // that + kRingCols, so the values of a run of neighbour columns are always contiguous.
+    static constexpr int kRingRowElems = 2 * Net::kRingCols * 3;
+    static constexpr int kRingOff = kCpOff + 16 * 3 * 16 * 4;
+    static constexpr int kMiscOff = kRingOff + 18 * kRingRowElems * 2; // ticket, abort flag
+    static constexpr int kBytes = kMiscOff + 64;
+    static_assert(kAct0Off % 16 == 0 && kHeadOff % 16 == 0 && kCpOff % 16 == 0, "vector alignment");
+    static_assert((16 * kHS) % 16 == 0 && (kRingRowElems * 2) % 4 == 0, "vector alignment");
+    // A ring row is read by the two rows below it, which trail by delay and 2 * delay columns and
+    // reach two columns further back, while the column being written and the zero columns right
+    // of the image are stored: all of these must be distinct slots.
+    static_assert(2 * Net::kDelay + 2 + Net::kDelay <= Net::kRingCols, "ring too small for the neighbourhood");
+};
 
 // All-reduce over the 16 lanes of a DPP row by rotations.
 template <int CTRL>
@@ -474,7 +504,7 @@ __device__ __forceinline__ void reader_advance(RowReader& rd, uint32_t slot, uin
 // Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for
 // every outstanding global access (pixel stores, mailbox traffic, stream-word and
 // mailbox prefetches), which would put HBM latency on the step's critical path
-// five times per step; nothing here hands global data from thread to thread.
+// several times per step; nothing here hands global data from thread to thread.
 __device__ __forceinline__ void lds_barrier() {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
     __builtin_amdgcn_s_barrier();
@@ -502,8 +532,8 @@ struct WaveLayer {
 
 // One hidden layer on this wave's out-blocks.  Same arithmetic per output element
 // as hidden_layer<> in pcc_device.h: bias, then k-blocks in order, each hi then
-// lo; ReLU; split into hi + lo.
-template <int NOB, int NKB, int SLOTS, bool SPLIT_IN>
+// lo; activation; split into hi + lo.
+template <int NOB, int NKB, int SLOTS, bool SPLIT_IN, bool LEAKY>
 __device__ __forceinline__ void dec_hidden_layer(const WaveLayer<NOB, NKB, SLOTS>& wl, int lane, int wave,
                                                  const u32x4_t (&in)[NKB][2], uint8_t* __restrict__ act_out) {
     f32x4_t acc[SLOTS];
@@ -523,8 +553,8 @@ __device__ __forceinline__ void dec_hidden_layer(const WaveLayer<NOB, NKB, SLOTS
         const int ob = wave + 4 * s;
         if (ob < NOB) {
             uint32_t l0, l1;
-            const uint32_t h0 = relu_split_bf16(acc[s].x, acc[s].y, l0);
-            const uint32_t h1 = relu_split_bf16(acc[s].z, acc[s].w, l1);
+            const uint32_t h0 = act_split_bf16<LEAKY>(acc[s].x, acc[s].y, l0);
+            const uint32_t h1 = act_split_bf16<LEAKY>(acc[s].z, acc[s].w, l1);
             // out-block ob is half (ob & 1) of k-block ob/2 of the next layer's operand
             uint8_t* dst = act_out + (((ob >> 1) * 2) * 64 + lane) * 16 + 8 * (ob & 1);
             *reinterpret_cast<uint2*>(dst) = make_uint2(h0, h1);
@@ -542,19 +572,65 @@ __device__ __forceinline__ void dec_load_act(const uint8_t* __restrict__ act, in
     }
 }
 
+// The whole network as seen by one wave: its weight slices of layers L .. last, and
+// the per-step evaluation that hands activations from layer to layer through LDS
+// (hidden layer l writes activation buffer l & 1).  Ends behind a barrier with the
+// raw head outputs in `headout`.
+template <class Net, int L, bool END = (L == Net::kLayers)>
+struct WaveNet {
+    static constexpr int NOB = Net::ob(L), NKB = Net::kb(L), SLOTS = (NOB + 3) / 4;
+    static constexpr bool kHead = L == Net::kLayers - 1;
+    WaveLayer<NOB, NKB, SLOTS> wl;
+    WaveNet<Net, L + 1> rest;
+
+    __device__ __forceinline__ void load(const uint8_t* __restrict__ model, int lane, int wave) {
+        wl.load(model + Layout<Net>::w_off(L), reinterpret_cast<const float*>(model + Layout<Net>::b_off(L)), lane, wave);
+        rest.load(model, lane, wave);
+    }
+    __device__ __forceinline__ void run(const u32x4_t (&in)[NKB][2], int lane, int wave, uint8_t* __restrict__ act0,
+                                        uint8_t* __restrict__ act1, float* __restrict__ headout) const {
+        if constexpr (kHead) {
+            static_assert(SLOTS == 1, "the head has at most four out-blocks, one per wave");
+            f32x4_t acc = wl.bias[0];
+#pragma unroll
+            for (int kb = 0; kb < NKB; ++kb) {
+                acc = mfma16(wl.a[0][kb], in[kb][0], acc);
+                acc = mfma16(wl.a[0][kb], in[kb][1], acc);
+            }
+            // registers s = 4 wave + i of group g, kept in (group, register) order
+            constexpr int HS = Layout<Net>::kHeadSlots;
+            if (wave < NOB)
+                *reinterpret_cast<f32x4_t*>(headout + (lane & 15) * (4 * HS) + (lane >> 4) * HS + 4 * wave) = acc;
+            lds_barrier();
+        } else {
+            uint8_t* out = (L & 1) ? act1 : act0;
+            dec_hidden_layer<NOB, NKB, SLOTS, (L > 0), Net::kLeaky>(wl, lane, wave, in, out);
+            lds_barrier();
+            u32x4_t nxt[Net::kb(L + 1)][2];
+            dec_load_act<Net::kb(L + 1)>(out, lane, nxt);
+            rest.run(nxt, lane, wave, act0, act1, headout);
+        }
+    }
+};
+template <class Net, int L>
+struct WaveNet<Net, L, true> {
+    __device__ __forceinline__ void load(const uint8_t* __restrict__, int, int) {}
+};
+
 // Symbol search by the 16 lanes (j = 0..15) of one pixel: two rounds of 16
 // evaluations.  All lanes of the group return the same x, start, freq.
-__device__ __forceinline__ int group_search(const ChanParams& cp, uint32_t slot, const float2* __restrict__ lut, int lane,
+template <int K>
+__device__ __forceinline__ int group_search(const ChanParams<K>& cp, uint32_t slot, const float2* __restrict__ lut, int lane,
                                             uint32_t& start, uint32_t& freq) {
     const int j = lane & 15, shift = lane & 48;
     // round 1: Cq(16 j); lanes 0..b satisfy Cq <= slot (Cq is increasing and Cq(0) = 0)
-    const uint32_t c1 = j == 0 ? 0u : cq_eval(cp, 16 * j, lut);
+    const uint32_t c1 = j == 0 ? 0u : cq_eval<K>(cp, 16 * j, lut);
     const bool p1 = c1 <= slot;
     const int b = __popcll((__ballot(p1) >> shift) & 0xFFFFull) - 1;
     const uint32_t lo1 = row_allmax(p1 ? c1 : 0u);           // Cq(16 b)
     const uint32_t hi1 = row_allmin(p1 ? 65536u : c1);       // Cq(16 b + 16)
     // round 2: Cq(16 b + j)
-    const uint32_t c2 = j == 0 ? lo1 : cq_eval(cp, 16 * b + j, lut);
+    const uint32_t c2 = j == 0 ? lo1 : cq_eval<K>(cp, 16 * b + j, lut);
     const bool p2 = c2 <= slot;
     const int cnt2 = __popcll((__ballot(p2) >> shift) & 0xFFFFull);
     start = row_allmax(p2 ? c2 : 0u);
@@ -562,23 +638,41 @@ __device__ __forceinline__ int group_search(const ChanParams& cp, uint32_t slot,
     return 16 * b + cnt2 - 1;
 }
 
+// N consecutive floats (N <= 16) from a 16-byte aligned LDS address, as whole vector reads.
+template <int N>
+__device__ __forceinline__ void lds_read_floats(const float* __restrict__ src, float (&dst)[N]) {
+    constexpr int NV = (N + 3) / 4;
+    f32x4_t v[NV];
+#pragma unroll
+    for (int i = 0; i < NV; ++i) v[i] = reinterpret_cast<const f32x4_t*>(src)[i];
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        const f32x4_t q = v[i >> 2];
+        dst[i] = (i & 3) == 0 ? q.x : (i & 3) == 1 ? q.y : (i & 3) == 2 ? q.z : q.w;
+    }
+}
+
 // MINBLOCKS = 1: all registers to one workgroup per CU (lowest latency per step; used when
 // every band gets a CU of its own).  MINBLOCKS = 2: two workgroups share a CU (a few
 // spills, ~15 % slower per step, but the second band fills the first one's stalls; used
 // when there are more bands than CUs).
-template <int MINBLOCKS>
+template <class Net, int MINBLOCKS>
 __global__ void __launch_bounds__(kDecThreads, MINBLOCKS)
 decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ stream, uint64_t nbytes, int n, int H,
               int W, int nbands, uint32_t dist, uint8_t* __restrict__ img_out, uint32_t* mailbox, int* status,
               uint32_t spin_limit) {
+    using Lay = Layout<Net>;
+    using D = DecLds<Net>;
+    constexpr int K = Net::K, HS = Lay::kHeadSlots, RC = Net::kRingCols, KB0 = Net::kb(0);
+    constexpr int kDelay = Net::kDelay, kReach = Net::kDelay - 1;   // columns right of c the neighbourhood reaches
     extern __shared__ __align__(16) uint8_t lds[];
-    float2* lut = reinterpret_cast<float2*>(lds + kDLutOff);
-    uint8_t* act0 = lds + kDAct0Off;
-    uint8_t* act1 = lds + kDAct1Off;
-    float* headout = reinterpret_cast<float*>(lds + kDHeadOff);
-    float* cpbuf = reinterpret_cast<float*>(lds + kDCpOff);
-    uint16_t* ring = reinterpret_cast<uint16_t*>(lds + kDRingOff);   // [18][16][3] bf16
-    int* misc = reinterpret_cast<int*>(lds + kDMiscOff);            // [0] ticket, [1] abort
+    float2* lut = reinterpret_cast<float2*>(lds + D::kLutOff);
+    uint8_t* act0 = lds + D::kAct0Off;
+    uint8_t* act1 = lds + D::kAct1Off;
+    float* headout = reinterpret_cast<float*>(lds + D::kHeadOff);
+    float* cpbuf = reinterpret_cast<float*>(lds + D::kCpOff);
+    uint16_t* ring = reinterpret_cast<uint16_t*>(lds + D::kRingOff);
+    int* misc = reinterpret_cast<int*>(lds + D::kMiscOff);            // [0] ticket, [1] abort
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     // network role: pixel nl of the tile, k-slot group g
@@ -590,26 +684,20 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
     // above it, which holds a smaller ticket and is therefore already running.
     if (tid == 0) { misc[0] = atomicAdd(&status[kStTicket], 1); misc[1] = 0; }
     {
-        const float2* src = reinterpret_cast<const float2*>(model + kLutOff);
+        const float2* src = reinterpret_cast<const float2*>(model + Lay::kLutOff);
         for (int i = tid; i < kLutEntries + 1; i += kDecThreads) lut[i] = src[i];
     }
-    for (int i = tid; i < 18 * kRingRowElems; i += kDecThreads) ring[i] = 0;
+    for (int i = tid; i < 18 * D::kRingRowElems; i += kDecThreads) ring[i] = 0;
 
     // this wave's weights stay in registers
-    WaveLayer<kL1_OB, kL1_KB, 3> wl1;
-    WaveLayer<kL2_OB, kL2_KB, 3> wl2;
-    WaveLayer<kL3_OB, kL3_KB, 2> wl3;
-    WaveLayer<kL4_OB, kL4_KB, 1> wl4;
-    wl1.load(model + kW1Off, reinterpret_cast<const float*>(model + kB1Off), lane, wave);
-    wl2.load(model + kW2Off, reinterpret_cast<const float*>(model + kB2Off), lane, wave);
-    wl3.load(model + kW3Off, reinterpret_cast<const float*>(model + kB3Off), lane, wave);
-    wl4.load(model + kW4Off, reinterpret_cast<const float*>(model + kB4Off), lane, wave);
+    WaveNet<Net, 0> net;
+    net.load(model, lane, wave);
     __syncthreads();
 
     const int ticket = misc[0];
     const int im = ticket / nbands, band = ticket - im * nbands;
     if (im >= n) return;
-    const float lut_scale = *reinterpret_cast<const float*>(model + kLutScaleOff);
+    const float lut_scale = *reinterpret_cast<const float*>(model + Lay::kLutScaleOff);
 
     const int r0 = band * kBandRows;
     const uint64_t rows_total = (uint64_t)n * H;
@@ -620,7 +708,7 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
         const uint32_t* hdr = reinterpret_cast<const uint32_t*>(stream);
         const uint64_t last = reinterpret_cast<const uint64_t*>(stream + kStreamHeader)[rows_total];
         if (hdr[0] != kStreamMagic || hdr[1] != 1u || hdr[2] != (uint32_t)n || hdr[3] != (uint32_t)H ||
-            hdr[4] != (uint32_t)W || hdr[5] != kModelTag || hdr[6] != dist || last != payload_bytes)
+            hdr[4] != (uint32_t)W || hdr[5] != model_tag<Net>() || hdr[6] != dist || last != payload_bytes)
             set_error(status, PCC_E_STREAM);
     }
 
@@ -645,21 +733,21 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
     uint32_t* mail_out = mailbox + ((size_t)im * nbands + band) * 2 * (size_t)W;
 
     const int last_row = min(r0 + kBandRows - 1, H - 1);
-    const int t_begin = 2 * r0, t_end = 2 * last_row + W - 1;
+    const int t_begin = kDelay * r0, t_end = kDelay * last_row + W - 1;
     const bool fetcher = band > 0 && tid < 2;     // thread 0: row r0-2 -> ring row 0; thread 1: row r0-1 -> ring row 1
     const uint32_t* mail_row = mail_in + (size_t)(tid & 1) * W;
     uint32_t pf = 0;                              // mailbox word for the next column, requested a step early
 
     // bf16 of the three channels of pixel word px into both copies of column cc of a ring row
     auto ring_put = [&](int rrow, int cc, uint32_t px) {
-        uint16_t* d = ring + rrow * kRingRowElems + (cc & 7) * 3;
+        uint16_t* d = ring + rrow * D::kRingRowElems + (cc & (RC - 1)) * 3;
         const uint16_t v0 = (uint16_t)byte_to_bf16(px & 0xFFu), v1 = (uint16_t)byte_to_bf16((px >> 8) & 0xFFu),
                        v2 = (uint16_t)byte_to_bf16((px >> 16) & 0xFFu);
         d[0] = v0; d[1] = v1; d[2] = v2;
-        d[24] = v0; d[25] = v1; d[26] = v2;
+        d[3 * RC] = v0; d[3 * RC + 1] = v1; d[3 * RC + 2] = v2;
     };
-    // Bring columns 0 and 1 of the two rows above the band into the ring, then keep
-    // one column ahead: the step at t needs column (t - t_begin) + 1.
+    // Bring columns 0 .. reach of the two rows above the band into the ring, then keep
+    // one column ahead: the step at t needs column (t - t_begin) + reach.
     auto fetch_column = [&](int cc, uint32_t have) -> bool {   // returns false on abort
         uint32_t v = have, spins = 0;
         while (!(v & kMailTag)) {
@@ -676,9 +764,10 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
         return true;
     };
     if (fetcher) {
-        bool ok = fetch_column(0, 0u);
-        if (ok && W > 1) ok = fetch_column(1, 0u);
-        if (ok && W > 2) pf = __hip_atomic_load(mail_row + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        bool ok = true;
+        for (int cc = 0; cc <= kReach; ++cc)
+            if (ok && cc < W) ok = fetch_column(cc, 0u);
+        if (ok && W > kReach + 1) pf = __hip_atomic_load(mail_row + kReach + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (!ok) {
             __hip_atomic_store(&status[kStAbort], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             misc[1] = 1;
@@ -686,140 +775,129 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
     }
     lds_barrier();
 
-    // network role: this lane's eight first-layer inputs are two runs of four
-    // consecutive ring values (row, offset within the 12-value window of columns c-2..c+1)
-    const int gA_row = nl + (g >= 2 ? 1 : 0), gA_off = (g & 1) ? 8 : 0;
-    const int gB_row = nl + (g == 0 ? 0 : (g == 2 ? 1 : 2)), gB_off = (g == 1) ? 0 : 4;
-    const uint16_t* gA = ring + gA_row * kRingRowElems + gA_off;
-    const uint16_t* gB = ring + gB_row * kRingRowElems + gB_off;
+    // network role: this lane's first-layer inputs are runs of four consecutive ring values
+    // (ring row, offset within the row's window that starts at column c-2); a run the
+    // network does not use reads as zero
+    const uint16_t* run_ptr[KB0][2];
+    bool run_used[KB0][2];
+#pragma unroll
+    for (int kbi = 0; kbi < KB0; ++kbi) {
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            int dr = 0, off = 0;
+            run_used[kbi][half] = Net::run_desc(kbi, g, half, dr, off);
+            run_ptr[kbi][half] = ring + (nl + 2 + dr) * D::kRingRowElems + off;
+        }
+    }
 
-#ifdef PCC_PHASE_TIMING
-    const bool timed = tid == 0 && ticket == (nbands * n > 1 ? 1 : 0);
-    unsigned long long phase_acc[16] = {};
-    unsigned long long phase_t = clock64();
-#endif
     for (int t = t_begin; t <= t_end; ++t) {
         if ((t & 7) == 0 && misc[1] != 0) break;  // uniform: written before the last barrier; a late exit only decodes garbage
-        PCC_PHASE(15);
 
         // ---- gather C_ij from the ring (zeros stand for pixels outside the image); every wave builds the full tile
-        u32x4_t in1[1][2];
+        u32x4_t in1[KB0][2];
         {
-            const int c = t - 2 * (r0 + nl);
-            const int w0 = ((c - 2) & 7) * 3;
-            uint32_t v[8];
+            const int c = t - kDelay * (r0 + nl);
+            const int w0 = ((c - 2) & (RC - 1)) * 3;
+            uint32_t v[KB0][8];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) { v[i] = gA[w0 + i]; v[4 + i] = gB[w0 + i]; }
+            for (int kbi = 0; kbi < KB0; ++kbi) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) { v[kbi][i] = run_ptr[kbi][0][w0 + i]; v[kbi][4 + i] = run_ptr[kbi][1][w0 + i]; }
+            }
             // one batch of LDS reads
-            asm volatile("" : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]), "+v"(v[4]), "+v"(v[5]), "+v"(v[6]), "+v"(v[7]));
-            in1[0][0].x = v[0] | (v[1] << 16);
-            in1[0][0].y = v[2] | (v[3] << 16);
-            in1[0][0].z = v[4] | (v[5] << 16);
-            in1[0][0].w = v[6] | (v[7] << 16);
-            in1[0][1] = in1[0][0];   // unused (layer-1 inputs are exact)
+            static_assert(KB0 == 1 || KB0 == 2, "the scheduling barrier below lists the reads explicitly");
+            if constexpr (KB0 == 1)
+                asm volatile("" : "+v"(v[0][0]), "+v"(v[0][1]), "+v"(v[0][2]), "+v"(v[0][3]), "+v"(v[0][4]), "+v"(v[0][5]),
+                                  "+v"(v[0][6]), "+v"(v[0][7]));
+            else
+                asm volatile("" : "+v"(v[0][0]), "+v"(v[0][1]), "+v"(v[0][2]), "+v"(v[0][3]), "+v"(v[0][4]), "+v"(v[0][5]),
+                                  "+v"(v[0][6]), "+v"(v[0][7]), "+v"(v[KB0 - 1][0]), "+v"(v[KB0 - 1][1]), "+v"(v[KB0 - 1][2]),
+                                  "+v"(v[KB0 - 1][3]), "+v"(v[KB0 - 1][4]), "+v"(v[KB0 - 1][5]), "+v"(v[KB0 - 1][6]),
+                                  "+v"(v[KB0 - 1][7]));
+#pragma unroll
+            for (int kbi = 0; kbi < KB0; ++kbi) {
+                const uint32_t m0 = run_used[kbi][0] ? 0xFFFFFFFFu : 0u, m1 = run_used[kbi][1] ? 0xFFFFFFFFu : 0u;
+                in1[kbi][0].x = (v[kbi][0] | (v[kbi][1] << 16)) & m0;
+                in1[kbi][0].y = (v[kbi][2] | (v[kbi][3] << 16)) & m0;
+                in1[kbi][0].z = (v[kbi][4] | (v[kbi][5] << 16)) & m1;
+                in1[kbi][0].w = (v[kbi][6] | (v[kbi][7] << 16)) & m1;
+                in1[kbi][1] = in1[kbi][0];   // unused (layer-1 inputs are exact)
+            }
         }
-        PCC_PHASE(0);
 
         // ---- network, layers meeting in LDS
-        dec_hidden_layer<kL1_OB, kL1_KB, 3, false>(wl1, lane, wave, in1, act0);
-        lds_barrier();
-        PCC_PHASE(1);
-        {
-            u32x4_t in[kL2_KB][2];
-            dec_load_act<kL2_KB>(act0, lane, in);
-            dec_hidden_layer<kL2_OB, kL2_KB, 3, true>(wl2, lane, wave, in, act1);
-        }
-        lds_barrier();
-        PCC_PHASE(2);
-        {
-            u32x4_t in[kL3_KB][2];
-            dec_load_act<kL3_KB>(act1, lane, in);
-            dec_hidden_layer<kL3_OB, kL3_KB, 2, true>(wl3, lane, wave, in, act0);
-        }
-        lds_barrier();
-        PCC_PHASE(3);
-        {
-            u32x4_t in[kL4_KB][2];
-            dec_load_act<kL4_KB>(act0, lane, in);
-            f32x4_t acc = wl4.bias[0];
-#pragma unroll
-            for (int kb = 0; kb < kL4_KB; ++kb) {
-                acc = mfma16(wl4.a[0][kb], in[kb][0], acc);
-                acc = mfma16(wl4.a[0][kb], in[kb][1], acc);
-            }
-            // registers s = 4 wave + i of group g, kept in (group, register) order
-            *reinterpret_cast<f32x4_t*>(headout + nl * 64 + g * 16 + 4 * wave) = acc;
-        }
-        lds_barrier();
-        PCC_PHASE(4);
+        net.run(in1, lane, wave, act0, act1, headout);
 
-        // ---- mixtures: lane j < 15 of pixel q prepares component j % 5 of channel j / 5
-        if (j < 15) {
-            const int ch = j / 5, k = j - 5 * ch;
-            const f32x4_t* src = reinterpret_cast<const f32x4_t*>(headout + q * 64 + ch * 16);
-            const f32x4_t v0 = src[0], v1 = src[1], v2 = src[2], v3 = src[3];
-            const float raw[15] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w, v2.x, v2.y, v2.z, v2.w, v3.x, v3.y, v3.z};
-            ChanParams all;
-            channel_setup(raw, lut_scale, all);
+        // ---- mixtures: lane j < 3K of pixel q prepares component j % K of channel j / K
+        if (j < 3 * K) {
+            const int ch = j / K, k = j - K * ch;
+            float raw[3 * K];
+            lds_read_floats<3 * K>(headout + q * (4 * HS) + ch * HS, raw);
+            ChanParams<K> all;
+            channel_setup<K>(raw, lut_scale, all);
             float pk = all.pi[0], mk = all.mu[0], ak = all.a[0];
 #pragma unroll
-            for (int kk = 1; kk < 5; ++kk) if (k == kk) { pk = all.pi[kk]; mk = all.mu[kk]; ak = all.a[kk]; }
+            for (int kk = 1; kk < K; ++kk) if (k == kk) { pk = all.pi[kk]; mk = all.mu[kk]; ak = all.a[kk]; }
             float* dst = cpbuf + (q * 3 + ch) * 16 + k;
-            dst[0] = pk; dst[5] = mk; dst[10] = ak;
+            dst[0] = pk; dst[K] = mk; dst[2 * K] = ak;
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
 
         // everything the three searches need, in one batch of LDS reads
-        ChanParams cpr, cpg, cpb;
-        float alpha[5], beta[5], gamma[5];
+        ChanParams<K> cpr, cpg, cpb;
+        float alpha[K], beta[K], gamma[K];
         {
-            auto load_cp = [&](int ch, ChanParams& cp) {
-                const f32x4_t* src = reinterpret_cast<const f32x4_t*>(cpbuf + (q * 3 + ch) * 16);
-                const f32x4_t v0 = src[0], v1 = src[1], v2 = src[2], v3 = src[3];
-                cp.pi[0] = v0.x; cp.pi[1] = v0.y; cp.pi[2] = v0.z; cp.pi[3] = v0.w; cp.pi[4] = v1.x;
-                cp.mu[0] = v1.y; cp.mu[1] = v1.z; cp.mu[2] = v1.w; cp.mu[3] = v2.x; cp.mu[4] = v2.y;
-                cp.a[0] = v2.z; cp.a[1] = v2.w; cp.a[2] = v3.x; cp.a[3] = v3.y; cp.a[4] = v3.z;
+            auto load_cp = [&](int ch, ChanParams<K>& cp) {
+                float v[3 * K];
+                lds_read_floats<3 * K>(cpbuf + (q * 3 + ch) * 16, v);
+#pragma unroll
+                for (int k = 0; k < K; ++k) { cp.pi[k] = v[k]; cp.mu[k] = v[K + k]; cp.a[k] = v[2 * K + k]; }
             };
             load_cp(0, cpr); load_cp(1, cpg); load_cp(2, cpb);
-            const float* hq = headout + q * 64;
-            const f32x4_t* g3 = reinterpret_cast<const f32x4_t*>(hq + 48);
-            const f32x4_t c0 = g3[0], c1 = g3[1], c2 = g3[2];
-            alpha[0] = hq[16 + 15]; alpha[1] = c0.x; alpha[2] = c0.y; alpha[3] = c0.z; alpha[4] = c0.w;
-            beta[0] = hq[32 + 15]; beta[1] = c1.x; beta[2] = c1.y; beta[3] = c1.z; beta[4] = c1.w;
-            gamma[0] = c2.x; gamma[1] = c2.y; gamma[2] = c2.z; gamma[3] = c2.w; gamma[4] = hq[48 + 12];
+            // coupling coefficients: canonical head outputs 9K.. (alpha), 10K.. (beta), 11K.. (gamma), wherever
+            // the head's (group, register) layout put them
+            const float* hq = headout + q * (4 * HS);
+            float g3[HS];                           // group 3 holds most of them: whole vector reads
+            lds_read_floats<HS>(hq + 3 * HS, g3);
+            static_for<0, K>([&](auto kc) {
+                constexpr int k = decltype(kc)::value;
+                constexpr int sa = head_slot<Net>(9 * K + k), sb = head_slot<Net>(10 * K + k), sc = head_slot<Net>(11 * K + k);
+                if constexpr (sa / HS == 3) alpha[k] = g3[sa % HS]; else alpha[k] = hq[sa];
+                if constexpr (sb / HS == 3) beta[k] = g3[sb % HS]; else beta[k] = hq[sb];
+                if constexpr (sc / HS == 3) gamma[k] = g3[sc % HS]; else gamma[k] = hq[sc];
+            });
         }
-        PCC_PHASE(5);
 
-        const int c = t - 2 * qrow;
+        const int c = t - kDelay * qrow;
         const bool active = qrow_ok && c >= 0 && c < W;
         uint32_t start, freq;
         // R
         uint32_t slot = (uint32_t)rd.x & 0xFFFFu;
-        const int sr = group_search(cpr, slot, lut, lane, start, freq);
+        const int sr = group_search<K>(cpr, slot, lut, lane, start, freq);
         reader_advance(rd, slot, start, freq, j, active);
         const float rhat = (float)sr * (1.0f / 256.0f);
-        PCC_PHASE(6);
         // G given R
-        couple_green(cpg, alpha, rhat);
+        couple_green<K>(cpg, alpha, rhat);
         slot = (uint32_t)rd.x & 0xFFFFu;
-        const int sg = group_search(cpg, slot, lut, lane, start, freq);
+        const int sg = group_search<K>(cpg, slot, lut, lane, start, freq);
         reader_advance(rd, slot, start, freq, j, active);
         const float ghat = (float)sg * (1.0f / 256.0f);
-        PCC_PHASE(7);
         // B given R, G
-        couple_blue(cpb, beta, gamma, rhat, ghat);
+        couple_blue<K>(cpb, beta, gamma, rhat, ghat);
         slot = (uint32_t)rd.x & 0xFFFFu;
-        const int sb = group_search(cpb, slot, lut, lane, start, freq);
+        const int sb = group_search<K>(cpb, slot, lut, lane, start, freq);
         reader_advance(rd, slot, start, freq, j, active);
-        PCC_PHASE(8);
 
         // ---- publish
         if (j == 0 && active) {
             const uint32_t px = (uint32_t)sr | ((uint32_t)sg << 8) | ((uint32_t)sb << 16);
             ring_put(q + 2, c, px);
-            if (c == W - 1) ring_put(q + 2, W, 0u);   // the column right of the image reads as zero
+            if (c == W - 1) {                       // the columns right of the image read as zero
+#pragma unroll
+                for (int z = 0; z < kReach; ++z) ring_put(q + 2, W + z, 0u);
+            }
             uint8_t* o = out_img + ((size_t)qrow * W + c) * 3;
             o[0] = (uint8_t)sr; o[1] = (uint8_t)sg; o[2] = (uint8_t)sb;
             if (q >= kBandRows - 2)
@@ -829,8 +907,8 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
         }
         // ---- rows above the band: column needed by the next step, and request the one after
         if (fetcher) {
-            const int cc = t - t_begin + 2;
-            if (cc == W) ring_put(tid & 1, W, 0u);    // the column right of the image reads as zero
+            const int cc = t - t_begin + kReach + 1;
+            if (cc >= W && cc < W + kReach) ring_put(tid & 1, cc, 0u);    // the columns right of the image read as zero
             if (cc < W && t < t_end) {
                 if (!fetch_column(cc, pf)) {
                     __hip_atomic_store(&status[kStAbort], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -839,42 +917,39 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
                 pf = (cc + 1 < W) ? __hip_atomic_load(mail_row + cc + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
             }
         }
-        PCC_PHASE(9);
         lds_barrier();
-        PCC_PHASE(10);
     }
-#ifdef PCC_PHASE_TIMING
-    if (timed) for (int k = 0; k < 16; ++k) g_phase_cycles[k] = phase_acc[k];
-#endif
 }
 
 // ---------------------------------------------------------------------------
 // test hook: full tables from given head outputs
 // ---------------------------------------------------------------------------
+template <class Net>
 __global__ void __launch_bounds__(256)
 cdf_tables_kernel(const uint8_t* __restrict__ model, const float* __restrict__ params, const uint8_t* __restrict__ rg,
                   size_t count, uint32_t* __restrict__ cq) {
+    constexpr int K = Net::K, HEAD = Net::dim(Net::kLayers);
     extern __shared__ __align__(16) uint8_t lds[];
     float2* lut = reinterpret_cast<float2*>(lds);
-    const float2* src = reinterpret_cast<const float2*>(model + kLutOff);
+    const float2* src = reinterpret_cast<const float2*>(model + Layout<Net>::kLutOff);
     for (int i = threadIdx.x; i < kLutEntries + 1; i += blockDim.x) lut[i] = src[i];
     __syncthreads();
     const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= count * 3) return;
     const size_t p = idx / 3;
     const int ch = (int)(idx - p * 3);
-    const float* o = params + p * PCC_HEAD_OUTPUTS;
-    float raw[15];
-    for (int s = 0; s < 15; ++s) raw[s] = o[15 * ch + s];
-    ChanParams cp;
-    channel_setup(raw, *reinterpret_cast<const float*>(model + kLutScaleOff), cp);
+    const float* o = params + p * HEAD;
+    float raw[3 * K];
+    for (int s = 0; s < 3 * K; ++s) raw[s] = o[3 * K * ch + s];
+    ChanParams<K> cp;
+    channel_setup<K>(raw, *reinterpret_cast<const float*>(model + Layout<Net>::kLutScaleOff), cp);
     const float rhat = (float)rg[2 * p] * (1.0f / 256.0f), ghat = (float)rg[2 * p + 1] * (1.0f / 256.0f);
-    float c1[5], c2[5];
-    for (int k = 0; k < 5; ++k) { c1[k] = ch == 1 ? o[45 + k] : o[50 + k]; c2[k] = o[55 + k]; }
-    if (ch == 1) couple_green(cp, c1, rhat);
-    if (ch == 2) couple_blue(cp, c1, c2, rhat, ghat);
+    float c1[K], c2[K];
+    for (int k = 0; k < K; ++k) { c1[k] = ch == 1 ? o[9 * K + k] : o[10 * K + k]; c2[k] = o[11 * K + k]; }
+    if (ch == 1) couple_green<K>(cp, c1, rhat);
+    if (ch == 2) couple_blue<K>(cp, c1, c2, rhat, ghat);
     uint32_t* dst = cq + idx * 257;
-    for (int e = 0; e <= 256; ++e) dst[e] = cq_full(cp, e, lut);
+    for (int e = 0; e <= 256; ++e) dst[e] = cq_full<K>(cp, e, lut);
 }
 
 }  // namespace pcc
@@ -884,8 +959,11 @@ cdf_tables_kernel(const uint8_t* __restrict__ model, const float* __restrict__ p
 // ===========================================================================
 using namespace pcc;
 
+enum { kNetWorkload = 0, kNetPaper = 1 };
+
 struct pcc_ctx {
     int device = 0;
+    int net = kNetWorkload;        // which network description the blob matched
     uint8_t* d_model = nullptr;
     // workspace (grown on demand)
     uint8_t* d_ws = nullptr;
@@ -968,6 +1046,156 @@ bool dims_ok(int n, int H, int W) {
            (uint64_t)H * W * 3 < (1ull << 31);   // byte offsets within one image are 32-bit
 }
 
+// Does the blob header describe network Net?  (activation id 0 = ReLU, 1 = LeakyReLU 0.01)
+template <class Net>
+bool header_matches(const uint8_t* p) {
+    if (rd32(p + 8) != (uint32_t)Net::kLayers) return false;
+    for (int i = 0; i < 8; ++i)
+        if (rd32(p + 12 + 4 * i) != (i <= Net::kLayers ? (uint32_t)Net::dim(i) : 0u)) return false;
+    return rd32(p + 44) == (uint32_t)Net::K && rd32(p + 48) == (uint32_t)Net::kNbhd &&
+           rd32(p + 52) == (uint32_t)Net::kDelay && rd32(p + 56) == (Net::kLeaky ? 1u : 0u);
+}
+
+// Weights and biases of the blob -> MFMA operand tiles in the order the kernels read them.
+template <class Net>
+int pack_model(const uint8_t* p, size_t blob_bytes, uint32_t dist, std::vector<uint8_t>& image) {
+    using Lay = Layout<Net>;
+    constexpr int NL = Net::kLayers;
+    size_t need = 64;
+    for (int l = 0; l < NL; ++l) need += 4 * ((size_t)Net::dim(l) * Net::dim(l + 1) + Net::dim(l + 1));
+    if (blob_bytes != need) return PCC_E_BLOB;
+    const uint8_t* wsrc[NL];
+    const uint8_t* bsrc[NL];
+    const uint8_t* q = p + 64;
+    for (int l = 0; l < NL; ++l) {
+        wsrc[l] = q; q += 4 * (size_t)Net::dim(l) * Net::dim(l + 1);
+        bsrc[l] = q; q += 4 * (size_t)Net::dim(l + 1);
+    }
+    auto Wat = [&](int l, int o, int i) { return rdf(wsrc[l] + 4 * ((size_t)o * Net::dim(l) + i)); };
+    auto Bat = [&](int l, int o) { return rdf(bsrc[l] + 4 * (size_t)o); };
+
+    image.assign(Lay::kModelBytes, 0);
+    uint16_t* w16 = reinterpret_cast<uint16_t*>(image.data());
+    for (int l = 0; l < NL; ++l) {
+        const int nob = Net::ob(l), nkb = Net::kb(l);
+        const bool head = l == NL - 1;
+        for (int ob = 0; ob < nob; ++ob)
+            for (int kb = 0; kb < nkb; ++kb)
+                for (int lane = 0; lane < 64; ++lane)
+                    for (int i = 0; i < 8; ++i) {
+                        const int m = lane & 15, g = lane >> 4;
+                        // output feature of A row m of this out-block
+                        const int o = head ? Net::head_index(m >> 2, 4 * ob + (m & 3)) : 16 * ob + m;
+                        // input feature of k-slot (g, i) of this k-block
+                        const int in = l == 0 ? in1_index<Net>(kb, g, i) : 32 * kb + kslot_feature(g, i);
+                        float v = 0.0f;
+                        if (o >= 0 && o < Net::dim(l + 1) && in >= 0 && in < Net::dim(l)) v = Wat(l, o, in);
+                        uint16_t h;
+                        if (!bf16_exact(v, &h)) return PCC_E_BLOB;
+                        if (l == 0 && v != 0.0f) {
+                            // fold the 1/256 input scaling into the first layer: exact unless it underflows
+                            const float s = v * (1.0f / 256.0f);
+                            if (!bf16_exact(s, &h) || s * 256.0f != v) return PCC_E_BLOB;
+                        }
+                        w16[(Lay::w_off(l) + (((ob * nkb + kb) * 64 + lane) * 16)) / 2 + i] = h;
+                    }
+        float* b = reinterpret_cast<float*>(image.data() + Lay::b_off(l));
+        for (int s = 0; s < 16 * nob; ++s) {
+            const int ob = s >> 4, m = s & 15;
+            const int o = head ? Net::head_index(m >> 2, 4 * ob + (m & 3)) : s;
+            b[s] = (o >= 0 && o < Net::dim(l + 1)) ? Bat(l, o) : 0.0f;
+        }
+    }
+    // Component CDF table in units of 2^-24 so that forward differences are exact in fp32.
+    float* lut = reinterpret_cast<float*>(image.data() + Lay::kLutOff);
+    const double lut_scale = dist == 0 ? (double)kLutScaleGaussian : (double)kLutScaleLogistic;
+    *reinterpret_cast<float*>(image.data() + Lay::kLutScaleOff) = (float)lut_scale;
+    std::vector<double> tq(kLutEntries + 1);
+    for (int i = 0; i < kLutEntries; ++i) {
+        const double z = (i - 768) / lut_scale;
+        const double F = dist == 0 ? 0.5 * erfc(-z / sqrt(2.0)) : 1.0 / (1.0 + exp(-z));
+        tq[i] = nearbyint(F * 16777216.0);
+    }
+    tq[0] = 0.0;
+    tq[kLutEntries - 1] = 16777216.0;
+    tq[kLutEntries] = tq[kLutEntries - 1];
+    for (int i = 0; i < kLutEntries; ++i) {
+        lut[2 * i] = (float)(tq[i] / 16777216.0);
+        lut[2 * i + 1] = (float)((tq[i + 1] - tq[i]) / 16777216.0);
+    }
+    lut[2 * kLutEntries] = 1.0f;
+    lut[2 * kLutEntries + 1] = 0.0f;
+    return PCC_OK;
+}
+
+template <class Net>
+bool set_kernel_attributes() {
+    const int enc = Layout<Net>::kModelBytes, dec = DecLds<Net>::kBytes;
+    bool ok = true;
+    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void*>(&encode_kernel<Net, 1, 512>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, enc) == hipSuccess;
+    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void*>(&encode_kernel<Net, 2, 512>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, enc) == hipSuccess;
+    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void*>(&encode_kernel<Net, 1, 1024>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, enc) == hipSuccess;
+    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_kernel<Net, 1>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, dec) == hipSuccess;
+    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_kernel<Net, 2>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, dec) == hipSuccess;
+    return ok;
+}
+
+template <class Net>
+int launch_encode(pcc_ctx* ctx, const uint8_t* d_img, int n, int H, int W, uint32_t* sf, float* params, float* bits,
+                  hipStream_t st) {
+    constexpr int kLds = Layout<Net>::kModelBytes;
+    const uint32_t P = (uint32_t)((uint64_t)n * H * W);
+    const EncodeVariant ev = kEncodeVariants[ctx->encode_variant];
+    const uint32_t per_block = 16u * ev.tiles * (ev.threads / 64);
+    uint32_t blocks = (P + per_block - 1) / per_block;
+    const uint32_t cus = ctx->num_cus > 0 ? (uint32_t)ctx->num_cus : 256u;
+    if (blocks > cus) blocks = cus;   // persistent: one workgroup per CU, looping over pixel groups
+    switch (ctx->encode_variant) {
+        case 0:
+            hipLaunchKernelGGL((encode_kernel<Net, 1, 512>), dim3(blocks), dim3(512), kLds, st, ctx->d_model, d_img, H, W, P,
+                               sf, params, bits, ctx->d_status);
+            break;
+        case 1:
+            hipLaunchKernelGGL((encode_kernel<Net, 2, 512>), dim3(blocks), dim3(512), kLds, st, ctx->d_model, d_img, H, W, P,
+                               sf, params, bits, ctx->d_status);
+            break;
+        default:
+            hipLaunchKernelGGL((encode_kernel<Net, 1, 1024>), dim3(blocks), dim3(1024), kLds, st, ctx->d_model, d_img, H, W,
+                               P, sf, params, bits, ctx->d_status);
+            break;
+    }
+    return hipGetLastError() == hipSuccess ? PCC_OK : PCC_E_HIP;
+}
+
+int launch_encode_any(pcc_ctx* ctx, const uint8_t* d_img, int n, int H, int W, uint32_t* sf, float* params, float* bits,
+                      hipStream_t st) {
+    return ctx->net == kNetPaper ? launch_encode<NetPaper>(ctx, d_img, n, H, W, sf, params, bits, st)
+                                 : launch_encode<NetWorkload>(ctx, d_img, n, H, W, sf, params, bits, st);
+}
+
+template <class Net>
+void launch_decode(pcc_ctx* ctx, const uint8_t* d_stream, size_t nbytes, int n, int H, int W, int nbands,
+                   uint8_t* d_img_out, uint32_t* d_mail, uint32_t spin_limit, hipStream_t st) {
+    constexpr int kLds = DecLds<Net>::kBytes;
+    const uint32_t grid = (uint32_t)(n * nbands);
+    const uint32_t cus = ctx->num_cus > 0 ? (uint32_t)ctx->num_cus : 256u;
+    if (grid <= cus)
+        hipLaunchKernelGGL((decode_kernel<Net, 1>), dim3(grid), dim3(kDecThreads), kLds, st, ctx->d_model, d_stream,
+                           (uint64_t)nbytes, n, H, W, nbands, ctx->dist, d_img_out, d_mail, ctx->d_status, spin_limit);
+    else
+        hipLaunchKernelGGL((decode_kernel<Net, 2>), dim3(grid), dim3(kDecThreads), kLds, st, ctx->d_model, d_stream,
+                           (uint64_t)nbytes, n, H, W, nbands, ctx->dist, d_img_out, d_mail, ctx->d_status, spin_limit);
+}
+
+inline int head_outputs(const pcc_ctx* ctx) {
+    return ctx->net == kNetPaper ? NetPaper::dim(NetPaper::kLayers) : NetWorkload::dim(NetWorkload::kLayers);
+}
+
 }  // namespace
 
 extern "C" {
@@ -992,112 +1220,47 @@ size_t pcc_stream_bound(int n, int H, int W) {
     return (size_t)kStreamHeader + 8 * (rows + 1) + rows * 4 * slab_words(W);
 }
 
-long pcc_wavefront_steps(int H, int W) { return (long)W + 2L * (H - 1); }
+long pcc_wavefront_steps(int H, int W, int delay) {
+    if (H < 1 || W < 1 || delay < 1) return 0;
+    return (long)W + (long)delay * (H - 1);
+}
 
 int pcc_create(pcc_ctx** out, const void* h_blob, size_t blob_bytes, int hip_device) {
     if (!out || !h_blob) return PCC_E_ARG;
     *out = nullptr;
     const uint8_t* p = (const uint8_t*)h_blob;
-    static const int dims[5] = {30, 160, 160, 128, 60};
-    if (blob_bytes < 64 || rd32(p) != kBlobMagic || rd32(p + 4) != 1u || rd32(p + 8) != 4u) return PCC_E_BLOB;
-    for (int i = 0; i < 5; ++i) if (rd32(p + 12 + 4 * i) != (uint32_t)dims[i]) return PCC_E_BLOB;
+    if (blob_bytes < 64 || rd32(p) != kBlobMagic || rd32(p + 4) != 1u) return PCC_E_BLOB;
     const uint32_t dist = rd32(p + 60);   // 0 = Gaussian mixture (Eq. (1)), 1 = logistic mixture (Eq. (8))
-    if (rd32(p + 44) != 5u || rd32(p + 48) != 10u || rd32(p + 52) != 2u || rd32(p + 56) != 0u || dist > 1u)
-        return PCC_E_BLOB;
-    size_t need = 64;
-    for (int l = 0; l < 4; ++l) need += 4 * ((size_t)dims[l] * dims[l + 1] + dims[l + 1]);
-    if (blob_bytes != need) return PCC_E_BLOB;
+    if (dist > 1u) return PCC_E_BLOB;
+    int net;
+    if (header_matches<NetWorkload>(p)) net = kNetWorkload;
+    else if (header_matches<NetPaper>(p)) net = kNetPaper;
+    else return PCC_E_BLOB;
 
-    const uint8_t* wsrc[4];
-    const uint8_t* bsrc[4];
-    const uint8_t* q = p + 64;
-    for (int l = 0; l < 4; ++l) {
-        wsrc[l] = q; q += 4 * (size_t)dims[l] * dims[l + 1];
-        bsrc[l] = q; q += 4 * (size_t)dims[l + 1];
-    }
-    auto Wat = [&](int l, int o, int i) { return rdf(wsrc[l] + 4 * ((size_t)o * dims[l] + i)); };
-    auto Bat = [&](int l, int o) { return rdf(bsrc[l] + 4 * (size_t)o); };
-
-    std::vector<uint8_t> image(kModelBytes, 0);
-    uint16_t* w16 = reinterpret_cast<uint16_t*>(image.data());
-    static const int nob[4] = {kL1_OB, kL2_OB, kL3_OB, kL4_OB}, nkb[4] = {kL1_KB, kL2_KB, kL3_KB, kL4_KB};
-    static const int woff[4] = {kW1Off, kW2Off, kW3Off, kW4Off}, boff[4] = {kB1Off, kB2Off, kB3Off, kB4Off};
-    for (int l = 0; l < 4; ++l) {
-        for (int ob = 0; ob < nob[l]; ++ob)
-            for (int kb = 0; kb < nkb[l]; ++kb)
-                for (int lane = 0; lane < 64; ++lane)
-                    for (int i = 0; i < 8; ++i) {
-                        const int m = lane & 15, g = lane >> 4;
-                        // output feature of A row m of this out-block
-                        const int o = l < 3 ? 16 * ob + m : head_index(m >> 2, 4 * ob + (m & 3));
-                        // input feature of k-slot (g, i) of this k-block
-                        const int in = l == 0 ? in1_index(g, i) : 32 * kb + kslot_feature(g, i);
-                        float v = 0.0f;
-                        if (o >= 0 && o < dims[l + 1] && in >= 0 && in < dims[l]) v = Wat(l, o, in);
-                        uint16_t h;
-                        if (!bf16_exact(v, &h)) return PCC_E_BLOB;
-                        if (l == 0 && v != 0.0f) {
-                            // fold the 1/256 input scaling into the first layer: exact unless it underflows
-                            const float s = v * (1.0f / 256.0f);
-                            if (!bf16_exact(s, &h) || s * 256.0f != v) return PCC_E_BLOB;
-                        }
-                        w16[(woff[l] + (((ob * nkb[l] + kb) * 64 + lane) * 16)) / 2 + i] = h;
-                    }
-        float* b = reinterpret_cast<float*>(image.data() + boff[l]);
-        const int padded = 16 * nob[l];
-        for (int s = 0; s < padded; ++s) {
-            const int ob = s >> 4, m = s & 15;
-            const int o = l < 3 ? s : head_index(m >> 2, 4 * ob + (m & 3));
-            b[s] = (o >= 0 && o < dims[l + 1]) ? Bat(l, o) : 0.0f;
-        }
-    }
-    // Component CDF table in units of 2^-24 so that forward differences are exact in fp32.
-    float* lut = reinterpret_cast<float*>(image.data() + kLutOff);
-    const double lut_scale = dist == 0 ? (double)kLutScaleGaussian : (double)kLutScaleLogistic;
-    *reinterpret_cast<float*>(image.data() + kLutScaleOff) = (float)lut_scale;
-    std::vector<double> tq(kLutEntries + 1);
-    for (int i = 0; i < kLutEntries; ++i) {
-        const double z = (i - 768) / lut_scale;
-        const double F = dist == 0 ? 0.5 * erfc(-z / sqrt(2.0)) : 1.0 / (1.0 + exp(-z));
-        tq[i] = nearbyint(F * 16777216.0);
-    }
-    tq[0] = 0.0;
-    tq[kLutEntries - 1] = 16777216.0;
-    tq[kLutEntries] = tq[kLutEntries - 1];
-    for (int i = 0; i < kLutEntries; ++i) {
-        lut[2 * i] = (float)(tq[i] / 16777216.0);
-        lut[2 * i + 1] = (float)((tq[i + 1] - tq[i]) / 16777216.0);
-    }
-    lut[2 * kLutEntries] = 1.0f;
-    lut[2 * kLutEntries + 1] = 0.0f;
+    std::vector<uint8_t> image;
+    const int prc = net == kNetPaper ? pack_model<NetPaper>(p, blob_bytes, dist, image)
+                                     : pack_model<NetWorkload>(p, blob_bytes, dist, image);
+    if (prc != PCC_OK) return prc;
 
     DeviceGuard guard(hip_device);
     if (!guard.ok) { (void)hipGetLastError(); return PCC_E_HIP; }
     pcc_ctx* ctx = new (std::nothrow) pcc_ctx();
     if (!ctx) return PCC_E_INTERNAL;
     ctx->device = hip_device;
+    ctx->net = net;
     ctx->dist = dist;
     hipDeviceProp_t prop;
     bool ok = hipGetDeviceProperties(&prop, hip_device) == hipSuccess;
     if (ok) ctx->num_cus = prop.multiProcessorCount;
-    ok = ok && hipMalloc((void**)&ctx->d_model, kModelBytes) == hipSuccess;
+    ok = ok && hipMalloc((void**)&ctx->d_model, image.size()) == hipSuccess;
     ok = ok && hipMalloc((void**)&ctx->d_status, kStWords * sizeof(int) + sizeof(uint64_t)) == hipSuccess;
     ok = ok && hipHostMalloc((void**)&ctx->h_status, kStWords * sizeof(int) + sizeof(uint64_t), hipHostMallocDefault) == hipSuccess;
-    ok = ok && hipMemcpy(ctx->d_model, image.data(), kModelBytes, hipMemcpyHostToDevice) == hipSuccess;
-    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void*>(&encode_kernel<1, 512>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, kModelBytes) == hipSuccess;
-    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void*>(&encode_kernel<2, 512>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, kModelBytes) == hipSuccess;
-    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void*>(&encode_kernel<1, 1024>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, kModelBytes) == hipSuccess;
+    ok = ok && hipMemcpy(ctx->d_model, image.data(), image.size(), hipMemcpyHostToDevice) == hipSuccess;
+    ok = ok && (net == kNetPaper ? set_kernel_attributes<NetPaper>() : set_kernel_attributes<NetWorkload>());
     if (const char* e = getenv("PCC_ENCODE_VARIANT")) {
         const int v = atoi(e);
         if (v >= 0 && v < 3) ctx->encode_variant = v;
     }
-    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_kernel<1>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, kDecLdsBytes) == hipSuccess;
-    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_kernel<2>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, kDecLdsBytes) == hipSuccess;
     if (!ok) { (void)hipGetLastError(); pcc_destroy(ctx); return PCC_E_HIP; }
     ctx->d_total = reinterpret_cast<uint64_t*>(ctx->d_status + kStWords);
     *out = ctx;
@@ -1115,29 +1278,16 @@ void pcc_destroy(pcc_ctx* ctx) {
     delete ctx;
 }
 
-static int launch_encode(pcc_ctx* ctx, const uint8_t* d_img, int n, int H, int W, uint32_t* sf, float* params,
-                         float* bits, hipStream_t st) {
-    const uint32_t P = (uint32_t)((uint64_t)n * H * W);
-    const EncodeVariant ev = kEncodeVariants[ctx->encode_variant];
-    const uint32_t per_block = 16u * ev.tiles * (ev.threads / 64);
-    uint32_t blocks = (P + per_block - 1) / per_block;
-    const uint32_t cus = ctx->num_cus > 0 ? (uint32_t)ctx->num_cus : 256u;
-    if (blocks > cus) blocks = cus;   // persistent: one workgroup per CU, looping over pixel groups
-    switch (ctx->encode_variant) {
-        case 0:
-            hipLaunchKernelGGL((encode_kernel<1, 512>), dim3(blocks), dim3(512), kModelBytes, st, ctx->d_model, d_img,
-                               H, W, P, sf, params, bits, ctx->d_status);
-            break;
-        case 1:
-            hipLaunchKernelGGL((encode_kernel<2, 512>), dim3(blocks), dim3(512), kModelBytes, st, ctx->d_model, d_img,
-                               H, W, P, sf, params, bits, ctx->d_status);
-            break;
-        default:
-            hipLaunchKernelGGL((encode_kernel<1, 1024>), dim3(blocks), dim3(1024), kModelBytes, st, ctx->d_model, d_img,
-                               H, W, P, sf, params, bits, ctx->d_status);
-            break;
-    }
-    return hipGetLastError() == hipSuccess ? PCC_OK : PCC_E_HIP;
+int pcc_model_info(const pcc_ctx* ctx, int* h_info) {
+    if (!ctx || !h_info) return PCC_E_ARG;
+    const bool paper = ctx->net == kNetPaper;
+    h_info[0] = head_outputs(ctx);
+    h_info[1] = paper ? NetPaper::K : NetWorkload::K;
+    h_info[2] = paper ? NetPaper::kNbhd : NetWorkload::kNbhd;
+    h_info[3] = paper ? NetPaper::kDelay : NetWorkload::kDelay;
+    h_info[4] = (int)ctx->dist;
+    h_info[5] = paper ? NetPaper::kLayers : NetWorkload::kLayers;
+    return PCC_OK;
 }
 
 int pcc_encode_probs(pcc_ctx* ctx, const uint8_t* d_img, int n, int H, int W, float* d_params, float* d_bits,
@@ -1145,7 +1295,7 @@ int pcc_encode_probs(pcc_ctx* ctx, const uint8_t* d_img, int n, int H, int W, fl
     if (!ctx || !d_img || !d_params || !dims_ok(n, H, W)) return PCC_E_ARG;
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return PCC_E_HIP;
-    return launch_encode(ctx, d_img, n, H, W, nullptr, d_params, d_bits, (hipStream_t)hip_stream);
+    return launch_encode_any(ctx, d_img, n, H, W, nullptr, d_params, d_bits, (hipStream_t)hip_stream);
 }
 
 int pcc_encode(pcc_ctx* ctx, const uint8_t* d_img, int n, int H, int W, uint8_t* d_stream, size_t cap_bytes,
@@ -1174,7 +1324,7 @@ int pcc_encode(pcc_ctx* ctx, const uint8_t* d_img, int n, int H, int W, uint8_t*
     if (hipMemsetAsync(ctx->d_status, 0, kStWords * sizeof(int) + sizeof(uint64_t), st) != hipSuccess) return PCC_E_HIP;
     prof_reset(ctx);
     prof_begin(ctx, PCC_T_ENCODE_PIXELS, st);
-    rc = launch_encode(ctx, d_img, n, H, W, d_sf, nullptr, nullptr, st);
+    rc = launch_encode_any(ctx, d_img, n, H, W, d_sf, nullptr, nullptr, st);
     if (rc != PCC_OK) return rc;
     prof_end(ctx, PCC_T_ENCODE_PIXELS, st);
     prof_begin(ctx, PCC_T_ENCODE_RANS, st);
@@ -1182,7 +1332,8 @@ int pcc_encode(pcc_ctx* ctx, const uint8_t* d_img, int n, int H, int W, uint8_t*
                        d_slabs, d_rw);
     prof_end(ctx, PCC_T_ENCODE_RANS, st);
     prof_begin(ctx, PCC_T_ENCODE_SCAN, st);
-    hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), 0, st, d_rw, rows, n, H, W, ctx->dist, d_stream, ctx->d_total);
+    const uint32_t tag = ctx->net == kNetPaper ? model_tag<NetPaper>() : model_tag<NetWorkload>();
+    hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), 0, st, d_rw, rows, n, H, W, tag, ctx->dist, d_stream, ctx->d_total);
     prof_end(ctx, PCC_T_ENCODE_SCAN, st);
     prof_begin(ctx, PCC_T_ENCODE_COMPACT, st);
     hipLaunchKernelGGL(compact_kernel, dim3(rows), dim3(64), 0, st, d_slabs, d_rw, W, rows, d_stream,
@@ -1222,14 +1373,10 @@ int pcc_decode(pcc_ctx* ctx, const uint8_t* d_stream, size_t nbytes, int n, int 
     const uint32_t spin_limit = 1u << 22;
     prof_reset(ctx);
     prof_begin(ctx, PCC_T_DECODE, st);
-    const uint32_t grid = (uint32_t)(n * nbands);
-    const uint32_t cus = ctx->num_cus > 0 ? (uint32_t)ctx->num_cus : 256u;
-    if (grid <= cus)
-        hipLaunchKernelGGL(decode_kernel<1>, dim3(grid), dim3(kDecThreads), kDecLdsBytes, st, ctx->d_model, d_stream,
-                           (uint64_t)nbytes, n, H, W, nbands, ctx->dist, d_img_out, d_mail, ctx->d_status, spin_limit);
+    if (ctx->net == kNetPaper)
+        launch_decode<NetPaper>(ctx, d_stream, nbytes, n, H, W, nbands, d_img_out, d_mail, spin_limit, st);
     else
-        hipLaunchKernelGGL(decode_kernel<2>, dim3(grid), dim3(kDecThreads), kDecLdsBytes, st, ctx->d_model, d_stream,
-                           (uint64_t)nbytes, n, H, W, nbands, ctx->dist, d_img_out, d_mail, ctx->d_status, spin_limit);
+        launch_decode<NetWorkload>(ctx, d_stream, nbytes, n, H, W, nbands, d_img_out, d_mail, spin_limit, st);
     prof_end(ctx, PCC_T_DECODE, st);
     if (hipGetLastError() != hipSuccess) return PCC_E_HIP;
     if (hipMemcpyAsync(ctx->h_status, ctx->d_status, kStWords * sizeof(int), hipMemcpyDeviceToHost, st) != hipSuccess)
@@ -1245,8 +1392,13 @@ int pcc_cdf_tables(pcc_ctx* ctx, const float* d_params, const uint8_t* d_rg, siz
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return PCC_E_HIP;
     const size_t threads = count * 3;
-    hipLaunchKernelGGL(cdf_tables_kernel, dim3((uint32_t)((threads + 255) / 256)), dim3(256), (kLutEntries + 1) * 8,
-                       (hipStream_t)hip_stream, ctx->d_model, d_params, d_rg, count, d_cq);
+    const dim3 grid((uint32_t)((threads + 255) / 256));
+    if (ctx->net == kNetPaper)
+        hipLaunchKernelGGL(cdf_tables_kernel<NetPaper>, grid, dim3(256), (kLutEntries + 1) * 8, (hipStream_t)hip_stream,
+                           ctx->d_model, d_params, d_rg, count, d_cq);
+    else
+        hipLaunchKernelGGL(cdf_tables_kernel<NetWorkload>, grid, dim3(256), (kLutEntries + 1) * 8, (hipStream_t)hip_stream,
+                           ctx->d_model, d_params, d_rg, count, d_cq);
     return hipGetLastError() == hipSuccess ? PCC_OK : PCC_E_HIP;
 }
 
@@ -1268,13 +1420,6 @@ int pcc_last_timings(pcc_ctx* ctx, float* h_ms) {
     for (int i = 0; i < PCC_N_TIMINGS; ++i) h_ms[i] = ctx->last_ms[i];
     return PCC_OK;
 }
-
-#ifdef PCC_PHASE_TIMING
-int pcc_debug_phase_cycles(unsigned long long* h_out16) {
-    return hipMemcpyFromSymbol(h_out16, HIP_SYMBOL(pcc::g_phase_cycles), 16 * sizeof(unsigned long long)) == hipSuccess
-               ? PCC_OK : PCC_E_HIP;
-}
-#endif
 
 int pcc_copy_intervals(pcc_ctx* ctx, uint32_t* d_out, size_t count, void* hip_stream) {
     if (!ctx || !d_out) return PCC_E_ARG;

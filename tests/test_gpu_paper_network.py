@@ -1,0 +1,222 @@
+"""The paper's own network shape on the HIP path against the CPU oracle (Sec. III-B, hyper-parameters of Sec. IV-E):
+12-pixel neighbourhood, 36 -> 128 x 4 -> 36, LeakyReLU, K = 3, wavefront delay 3.  Needs an MI355X."""
+import struct
+
+import numpy as np
+import pytest
+
+from oracle import pcc_oracle as po
+from paper_2212_01185_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+PARAM_ATOL = 2e-3         # raw head outputs against the exact fp64 network
+PARAM_ATOL_SPLIT = 2e-4   # against the oracle rounding activations to hi + lo bf16 the same way
+BITS_RTOL = 1e-3          # bits/pixel within 0.1 %
+CQ_ATOL = 2               # integer CDF counts
+TAG = 3 | (12 << 8) | (3 << 16) | (16 << 24)
+
+
+def _log(msg):
+    print(msg, flush=True)
+
+
+@pytest.fixture(scope="module")
+def codec_paper(paper_blob):
+    from paper_2212_01185_amd import binding
+    if not torch.cuda.is_available():
+        pytest.fail("no GPU visible")
+    c = binding.Codec(paper_blob, 0)
+    yield c
+    c.close()
+
+
+@pytest.fixture(scope="module")
+def codec_paper_sharp(paper_sharp_blob):
+    from paper_2212_01185_amd import binding
+    c = binding.Codec(paper_sharp_blob, 0)
+    yield c
+    c.close()
+
+
+def _dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def _roundtrip(codec, imgs):
+    n, h, w, _ = imgs.shape
+    stream = codec.pcc_encode(_dev(imgs))
+    out = codec.pcc_decode(stream, n, h, w)
+    torch.cuda.synchronize()
+    return stream, out.cpu().numpy()
+
+
+def test_model_info(codec_paper):
+    assert codec_paper.pcc_model_info() == (36, 3, 12, 3, 0, 5)
+
+
+def test_params_and_bits_match_oracle(codec_paper, orc_paper):
+    imgs = synth.make_batch(0)
+    _log("paper net: encode_probs 64x64")
+    params, bits = codec_paper.pcc_encode_probs(_dev(imgs))
+    torch.cuda.synchronize()
+    assert tuple(params.shape) == (1, 64, 64, 36)
+    params = params.cpu().numpy().astype(np.float64)[0]
+    exact = orc_paper.params_rows(imgs[0], range(64), po.MODE_EXACT)
+    err_exact = np.abs(params - exact).max()
+    _log("max |params - oracle(exact)| = %.3g (mean %.3g)" % (err_exact, np.abs(params - exact).mean()))
+    assert err_exact <= PARAM_ATOL
+    want = orc_paper.params_rows(imgs[0], range(64), po.MODE_SPLIT)
+    err = np.abs(params - want).max()
+    _log("max |params - oracle(split activations)| = %.3g" % err)
+    assert err <= PARAM_ATOL_SPLIT
+    bits = bits.cpu().numpy().astype(np.float64)
+    _, wbits = orc_paper.encode(imgs, po.MODE_EXACT)
+    _log("bits/pixel gpu %.5f oracle %.5f" % (bits.mean(), wbits.mean()))
+    assert abs(bits.sum() / wbits.sum() - 1) <= BITS_RTOL
+    assert np.abs(bits - wbits).mean() < 0.01
+
+
+def test_cdf_tables_against_oracle(codec_paper, orc_paper):
+    rng = np.random.default_rng(31)
+    heads = [rng.normal(0, s, 36) for s in (0.1, 0.5, 1.0, 3.0) for _ in range(40)]
+    for mu in (0.0, 0.5, 100.2 / 256, 100.5 / 256, 255 / 256, -3.0, 4.0):
+        for ls in (-20.0, -8.0, -4.0, 0.0, 4.0, 20.0):
+            o = np.zeros(36)
+            o[3:6] = o[12:15] = o[21:24] = mu
+            o[6:9] = o[15:18] = o[24:27] = ls
+            heads.append(o)
+    heads = np.asarray(heads, dtype=np.float32)
+    rg = rng.integers(0, 256, (len(heads), 2), dtype=np.uint8)
+    cq = codec_paper.pcc_cdf_tables(_dev(heads), _dev(rg))
+    torch.cuda.synchronize()
+    cq = cq.cpu().numpy().astype(np.int64)
+    assert (cq[:, :, 0] == 0).all() and (cq[:, :, 256] == 65536).all()
+    assert (np.diff(cq, axis=2) >= 1).all()
+    worst = 0
+    for i, o in enumerate(heads.astype(np.float64)):
+        for ch in range(3):
+            want = orc_paper.cdf_table(o, ch, int(rg[i, 0]), int(rg[i, 1])).astype(np.int64)
+            worst = max(worst, int(np.abs(cq[i, ch] - want).max()))
+    _log("paper net: max |Cq_gpu - Cq_oracle| = %d counts" % worst)
+    assert worst <= CQ_ATOL
+
+
+def _expected_stream(imgs_shape, intervals):
+    """The container assembled from oracle-coded rows of the given (start, freq) pairs."""
+    n, h, w, _ = imgs_shape
+    sf = intervals.reshape(n * h, 3 * w).astype(np.uint32)
+    payloads = [po.rans_encode(row & 0xFFFF, (row >> 16) + 1) for row in sf]
+    offs = np.concatenate([[0], np.cumsum([len(p) for p in payloads])]).astype("<u8")
+    head = struct.pack("<8I", 0x31434350, 1, n, h, w, TAG, 0, 0)
+    return head + offs.tobytes() + b"".join(payloads)
+
+
+@pytest.mark.parametrize("shape", [(1, 64, 64), (2, 17, 33)])
+def test_coder_and_container_bit_exact(codec_paper, codec_paper_sharp, shape):
+    n, h, w = shape
+    rng = np.random.default_rng(32)
+    imgs = rng.integers(0, 256, (n, h, w, 3), dtype=np.uint8)
+    for c in (codec_paper, codec_paper_sharp):
+        stream = c.pcc_encode(_dev(imgs))
+        iv = c.pcc_copy_intervals(n, h, w)
+        torch.cuda.synchronize()
+        iv = iv.cpu().numpy().view(np.uint32)
+        freq = (iv >> 16) + 1
+        assert freq.min() >= 1 and ((iv & 0xFFFF) + freq).max() <= 65536
+        assert stream.cpu().numpy().tobytes() == _expected_stream(imgs.shape, iv)
+
+
+def test_container_structure(codec_paper):
+    """Header words (with this network's tag), offset table and total size of a stream."""
+    rng = np.random.default_rng(33)
+    imgs = rng.integers(0, 256, (1, 9, 21, 3), dtype=np.uint8)
+    stream = codec_paper.pcc_encode(_dev(imgs))
+    raw = stream.cpu().numpy().tobytes()
+    hdr = struct.unpack("<8I", raw[:32])
+    assert hdr[:7] == (0x31434350, 1, 1, 9, 21, TAG, 0)
+    offs = np.frombuffer(raw[32:32 + 8 * 10], dtype="<u8")
+    assert offs[0] == 0 and (np.diff(offs.astype(np.int64)) >= 8).all()
+    assert 32 + 80 + int(offs[-1]) == len(raw)
+
+
+def _edge_images():
+    rng = np.random.default_rng(34)
+    yield "1x1", rng.integers(0, 256, (1, 1, 1, 3), dtype=np.uint8)
+    yield "1x9", rng.integers(0, 256, (1, 1, 9, 3), dtype=np.uint8)
+    yield "9x1", rng.integers(0, 256, (1, 9, 1, 3), dtype=np.uint8)
+    yield "2x2", rng.integers(0, 256, (1, 2, 2, 3), dtype=np.uint8)
+    yield "3x3", rng.integers(0, 256, (1, 3, 3, 3), dtype=np.uint8)
+    yield "3x5x2", rng.integers(0, 256, (2, 3, 5, 3), dtype=np.uint8)
+    yield "16x16", rng.integers(0, 256, (1, 16, 16, 3), dtype=np.uint8)
+    yield "17x33x3", rng.integers(0, 256, (3, 17, 33, 3), dtype=np.uint8)     # ragged band, ragged tile
+    yield "40x7", rng.integers(0, 256, (1, 40, 7, 3), dtype=np.uint8)         # taller than wide
+    yield "33x2", rng.integers(0, 256, (1, 33, 2, 3), dtype=np.uint8)         # narrower than the neighbourhood
+    yield "zeros", np.zeros((1, 33, 20, 3), dtype=np.uint8)
+    yield "ones", np.full((1, 33, 20, 3), 255, dtype=np.uint8)
+    yield "blobs", synth.make_image(3, synth.ImageSpec(100, 50, 5, 3.0, 12.0))[None]
+
+
+def test_roundtrip_edge_shapes(codec_paper, codec_paper_sharp):
+    for name, imgs in _edge_images():
+        for which, c in (("default", codec_paper), ("sharp", codec_paper_sharp)):
+            _log("paper net roundtrip %s %s" % (name, which))
+            _, out = _roundtrip(c, imgs)
+            np.testing.assert_array_equal(out, imgs, err_msg="%s %s" % (name, which))
+
+
+def test_borders_match_oracle(codec_paper, orc_paper):
+    """Head outputs at the image borders of a ragged shape (zero padding on all sides of the window)."""
+    rng = np.random.default_rng(35)
+    img = rng.integers(0, 256, (19, 37, 3), dtype=np.uint8)
+    params, _ = codec_paper.pcc_encode_probs(_dev(img[None]))
+    torch.cuda.synchronize()
+    got = params.cpu().numpy().astype(np.float64)[0]
+    want = orc_paper.params_rows(img, range(19), po.MODE_EXACT)
+    err = np.abs(got - want)
+    _log("19x37 random image: max err %.3g, at borders %.3g" % (err.max(), max(err[:2].max(), err[:, :2].max(), err[:, -3:].max())))
+    assert err.max() <= PARAM_ATOL
+
+
+def test_512x512_as_in_the_papers_timing_table(codec_paper, orc_paper):
+    """The image size of the paper's run-time table: round trip, sampled head outputs, stream length."""
+    from paper_2212_01185_amd import binding
+    img = synth.make_image(7, synth.ImageSpec(512, 512, 24, 8.0, 64.0))[None]
+    params, bits = codec_paper.pcc_encode_probs(_dev(img))
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(36)
+    pts = [(0, 0), (511, 511), (0, 511), (511, 0), (1, 1), (2, 509)]
+    pts += [(int(rng.integers(512)), int(rng.integers(512))) for _ in range(150)]
+    idx = torch.tensor(pts, device="cuda")
+    got = params[0, idx[:, 0], idx[:, 1]].cpu().numpy().astype(np.float64)
+    want = np.stack([orc_paper.params_at(img[0], r, c, po.MODE_EXACT) for r, c in pts])
+    err = np.abs(got - want).max()
+    _log("512x512 sampled params: max err %.3g" % err)
+    assert err <= PARAM_ATOL
+    _log("512x512 round trip")
+    stream, out = _roundtrip(codec_paper, img)
+    assert np.array_equal(out, img)
+    ideal = float(bits.double().sum().item())
+    over = 8 * stream.numel() - ideal
+    _log("stream %d bytes (%.3f bpsp), overhead over ideal %.0f bits" % (stream.numel(), 8 * stream.numel() / (3 * 512 * 512), over))
+    assert 0 <= over - 8 * (32 + 8 * 513) <= 512 * 96 + 64
+    assert binding.pcc_wavefront_steps(512, 512, codec_paper.delay) == po.wavefront_steps(512, 512, 3)
+
+
+def test_streams_of_the_other_network_are_refused(codec_paper, blob):
+    from paper_2212_01185_amd import binding
+    other = binding.Codec(blob, 0)
+    try:
+        imgs = synth.make_batch(0)
+        s_other = other.pcc_encode(_dev(imgs))
+        with pytest.raises(binding.PccError) as e:
+            codec_paper.pcc_decode(s_other, 1, 64, 64)
+        assert e.value.code == binding.PCC_E_STREAM
+        s_paper = codec_paper.pcc_encode(_dev(imgs))
+        with pytest.raises(binding.PccError) as e:
+            other.pcc_decode(s_paper, 1, 64, 64)
+        assert e.value.code == binding.PCC_E_STREAM
+    finally:
+        other.close()

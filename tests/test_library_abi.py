@@ -27,17 +27,24 @@ def test_library_exports_every_declared_symbol():
 def test_host_only_entry_points():
     assert binding.pcc_strerror(0) == "ok"
     assert "stream" in binding.pcc_strerror(binding.PCC_E_STREAM)
-    assert binding.pcc_wavefront_steps(512, 768) == 1790
+    assert binding.pcc_wavefront_steps(512, 768) == 1790          # delay 2 by default
+    # Eq. (6) with the paper's neighbourhood (h = 2, so each row trails by 3): D + (D - 1)(h + 1)
+    assert binding.pcc_wavefront_steps(512, 512, 3) == 512 + 511 * 3
+    assert binding.pcc_wavefront_steps(1, 9, 3) == 9 and binding.pcc_wavefront_steps(0, 9, 3) == 0
     # header + offsets + per row (state + at most 2 bytes per symbol + slack)
     b = binding.pcc_stream_bound(1, 64, 64)
     assert 32 + 8 * 65 + 64 * (8 + 6 * 64) <= b <= 32 + 8 * 65 + 64 * (6 * 64 + 24)
     assert binding.pcc_stream_bound(0, 1, 1) == 0
 
 
-def test_create_rejects_bad_blobs_before_touching_the_gpu(blob):
+def test_create_rejects_bad_blobs_before_touching_the_gpu(blob, paper_blob):
     lib = binding.load()
     h = ctypes.c_void_p()
-    for bad in (blob[:-4], b"\0" * len(blob), blob[:64]):
+    import struct
+    words = list(struct.unpack("<16I", paper_blob[:64]))
+    relu_paper = struct.pack("<16I", *(words[:14] + [0] + words[15:])) + paper_blob[64:]   # paper shape but ReLU
+    k5_paper = struct.pack("<16I", *(words[:11] + [5] + words[12:])) + paper_blob[64:]     # paper shape but K = 5
+    for bad in (blob[:-4], b"\0" * len(blob), blob[:64], paper_blob[:-4], relu_paper, k5_paper):
         buf = ctypes.create_string_buffer(bad, len(bad))
         assert lib.pcc_create(ctypes.byref(h), buf, len(bad), 0) == binding.PCC_E_BLOB
     # a weight that is not a bf16 value
