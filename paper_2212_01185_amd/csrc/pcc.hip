@@ -467,19 +467,36 @@ __device__ __forceinline__ uint32_t row_allmin(uint32_t v) {
 // when a 16-word block is used up is not needed for another 16 words.
 struct RowReader {
     uint64_t x;
-    const uint32_t* words;  // payload after the 8-byte state
-    uint32_t nwords, pos;   // pos: words consumed so far
-    uint32_t cur, nxt;      // words[(pos & ~15) + j], words[(pos & ~15) + 16 + j]
+    const uint32_t* payload;  // the row's payload: 8-byte state, then the words
+    uint32_t last;            // index of the payload's last 32-bit word (>= 1: the state is two words)
+    uint32_t nwords, pos;     // words after the state; words consumed so far
+    uint32_t cur, nxt;        // words[(pos & ~15) + j], words[(pos & ~15) + 16 + j]
     bool bad;
 };
 
+// Word i of the row (i counted after the state).  Indices past the end read the
+// payload's last word instead: such a value is only ever consumed by a damaged
+// stream, which the position check in reader_advance reports.  The load carries
+// no condition, so its result can stay in flight until it is needed, and it is
+// in bounds for every i as long as payload[0 .. last] is readable.
+__device__ __forceinline__ uint32_t reader_word(const RowReader& rd, uint32_t i) {
+    return rd.payload[min(i + 2u, rd.last)];
+}
+
+// A reader over no words at all (rows outside the image, rows whose offsets are
+// damaged): `safe` is any readable pair of words; every renormalisation then counts as an over-read.
+__device__ __forceinline__ void reader_init_empty(RowReader& rd, const uint32_t* safe, bool bad) {
+    rd.x = kRansL; rd.payload = safe; rd.last = 1; rd.nwords = 0; rd.pos = 0; rd.cur = 0; rd.nxt = 0; rd.bad = bad;
+}
+
 __device__ __forceinline__ void reader_init(RowReader& rd, const uint32_t* payload, uint32_t nwords_total, int j) {
     rd.x = (uint64_t)payload[0] | ((uint64_t)payload[1] << 32);
-    rd.words = payload + 2;
+    rd.payload = payload;
+    rd.last = nwords_total - 1;
     rd.nwords = nwords_total - 2;
     rd.pos = 0;
-    rd.cur = (uint32_t)j < rd.nwords ? rd.words[j] : 0u;
-    rd.nxt = (uint32_t)j + 16u < rd.nwords ? rd.words[j + 16] : 0u;
+    rd.cur = reader_word(rd, (uint32_t)j);
+    rd.nxt = reader_word(rd, (uint32_t)j + 16u);
     rd.bad = false;
     if (rd.x < kRansL || (rd.x >> 63)) { rd.bad = true; rd.x = kRansL; }
 }
@@ -495,8 +512,10 @@ __device__ __forceinline__ void reader_advance(RowReader& rd, uint32_t slot, uin
         rd.pos += 1;
         if ((rd.pos & 15u) == 0u) {
             rd.cur = rd.nxt;
-            const uint32_t idx = rd.pos + 16u + (uint32_t)j;
-            rd.nxt = idx < rd.nwords ? rd.words[idx] : 0u;
+            // scheduling only: the copy is made before the load is issued, so that the load can
+            // write rd.nxt in place and stay in flight (no wait) until the next block change
+            asm volatile("" : "+v"(rd.cur));
+            rd.nxt = reader_word(rd, rd.pos + 16u + (uint32_t)j);
         }
     }
 }
@@ -716,7 +735,7 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
     const int qrow = r0 + q;
     const bool qrow_ok = qrow < H;
     RowReader rd;
-    rd.x = kRansL; rd.words = nullptr; rd.nwords = 0; rd.pos = 0; rd.cur = 0; rd.nxt = 0; rd.bad = false;
+    reader_init_empty(rd, reinterpret_cast<const uint32_t*>(stream), false);   // the stream header is always readable
     if (qrow_ok) {
         const uint64_t* offs = reinterpret_cast<const uint64_t*>(stream + kStreamHeader);
         const uint64_t rowg = (uint64_t)im * H + qrow;
