@@ -17,7 +17,8 @@
  *   - discretised Gaussian mixture pmf: Eq. (1);
  *   - R -> G -> B factorisation with mean-only coupling: Eq. (2), (3), (4);
  *   - encoder sees the whole image, decoder is sequential: Sec. III-C, first
- *     paragraph; the wavefront order and its pass count: Sec. III-C, Eq. (6).
+ *     paragraph; the wavefront order and its pass count: Sec. III-C, Eq. (6);
+ *     the diagonal order, its pass count and its copied neighbours: Sec. III-C, Eq. (7).
  * What the paper leaves open and this file fixes (each stated at its place):
  *   input scaling x/256, open tails, softmax / exp(clamp) parameterisation,
  *   per-component coupling coefficients, 16-bit integer CDF rule, the rANS
@@ -115,8 +116,11 @@ int orc_model_create(const void *blob, size_t nbytes, orc_model **out) {
     uint32_t act = rd32(p + 56), dist = rd32(p + 60);
     m->dist = (int)dist;
     m->act = (int)act;
-    /* the wavefront delay per row is the neighbourhood's right reach + 1: Eq. (6) with h = reach */
-    if (m->K < 1 || m->K > ORC_MAX_K || !((m->nbhd == 10 && m->delay == 2) || (m->nbhd == 12 && m->delay == 3)) ||
+    /* the wavefront delay per row is the neighbourhood's right reach + 1: Eq. (6) with h = reach;
+     * delay 1 with the 12-pixel neighbourhood is the diagonal variant (Eq. (7)), whose three
+     * not yet decoded neighbours are replaced by a copy (see orc_tap_source) */
+    if (m->K < 1 || m->K > ORC_MAX_K ||
+        !((m->nbhd == 10 && m->delay == 2) || (m->nbhd == 12 && (m->delay == 3 || m->delay == 1))) ||
         act > 1 || dist > 1 ||
         m->dims[0] != 3 * m->nbhd || m->dims[m->n_layers] != 12 * m->K) { free(m); return ORC_E_BLOB; }
     size_t need = 64;
@@ -137,15 +141,32 @@ int orc_model_create(const void *blob, size_t nbytes, orc_model **out) {
 
 /* ------------------------------------------------------------------ network */
 
+/* Position the network input for neighbour j of pixel (r, c) is read from.
+ * Wavefront models: the neighbour itself.  Diagonal model (Sec. III-C, text
+ * after Eq. (7)): a pass decodes all pixels of one anti-diagonal r + c = t, so
+ * the three neighbours on or beyond the pixel's own anti-diagonal -- (r-2,c+2),
+ * (r-1,c+1), (r-1,c+2) -- are not yet decoded and carry a copy of an available
+ * pixel instead.  Which pixel the paper copies is shown only in a figure that
+ * is lost; this build takes (r-1, c), the nearest decoded pixel to all three.
+ * The copy is made on the zero-padded patch: it applies wherever the three
+ * positions fall, and copies zero when (r-1, c) itself is outside the image. */
+void orc_tap_source(const orc_model *m, int r, int c, int j, int *rr, int *cc) {
+    const int (*nb)[2] = m->nbhd == 10 ? NBHD10 : NBHD12;
+    int dr = nb[j][0], dc = nb[j][1];
+    if (m->delay == 1 && dr + dc >= 0) { dr = -1; dc = 0; }
+    *rr = r + dr;
+    *cc = c + dc;
+}
+
 /* C_ij as the network input vector (Sec. III-A; Sec. III-C, second paragraph):
- * u[3*j + ch] = img[r+dr_j][c+dc_j][ch] / 256, and 0 where the neighbour lies
- * outside the image (the zero padding of the first convolution).  The scaling
- * by 1/256 is this build's choice; the paper does not state one. */
+ * u[3*j + ch] = img[source of neighbour j][ch] / 256, and 0 where that position
+ * lies outside the image (the zero padding of the first convolution).  The
+ * scaling by 1/256 is this build's choice; the paper does not state one. */
 void orc_gather(const orc_model *m, const uint8_t *img, int H, int W, int r, int c, double *u) {
     (void)H;
-    const int (*nb)[2] = m->nbhd == 10 ? NBHD10 : NBHD12;
     for (int j = 0; j < m->nbhd; ++j) {
-        int rr = r + nb[j][0], cc = c + nb[j][1];
+        int rr, cc;
+        orc_tap_source(m, r, c, j, &rr, &cc);
         for (int ch = 0; ch < 3; ++ch) {
             double v = 0.0;
             if (rr >= 0 && cc >= 0 && cc < W) v = img[((size_t)rr * W + cc) * 3 + ch] / 256.0;
@@ -425,16 +446,20 @@ int orc_encode(const orc_model *m, const uint8_t *img, int n, int H, int W, int 
     return rc;
 }
 
-/* Wavefront pass count for an H x W image when each row trails the one above
- * by `delay` columns: Eq. (6) generalised to W != H, T = W + (H-1)*delay
- * (the paper's D + (D-1)(h+1) has delay = h+1 and W = H = D). */
+/* Pass count for an H x W image when each row trails the one above by `delay`
+ * columns: Eq. (6) generalised to W != H, T = W + (H-1)*delay (the paper's
+ * D + (D-1)(h+1) has delay = h+1 and W = H = D); delay = 1 is the diagonal
+ * order, T = W + H - 1, Eq. (7)'s 2D - 1. */
 long orc_wavefront_steps(int H, int W, int delay) { return (long)W + (long)(H - 1) * delay; }
 
 /* Decoder (Sec. III-C): a pixel is decoded by evaluating the network on its
  * already decoded neighbourhood, then R, then G given R, then B given R and G.
  * order = RASTER is the fully sequential decoder (one pass per pixel);
  * order = WAVEFRONT visits passes t = 0,1,..., and in pass t every row r whose
- * column c = t - delay*r lies in the image.  Both must give the same image. */
+ * column c = t - delay*r lies in the image (delay = 1: the anti-diagonal
+ * r + c = t).  A pass is parallel: the networks of all its pixels are
+ * evaluated on the image as it stood before the pass, and only then are its
+ * pixels decoded.  Both orders must give the same image. */
 int orc_decode(const orc_model *m, const uint8_t *stream, size_t nbytes, int n, int H, int W,
                int mode, int order, uint8_t *img_out) {
     if (!m || !stream || !img_out || n < 1 || H < 1 || W < 1) return ORC_E_ARG;
@@ -455,8 +480,9 @@ int orc_decode(const orc_model *m, const uint8_t *stream, size_t nbytes, int n, 
     if (rd64(stream + STREAM_HEADER + 8 * rows) != nbytes - table) { free(dec); return ORC_E_STREAM; }
     memset(img_out, 0, (size_t)n * H * W * 3);
     int rc = ORC_OK;
-    double o[ORC_MAX_WIDTH];
     uint32_t cq[257];
+    double *o_pass = (double *)malloc((size_t)H * ORC_MAX_WIDTH * sizeof(double));   /* head outputs of one pass, per row */
+    if (!o_pass) { free(dec); return ORC_E_INTERNAL; }
     long T = order == ORC_ORDER_WAVEFRONT ? orc_wavefront_steps(H, W, m->delay) : (long)H * W;
     for (int i = 0; i < n && rc == ORC_OK; ++i) {
         uint8_t *im = img_out + (size_t)i * H * W * 3;
@@ -464,12 +490,19 @@ int orc_decode(const orc_model *m, const uint8_t *stream, size_t nbytes, int n, 
             int r_lo, r_hi;
             if (order == ORC_ORDER_WAVEFRONT) { r_lo = 0; r_hi = H - 1; }
             else { r_lo = r_hi = (int)(t / W); }
+            /* first every network of the pass, on the image before the pass ... */
+            for (int r = r_lo; r <= r_hi; ++r) {
+                long c = order == ORC_ORDER_WAVEFRONT ? t - (long)m->delay * r : t % W;
+                if (c < 0 || c >= W) continue;
+                orc_params_at(m, im, H, W, r, (int)c, mode, o_pass + (size_t)r * ORC_MAX_WIDTH);
+            }
+            /* ... then its symbols */
             for (int r = r_lo; r <= r_hi && rc == ORC_OK; ++r) {
                 long c = order == ORC_ORDER_WAVEFRONT ? t - (long)m->delay * r : t % W;
                 if (c < 0 || c >= W) continue;
                 rans_dec *d = &dec[(size_t)i * H + r];
                 uint8_t *px = im + ((size_t)r * W + c) * 3;
-                orc_params_at(m, im, H, W, r, (int)c, mode, o);
+                const double *o = o_pass + (size_t)r * ORC_MAX_WIDTH;
                 for (int ch = 0; ch < 3; ++ch) {
                     if (orc_cdf_table(m, o, ch, px[0], px[1], cq) != ORC_OK) { rc = ORC_E_INTERNAL; break; }
                     uint32_t slot = rans_dec_peek(d);
@@ -482,6 +515,7 @@ int orc_decode(const orc_model *m, const uint8_t *stream, size_t nbytes, int n, 
             }
         }
     }
+    free(o_pass);
     for (size_t k = 0; k < rows && rc == ORC_OK; ++k) if (!rans_dec_finished(&dec[k])) rc = ORC_E_STREAM;
     free(dec);
     return rc;

@@ -46,6 +46,8 @@ def lib():
         L.orc_model_destroy.restype = None
         L.orc_gather.argtypes = [vp, vp, i32, i32, i32, i32, vp]
         L.orc_gather.restype = None
+        L.orc_tap_source.argtypes = [vp, i32, i32, i32, vp, vp]
+        L.orc_tap_source.restype = None
         L.orc_mlp.argtypes = [vp, vp, i32, vp]
         L.orc_mlp.restype = None
         L.orc_params_at.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp]
@@ -110,6 +112,12 @@ class Oracle:
         u = np.zeros(self.dims[0], dtype=np.float64)
         lib().orc_gather(self._h, _ptr(img), h, w, r, c, _ptr(u))
         return u
+
+    def tap_source(self, r: int, c: int, j: int):
+        """(row, column) the network input for neighbour j of pixel (r, c) is read from (may lie outside the image)."""
+        rr, cc = C.c_int(0), C.c_int(0)
+        lib().orc_tap_source(self._h, r, c, j, C.byref(rr), C.byref(cc))
+        return rr.value, cc.value
 
     def mlp(self, u: np.ndarray, mode: int = MODE_EXACT) -> np.ndarray:
         u = np.ascontiguousarray(u, dtype=np.float64)

@@ -199,6 +199,13 @@ def make_paper_blob(seed: int = 0, sharp: bool = False, dist: int = DIST_GAUSSIA
                      act=ACT_LEAKY, dist=dist)
 
 
+def make_diagonal_blob(seed: int = 0, sharp: bool = False, dist: int = DIST_GAUSSIAN) -> bytes:
+    """The paper's network shape for the diagonal decoding order (Sec. III-C, Eq. (7)): same layers and
+    12-pixel input, rows trail by one column (delay 1), three inputs are copies (the coder's business)."""
+    return pack_blob(make_weights(seed, PAPER_DIMS, sharp=sharp), k=PAPER_K, nbhd=PAPER_NBHD, delay=1,
+                     act=ACT_LEAKY, dist=dist)
+
+
 def param_count(dims) -> int:
     """Weights + biases of a fully connected stack with these layer widths."""
     return sum(i * o + o for i, o in zip(dims[:-1], dims[1:]))

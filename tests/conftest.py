@@ -64,3 +64,21 @@ def paper_sharp_blob():
 def orc_paper(paper_blob):
     from oracle import pcc_oracle
     return pcc_oracle.Oracle(paper_blob)
+
+
+@pytest.fixture(scope="session")
+def diagonal_blob():
+    from paper_2212_01185_amd import synth
+    return synth.make_diagonal_blob(0)
+
+
+@pytest.fixture(scope="session")
+def diagonal_sharp_blob():
+    from paper_2212_01185_amd import synth
+    return synth.make_diagonal_blob(0, sharp=True)
+
+
+@pytest.fixture(scope="session")
+def orc_diagonal(diagonal_blob):
+    from oracle import pcc_oracle
+    return pcc_oracle.Oracle(diagonal_blob)

@@ -377,6 +377,76 @@ def test_paper_network_roundtrip(orc_paper):
             assert f.min() >= 1 and f.sum() == 65536
 
 
+# ----------------------------------------------------------------- diagonal decoding order (Sec. III-C, Eq. (7))
+
+def test_diagonal_pass_count_is_eq7():
+    for d in (1, 2, 64, 128, 256, 512):
+        assert po.wavefront_steps(d, d, 1) == 2 * d - 1          # Eq. (7): T = 2D - 1
+    assert po.wavefront_steps(512, 768, 1) == 768 + 512 - 1
+
+
+@pytest.mark.parametrize("h,w", [(1, 1), (1, 7), (7, 1), (3, 2), (5, 9), (9, 5)])
+def test_diagonal_sources_are_decoded_before_the_pass(orc_diagonal, orc_paper, h, w):
+    """Every position the diagonal model reads lies on an earlier anti-diagonal (or outside the image);
+    exactly the three neighbours the paper names are replaced, all by the pixel straight above; the
+    wavefront model of the same shape replaces none."""
+    for r in range(h):
+        for c in range(w):
+            replaced = []
+            for j, (dr, dc) in enumerate(OFFSETS12):
+                rr, cc = orc_diagonal.tap_source(r, c, j)
+                if 0 <= rr < h and 0 <= cc < w:
+                    assert rr + cc < r + c                       # decoded in an earlier pass
+                    assert rr * w + cc < r * w + c               # and earlier in raster order, too
+                if (rr, cc) != (r + dr, c + dc):
+                    replaced.append((dr, dc))
+                    assert (rr, cc) == (r - 1, c)
+                assert orc_paper.tap_source(r, c, j) == (r + dr, c + dc)
+            assert sorted(replaced) == [(-2, 2), (-1, 1), (-1, 2)]
+    # the pixels of one pass are exactly one anti-diagonal
+    steps = {r + c for r in range(h) for c in range(w)}
+    assert steps == set(range(po.wavefront_steps(h, w, 1)))
+
+
+def test_diagonal_gather_copies_on_the_padded_patch(orc_diagonal, orc_paper):
+    rng = np.random.default_rng(41)
+    img = rng.integers(1, 256, size=(6, 7, 3), dtype=np.uint8)      # no zeros: padding is recognisable
+    pad = np.zeros((6 + 2, 7 + 4, 3), dtype=np.float64)
+    pad[2:, 2:-2] = img / 256.0
+    for r in range(6):
+        for c in range(7):
+            patch = {(dr, dc): pad[r + 2 + dr, c + 2 + dc].copy() for dr, dc in OFFSETS12}
+            above = pad[r + 2 - 1, c + 2]
+            for key in ((-2, 2), (-1, 1), (-1, 2)):
+                patch[key] = above
+            want = np.concatenate([patch[o] for o in OFFSETS12])
+            np.testing.assert_array_equal(orc_diagonal.gather(img, r, c), want)
+    # a constant image: the copies equal what they replace where all three replaced positions lie in the
+    # image, and in the first row, where the pixel above is padding like they are
+    flat = np.full((5, 9, 3), 77, dtype=np.uint8)
+    for r in range(5):
+        for c in range(9):
+            same = np.array_equal(orc_diagonal.gather(flat, r, c), orc_paper.gather(flat, r, c))
+            assert same == (r == 0 or (r >= 2 and c + 2 < 9))
+
+
+def test_diagonal_roundtrip_raster_equals_diagonal_order(orc_diagonal, orc_paper):
+    rng = np.random.default_rng(42)
+    cases = [rng.integers(0, 256, (1, 1, 1, 3), dtype=np.uint8), rng.integers(0, 256, (1, 1, 9, 3), dtype=np.uint8),
+             rng.integers(0, 256, (1, 9, 1, 3), dtype=np.uint8), rng.integers(0, 256, (2, 6, 7, 3), dtype=np.uint8),
+             np.zeros((1, 5, 5, 3), dtype=np.uint8), synth.make_image(8, synth.ImageSpec(19, 11, 3, 2.0, 6.0))[None]]
+    for imgs in cases:
+        n, h, w, _ = imgs.shape
+        stream, bits = orc_diagonal.encode(imgs)
+        np.testing.assert_array_equal(orc_diagonal.decode(stream, n, h, w, order=po.ORDER_RASTER), imgs)
+        np.testing.assert_array_equal(orc_diagonal.decode(stream, n, h, w, order=po.ORDER_WAVEFRONT), imgs)
+    # the stream says which order it was made for: the wavefront model of the same shape refuses it
+    imgs = cases[3]
+    stream, _ = orc_diagonal.encode(imgs)
+    with pytest.raises(Exception):
+        orc_paper.decode(stream, 2, 6, 7)
+
+
 # ----------------------------------------------------------------- rANS
 
 def _random_tables(rng, nsym):
