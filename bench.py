@@ -6,10 +6,11 @@ pixels through gather, network, mixture CDF, row-rANS, stream assembly, then the
 wavefront decoder), inputs and outputs resident in HBM.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1] [--no-cpu-baseline]
-                  [--network workload|paper] [--image WxH]
+                  [--network workload|paper|diagonal] [--image WxH]
 
 --network paper runs the paper's own network shape (12-pixel neighbourhood, 36-128x4-36, LeakyReLU, K=3,
-delay 3) instead of the measured workloads' one; --image 512x512 gives the image size of the paper's run-time
+delay 3) instead of the measured workloads' one, --network diagonal the same shape in the diagonal decoding
+order (passes r + c, three inputs copied); --image 512x512 gives the image size of the paper's run-time
 table.  Neither is the headline: the driver's default run is config 1 with the workload network.
 """
 from __future__ import annotations
@@ -25,9 +26,13 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 # 2 * multiply-accumulates per pixel: 30-160-160-128-60 (58,560) and 36-128-128-128-128-36 (58,368)
-FLOP_PER_PIXEL_BY_NET = {"workload": 117120, "paper": 116736}
+FLOP_PER_PIXEL_BY_NET = {"workload": 117120, "paper": 116736, "diagonal": 116736}
 NET_NAME = {"workload": "He-init 30-160-160-128-60 network, ReLU, K=5, 10-pixel neighbourhood",
-            "paper": "He-init 36-128-128-128-128-36 network, LeakyReLU, K=3, 12-pixel neighbourhood"}
+            "paper": "He-init 36-128-128-128-128-36 network, LeakyReLU, K=3, 12-pixel neighbourhood",
+            "diagonal": "He-init 36-128-128-128-128-36 network, LeakyReLU, K=3, 12-pixel neighbourhood with the three "
+                        "undecoded inputs copied, diagonal order"}
+# paper, Table II: 512x512, diagonal order: encode 3.08 s, decode 27.22 s
+PAPER_512_DIAGONAL_STEP_SECONDS = 3.08 + 27.22
 # paper, Table II: 512x512, wavefront, RTX 2080 + i7-9700: encode 3.10 s, decode 26.26 s
 PAPER_512_STEP_SECONDS = 3.10 + 26.26
 PEAK_BF16_TFLOPS = 2500.0        # MI355X dense bf16 MFMA
@@ -67,7 +72,7 @@ def main():
     ap.add_argument("--config", type=int, default=1, help="workload id 0..4 (1 = 768x512, the headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=48)
-    ap.add_argument("--network", choices=("workload", "paper"), default="workload")
+    ap.add_argument("--network", choices=("workload", "paper", "diagonal"), default="workload")
     ap.add_argument("--image", default=None, help="WxH of one synthetic image instead of a numbered config")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs: three encodes + decodes and one plain "
@@ -82,7 +87,7 @@ def main():
     from paper_2212_01185_amd import binding, synth
 
     FLOP_PER_PIXEL = FLOP_PER_PIXEL_BY_NET[args.network]
-    blob = synth.make_blob(0) if args.network == "workload" else synth.make_paper_blob(0)
+    blob = {"workload": synth.make_blob, "paper": synth.make_paper_blob, "diagonal": synth.make_diagonal_blob}[args.network](0)
     if args.image:
         iw, ih = (int(v) for v in args.image.lower().split("x"))
         imgs = synth.make_image(0, synth.ImageSpec(iw, ih, 32, 8.0, 64.0))[None]
@@ -140,7 +145,8 @@ def main():
     stream_bytes = int(s.numel())
     steps_wave = binding.pcc_wavefront_steps(h, w, codec.delay)
     headline = args.network == "workload" and not args.image and args.config == 1
-    paper_case = args.network == "paper" and (n, h, w) == (1, 512, 512)
+    paper_case = args.network in ("paper", "diagonal") and (n, h, w) == (1, 512, 512)
+    paper_seconds = PAPER_512_STEP_SECONDS if args.network == "paper" else PAPER_512_DIAGONAL_STEP_SECONDS
 
     enc_tflops = FLOP_PER_PIXEL * pixels / (kern["encode_pixels"] * 1e-3) / 1e12
     result = {
@@ -150,7 +156,7 @@ def main():
         "n_gpus": 1, "steps": k, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak",
         # only the paper's own case (its network shape, its 512x512 image size; its machine was an RTX 2080)
-        "vs_baseline": (pixels / (ms_per_step * 1e-3)) / (512 * 512 / PAPER_512_STEP_SECONDS) if paper_case else None,
+        "vs_baseline": (pixels / (ms_per_step * 1e-3)) / (512 * 512 / paper_seconds) if paper_case else None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "%s RGB uint8, seeded blobs+gradient+noise, %s" % (wl_name, NET_NAME[args.network]),
                    "pixels": pixels, "wavefront_steps": steps_wave, "stream_bytes": stream_bytes,
@@ -171,7 +177,8 @@ def main():
             "achieved_TFLOP_s": FLOP_PER_PIXEL * pixels / (kern["decode"] * 1e-3) / 1e12,
             "frac_of_mfma_peak": FLOP_PER_PIXEL * pixels / (kern["decode"] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
         },
-        "paper_context": "paper, 512x512 wavefront on RTX 2080 + i7-9700: encode 3.10 s, decode 26.26 s (0.0846 / 0.00998 MPix/s)",
+        "paper_context": "paper, 512x512 on RTX 2080 + i7-9700: wavefront encode 3.10 s, decode 26.26 s (0.0846 / 0.00998 MPix/s); "
+                         "diagonal 3.08 s / 27.22 s",
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(blob, imgs, min(args.cpu_rows, h))

@@ -28,14 +28,18 @@
  * per row, activation id, distribution id}, then per layer W[out][in] and
  * b[out] as fp32.  Weights must be exactly representable in bf16 (biases are
  * fp32); components are Gaussian (distribution id 0, Eq. (1)) or logistic
- * (id 1, Eq. (8)).  This library accepts two network shapes:
+ * (id 1, Eq. (8)).  This library accepts three models:
  *   - 30 -> 160 -> 160 -> 128 -> 60, ReLU (activation id 0), K = 5, the
  *     10-pixel neighbourhood {rows r-2, r-1 at columns c-2..c+1; row r at
  *     c-2, c-1}, delay 2 (the measured workloads);
  *   - 36 -> 128 -> 128 -> 128 -> 128 -> 36, LeakyReLU with slope 0.01 (id 1),
  *     K = 3, the 12-pixel neighbourhood {rows r-2, r-1 at columns c-2..c+2;
  *     row r at c-2, c-1}, delay 3 (the network of Sec. III-B with the
- *     hyper-parameters of Sec. IV-E).
+ *     hyper-parameters of Sec. IV-E);
+ *   - the same shape with delay 1: the diagonal decoding order of Sec. III-C,
+ *     Eq. (7).  A pass decodes the anti-diagonal r + c = t; the inputs of the
+ *     three neighbours not yet decoded then, (r-2,c+2), (r-1,c+1), (r-1,c+2),
+ *     carry copies of pixel (r-1,c) (zero in the first row), at the encoder too.
  * Head layout o[12 K]: for each of R,G,B: K mixture logits, K means, K
  * log-sigmas (units of 1/256 of the grey range); then K alphas, K betas,
  * K gammas of Eq. (3)-(4).

@@ -442,7 +442,10 @@ struct DecLds {
     // A ring row is read by the two rows below it, which trail by delay and 2 * delay columns and
     // reach two columns further back, while the column being written and the zero columns right
     // of the image are stored: all of these must be distinct slots.
-    static_assert(2 * Net::kDelay + 2 + Net::kDelay <= Net::kRingCols, "ring too small for the neighbourhood");
+    static constexpr int kMaxReach = Net::kReach1 > Net::kReach2 ? Net::kReach1 : Net::kReach2;
+    static_assert(2 * Net::kDelay + 3 + kMaxReach <= Net::kRingCols, "ring too small for the neighbourhood");
+    // what a row reads of the rows above must have been decoded in an earlier pass
+    static_assert(Net::kReach1 <= Net::kDelay - 1 && Net::kReach2 <= 2 * Net::kDelay - 1, "schedule is not causal");
 };
 
 // All-reduce over the 16 lanes of a DPP row by rotations.
@@ -683,7 +686,7 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
     using Lay = Layout<Net>;
     using D = DecLds<Net>;
     constexpr int K = Net::K, HS = Lay::kHeadSlots, RC = Net::kRingCols, KB0 = Net::kb(0);
-    constexpr int kDelay = Net::kDelay, kReach = Net::kDelay - 1;   // columns right of c the neighbourhood reaches
+    constexpr int kDelay = Net::kDelay, kMaxReach = D::kMaxReach;
     extern __shared__ __align__(16) uint8_t lds[];
     float2* lut = reinterpret_cast<float2*>(lds + D::kLutOff);
     uint8_t* act0 = lds + D::kAct0Off;
@@ -755,6 +758,10 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
     const int t_begin = kDelay * r0, t_end = kDelay * last_row + W - 1;
     const bool fetcher = band > 0 && tid < 2;     // thread 0: row r0-2 -> ring row 0; thread 1: row r0-1 -> ring row 1
     const uint32_t* mail_row = mail_in + (size_t)(tid & 1) * W;
+    // Columns right of the band's first row's column that the fetched row must be known to: row r0-2 is
+    // read by the band's first row only; row r0-1 by the first row and, one delay later, by the second.
+    const int ahead = (tid & 1) ? (Net::kReach1 > Net::kReach2 - kDelay ? Net::kReach1 : Net::kReach2 - kDelay)
+                                : Net::kReach2;
     uint32_t pf = 0;                              // mailbox word for the next column, requested a step early
 
     // bf16 of the three channels of pixel word px into both copies of column cc of a ring row
@@ -765,8 +772,8 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
         d[0] = v0; d[1] = v1; d[2] = v2;
         d[3 * RC] = v0; d[3 * RC + 1] = v1; d[3 * RC + 2] = v2;
     };
-    // Bring columns 0 .. reach of the two rows above the band into the ring, then keep
-    // one column ahead: the step at t needs column (t - t_begin) + reach.
+    // Bring columns 0 .. ahead of the two rows above the band into the ring, then keep
+    // one column ahead: the step at t needs column (t - t_begin) + ahead.
     auto fetch_column = [&](int cc, uint32_t have) -> bool {   // returns false on abort
         uint32_t v = have, spins = 0;
         while (!(v & kMailTag)) {
@@ -784,9 +791,9 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
     };
     if (fetcher) {
         bool ok = true;
-        for (int cc = 0; cc <= kReach; ++cc)
+        for (int cc = 0; cc <= ahead; ++cc)
             if (ok && cc < W) ok = fetch_column(cc, 0u);
-        if (ok && W > kReach + 1) pf = __hip_atomic_load(mail_row + kReach + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (ok && W > ahead + 1) pf = __hip_atomic_load(mail_row + ahead + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (!ok) {
             __hip_atomic_store(&status[kStAbort], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             misc[1] = 1;
@@ -915,7 +922,7 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
             ring_put(q + 2, c, px);
             if (c == W - 1) {                       // the columns right of the image read as zero
 #pragma unroll
-                for (int z = 0; z < kReach; ++z) ring_put(q + 2, W + z, 0u);
+                for (int z = 0; z < kMaxReach; ++z) ring_put(q + 2, W + z, 0u);
             }
             uint8_t* o = out_img + ((size_t)qrow * W + c) * 3;
             o[0] = (uint8_t)sr; o[1] = (uint8_t)sg; o[2] = (uint8_t)sb;
@@ -926,8 +933,8 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
         }
         // ---- rows above the band: column needed by the next step, and request the one after
         if (fetcher) {
-            const int cc = t - t_begin + kReach + 1;
-            if (cc >= W && cc < W + kReach) ring_put(tid & 1, cc, 0u);    // the columns right of the image read as zero
+            const int cc = t - t_begin + ahead + 1;
+            if (cc >= W && cc < W + kMaxReach) ring_put(tid & 1, cc, 0u);    // the columns right of the image read as zero
             if (cc < W && t < t_end) {
                 if (!fetch_column(cc, pf)) {
                     __hip_atomic_store(&status[kStAbort], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -978,7 +985,7 @@ cdf_tables_kernel(const uint8_t* __restrict__ model, const float* __restrict__ p
 // ===========================================================================
 using namespace pcc;
 
-enum { kNetWorkload = 0, kNetPaper = 1 };
+enum { kNetWorkload = 0, kNetPaper = 1, kNetDiagonal = 2 };
 
 struct pcc_ctx {
     int device = 0;
@@ -1065,6 +1072,16 @@ bool dims_ok(int n, int H, int W) {
            (uint64_t)H * W * 3 < (1ull << 31);   // byte offsets within one image are 32-bit
 }
 
+// Calls f with a value of the network description type that `net` names.
+template <class F>
+auto with_net(int net, F&& f) {
+    switch (net) {
+        case kNetPaper: return f(NetPaper{});
+        case kNetDiagonal: return f(NetDiagonal{});
+        default: return f(NetWorkload{});
+    }
+}
+
 // Does the blob header describe network Net?  (activation id 0 = ReLU, 1 = LeakyReLU 0.01)
 template <class Net>
 bool header_matches(const uint8_t* p) {
@@ -1106,7 +1123,7 @@ int pack_model(const uint8_t* p, size_t blob_bytes, uint32_t dist, std::vector<u
                         // output feature of A row m of this out-block
                         const int o = head ? Net::head_index(m >> 2, 4 * ob + (m & 3)) : 16 * ob + m;
                         // input feature of k-slot (g, i) of this k-block
-                        const int in = l == 0 ? in1_index<Net>(kb, g, i) : 32 * kb + kslot_feature(g, i);
+                        const int in = l == 0 ? Net::in_index(kb, g, i) : 32 * kb + kslot_feature(g, i);
                         float v = 0.0f;
                         if (o >= 0 && o < Net::dim(l + 1) && in >= 0 && in < Net::dim(l)) v = Wat(l, o, in);
                         uint16_t h;
@@ -1193,8 +1210,9 @@ int launch_encode(pcc_ctx* ctx, const uint8_t* d_img, int n, int H, int W, uint3
 
 int launch_encode_any(pcc_ctx* ctx, const uint8_t* d_img, int n, int H, int W, uint32_t* sf, float* params, float* bits,
                       hipStream_t st) {
-    return ctx->net == kNetPaper ? launch_encode<NetPaper>(ctx, d_img, n, H, W, sf, params, bits, st)
-                                 : launch_encode<NetWorkload>(ctx, d_img, n, H, W, sf, params, bits, st);
+    return with_net(ctx->net, [&](auto net) {
+        return launch_encode<decltype(net)>(ctx, d_img, n, H, W, sf, params, bits, st);
+    });
 }
 
 template <class Net>
@@ -1212,7 +1230,7 @@ void launch_decode(pcc_ctx* ctx, const uint8_t* d_stream, size_t nbytes, int n, 
 }
 
 inline int head_outputs(const pcc_ctx* ctx) {
-    return ctx->net == kNetPaper ? NetPaper::dim(NetPaper::kLayers) : NetWorkload::dim(NetWorkload::kLayers);
+    return with_net(ctx->net, [](auto net) { using Net = decltype(net); return Net::dim(Net::kLayers); });
 }
 
 }  // namespace
@@ -1254,11 +1272,11 @@ int pcc_create(pcc_ctx** out, const void* h_blob, size_t blob_bytes, int hip_dev
     int net;
     if (header_matches<NetWorkload>(p)) net = kNetWorkload;
     else if (header_matches<NetPaper>(p)) net = kNetPaper;
+    else if (header_matches<NetDiagonal>(p)) net = kNetDiagonal;
     else return PCC_E_BLOB;
 
     std::vector<uint8_t> image;
-    const int prc = net == kNetPaper ? pack_model<NetPaper>(p, blob_bytes, dist, image)
-                                     : pack_model<NetWorkload>(p, blob_bytes, dist, image);
+    const int prc = with_net(net, [&](auto tag) { return pack_model<decltype(tag)>(p, blob_bytes, dist, image); });
     if (prc != PCC_OK) return prc;
 
     DeviceGuard guard(hip_device);
@@ -1275,7 +1293,7 @@ int pcc_create(pcc_ctx** out, const void* h_blob, size_t blob_bytes, int hip_dev
     ok = ok && hipMalloc((void**)&ctx->d_status, kStWords * sizeof(int) + sizeof(uint64_t)) == hipSuccess;
     ok = ok && hipHostMalloc((void**)&ctx->h_status, kStWords * sizeof(int) + sizeof(uint64_t), hipHostMallocDefault) == hipSuccess;
     ok = ok && hipMemcpy(ctx->d_model, image.data(), image.size(), hipMemcpyHostToDevice) == hipSuccess;
-    ok = ok && (net == kNetPaper ? set_kernel_attributes<NetPaper>() : set_kernel_attributes<NetWorkload>());
+    ok = ok && with_net(net, [](auto tag) { return set_kernel_attributes<decltype(tag)>(); });
     if (const char* e = getenv("PCC_ENCODE_VARIANT")) {
         const int v = atoi(e);
         if (v >= 0 && v < 3) ctx->encode_variant = v;
@@ -1299,13 +1317,16 @@ void pcc_destroy(pcc_ctx* ctx) {
 
 int pcc_model_info(const pcc_ctx* ctx, int* h_info) {
     if (!ctx || !h_info) return PCC_E_ARG;
-    const bool paper = ctx->net == kNetPaper;
-    h_info[0] = head_outputs(ctx);
-    h_info[1] = paper ? NetPaper::K : NetWorkload::K;
-    h_info[2] = paper ? NetPaper::kNbhd : NetWorkload::kNbhd;
-    h_info[3] = paper ? NetPaper::kDelay : NetWorkload::kDelay;
-    h_info[4] = (int)ctx->dist;
-    h_info[5] = paper ? NetPaper::kLayers : NetWorkload::kLayers;
+    with_net(ctx->net, [&](auto tag) {
+        using Net = decltype(tag);
+        h_info[0] = Net::dim(Net::kLayers);
+        h_info[1] = Net::K;
+        h_info[2] = Net::kNbhd;
+        h_info[3] = Net::kDelay;
+        h_info[4] = (int)ctx->dist;
+        h_info[5] = Net::kLayers;
+        return 0;
+    });
     return PCC_OK;
 }
 
@@ -1351,7 +1372,7 @@ int pcc_encode(pcc_ctx* ctx, const uint8_t* d_img, int n, int H, int W, uint8_t*
                        d_slabs, d_rw);
     prof_end(ctx, PCC_T_ENCODE_RANS, st);
     prof_begin(ctx, PCC_T_ENCODE_SCAN, st);
-    const uint32_t tag = ctx->net == kNetPaper ? model_tag<NetPaper>() : model_tag<NetWorkload>();
+    const uint32_t tag = with_net(ctx->net, [](auto net) { return model_tag<decltype(net)>(); });
     hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), 0, st, d_rw, rows, n, H, W, tag, ctx->dist, d_stream, ctx->d_total);
     prof_end(ctx, PCC_T_ENCODE_SCAN, st);
     prof_begin(ctx, PCC_T_ENCODE_COMPACT, st);
@@ -1392,10 +1413,10 @@ int pcc_decode(pcc_ctx* ctx, const uint8_t* d_stream, size_t nbytes, int n, int 
     const uint32_t spin_limit = 1u << 22;
     prof_reset(ctx);
     prof_begin(ctx, PCC_T_DECODE, st);
-    if (ctx->net == kNetPaper)
-        launch_decode<NetPaper>(ctx, d_stream, nbytes, n, H, W, nbands, d_img_out, d_mail, spin_limit, st);
-    else
-        launch_decode<NetWorkload>(ctx, d_stream, nbytes, n, H, W, nbands, d_img_out, d_mail, spin_limit, st);
+    with_net(ctx->net, [&](auto net) {
+        launch_decode<decltype(net)>(ctx, d_stream, nbytes, n, H, W, nbands, d_img_out, d_mail, spin_limit, st);
+        return 0;
+    });
     prof_end(ctx, PCC_T_DECODE, st);
     if (hipGetLastError() != hipSuccess) return PCC_E_HIP;
     if (hipMemcpyAsync(ctx->h_status, ctx->d_status, kStWords * sizeof(int), hipMemcpyDeviceToHost, st) != hipSuccess)
@@ -1412,12 +1433,11 @@ int pcc_cdf_tables(pcc_ctx* ctx, const float* d_params, const uint8_t* d_rg, siz
     if (!guard.ok) return PCC_E_HIP;
     const size_t threads = count * 3;
     const dim3 grid((uint32_t)((threads + 255) / 256));
-    if (ctx->net == kNetPaper)
-        hipLaunchKernelGGL(cdf_tables_kernel<NetPaper>, grid, dim3(256), (kLutEntries + 1) * 8, (hipStream_t)hip_stream,
+    with_net(ctx->net, [&](auto net) {
+        hipLaunchKernelGGL(cdf_tables_kernel<decltype(net)>, grid, dim3(256), (kLutEntries + 1) * 8, (hipStream_t)hip_stream,
                            ctx->d_model, d_params, d_rg, count, d_cq);
-    else
-        hipLaunchKernelGGL(cdf_tables_kernel<NetWorkload>, grid, dim3(256), (kLutEntries + 1) * 8, (hipStream_t)hip_stream,
-                           ctx->d_model, d_params, d_rg, count, d_cq);
+        return 0;
+    });
     return hipGetLastError() == hipSuccess ? PCC_OK : PCC_E_HIP;
 }
 

@@ -27,12 +27,26 @@ typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 // next layer, so ob(l) = 2 kb(l+1).
 // ---------------------------------------------------------------------------
 
+// Canonical input index 3*j + ch (neighbour j in raster order, channel ch) of slot i
+// (0..7) of lane group g in first-layer k-block kbi, or -1 for a padding slot, for a
+// network whose byte runs carry the neighbours in place.
+template <class Net>
+__host__ __device__ constexpr int run_in_index(int kbi, int g, int i) {
+    int dr = 0, off = 0;
+    if (!Net::run_desc(kbi, g, i >> 2, dr, off)) return -1;
+    const int b = off + (i & 3);
+    const int len = dr == 0 ? 6 : Net::kUpBytes;
+    if (b >= len) return -1;
+    return (dr == -2 ? 0 : dr == -1 ? Net::kUpBytes : 2 * Net::kUpBytes) + b;
+}
+
 // The measured workloads' network: 30 -> 160 -> 160 -> 128 -> 60, ReLU, K = 5,
 // neighbourhood {rows r-2, r-1 at columns c-2..c+1; row r at c-2, c-1}, wavefront delay 2.
 struct NetWorkload {
     static constexpr int kLayers = 4;
     static constexpr int K = 5;
     static constexpr int kNbhd = 10, kDelay = 2;
+    static constexpr int kReach1 = 1, kReach2 = 1;   // columns right of c that rows r-1 and r-2 are read at
     static constexpr int kUpBytes = 12;       // bytes of one upper row's neighbours (columns c-2..c+1)
     static constexpr int kRingCols = 8;       // decoder ring columns (power of two)
     static constexpr bool kLeaky = false;
@@ -55,6 +69,7 @@ struct NetWorkload {
         else { dr = g == 0 ? -2 : (g == 2 ? -1 : 0); off = g == 1 ? 0 : 4; }
         return true;
     }
+    __host__ __device__ static constexpr int in_index(int kbi, int g, int i) { return run_in_index<NetWorkload>(kbi, g, i); }
 };
 
 // The paper's own network (Sec. III-B; hyper-parameter table of Sec. IV-E): the 12
@@ -64,6 +79,7 @@ struct NetPaper {
     static constexpr int kLayers = 5;
     static constexpr int K = 3;
     static constexpr int kNbhd = 12, kDelay = 3;
+    static constexpr int kReach1 = 2, kReach2 = 2;
     static constexpr int kUpBytes = 15;
     static constexpr int kRingCols = 16;
     static constexpr bool kLeaky = true;
@@ -81,7 +97,55 @@ struct NetPaper {
         dr = 0; off = 4 * half;
         return g == 0;
     }
+    __host__ __device__ static constexpr int in_index(int kbi, int g, int i) { return run_in_index<NetPaper>(kbi, g, i); }
 };
+
+// The same network in the diagonal decoding order (Sec. III-C, Eq. (7)): a pass decodes the
+// anti-diagonal r + c = t (delay 1), so the neighbours (r-2,c+2), (r-1,c+1), (r-1,c+2) are not yet
+// decoded; their nine inputs carry copies of pixel (r-1,c) instead.  The copies are made by
+// reading that pixel's bytes again: extra runs that start at byte 5, 6 or 8 of row r-1.
+struct NetDiagonal : NetPaper {
+    static constexpr int kDelay = 1;
+    static constexpr int kReach1 = 0, kReach2 = 1;   // row r-1 is read up to column c, row r-2 up to c+1
+    static constexpr int kRingCols = 8;
+    __host__ __device__ static constexpr bool run_desc(int kbi, int g, int half, int& dr, int& off) {
+        if (kbi == 0) {
+            if (g == 0) { dr = -2; off = 4 * half; }                          // row r-2, bytes 0..7
+            else if (g == 1) { dr = half ? -1 : -2; off = half ? 6 : 8; }     // row r-2 bytes 8..11 | copy for (r-2,c+2)
+            else if (g == 2) { dr = -1; off = 4 * half; }                     // row r-1, bytes 0..7
+            else { dr = -1; off = half ? 6 : 5; }                             // copies for (r-1,c+1) | (r-1,c+2)
+            return true;
+        }
+        if (g == 0) { dr = 0; off = 4 * half; return true; }                  // row r, bytes 0..5
+        dr = -1; off = 8;                                                     // row r-1 byte 8: pixel (r-1,c), blue
+        return g == 1 && half == 0;
+    }
+    __host__ __device__ static constexpr int in_index(int kbi, int g, int i) {
+        if (kbi == 0) {
+            if (g == 0) return i;
+            if (g == 1) return i < 4 ? 8 + i : (i < 7 ? 12 + (i - 4) : -1);
+            if (g == 2) return 15 + i;
+            return i == 0 ? -1 : (i < 4 ? 24 + (i - 1) : (i < 7 ? 27 + (i - 4) : -1));
+        }
+        if (g == 0) return i < 6 ? 30 + i : -1;
+        return (g == 1 && i == 0) ? 23 : -1;
+    }
+};
+
+// Every canonical first-layer input sits in exactly one k-slot.
+template <class Net>
+constexpr bool inputs_placed_once() {
+    for (int want = 0; want < Net::dim(0); ++want) {
+        int n = 0;
+        for (int kbi = 0; kbi < Net::kb(0); ++kbi)
+            for (int g = 0; g < 4; ++g)
+                for (int i = 0; i < 8; ++i) n += Net::in_index(kbi, g, i) == want ? 1 : 0;
+        if (n != 1) return false;
+    }
+    return true;
+}
+static_assert(inputs_placed_once<NetWorkload>() && inputs_placed_once<NetPaper>() && inputs_placed_once<NetDiagonal>(),
+              "first-layer slot map");
 
 constexpr int kBlockBytes = 64 * 16;  // one (out-block, k-block) A operand: 64 lanes x 8 bf16
 
@@ -118,17 +182,6 @@ struct Layout {
 };
 static_assert(Layout<NetWorkload>::kWeightBytes == 118784, "workload weight image size");
 
-// Canonical input index 3*j + ch of slot i (0..7) of lane group g in first-layer
-// k-block kbi, or -1 for a padding slot.
-template <class Net>
-__host__ __device__ constexpr int in1_index(int kbi, int g, int i) {
-    int dr = 0, off = 0;
-    if (!Net::run_desc(kbi, g, i >> 2, dr, off)) return -1;
-    const int b = off + (i & 3);
-    const int len = dr == 0 ? 6 : Net::kUpBytes;
-    if (b >= len) return -1;
-    return (dr == -2 ? 0 : dr == -1 ? Net::kUpBytes : 2 * Net::kUpBytes) + b;
-}
 // Feature index (within a 32-wide k-block) held in slot i of lane group g for
 // the layers after the first: the two 16-row output tiles of the previous layer,
 // as MFMA left them.

@@ -220,3 +220,91 @@ def test_streams_of_the_other_network_are_refused(codec_paper, blob):
         assert e.value.code == binding.PCC_E_STREAM
     finally:
         other.close()
+
+
+# ----------------------------------------------------------------- diagonal decoding order (Sec. III-C, Eq. (7))
+
+TAG_DIAGONAL = 3 | (12 << 8) | (1 << 16) | (16 << 24)
+
+
+@pytest.fixture(scope="module")
+def codec_diagonal(diagonal_blob):
+    from paper_2212_01185_amd import binding
+    c = binding.Codec(diagonal_blob, 0)
+    yield c
+    c.close()
+
+
+@pytest.fixture(scope="module")
+def codec_diagonal_sharp(diagonal_sharp_blob):
+    from paper_2212_01185_amd import binding
+    c = binding.Codec(diagonal_sharp_blob, 0)
+    yield c
+    c.close()
+
+
+def test_diagonal_params_and_bits_match_oracle(codec_diagonal, orc_diagonal, orc_paper):
+    assert codec_diagonal.pcc_model_info() == (36, 3, 12, 1, 0, 5)
+    rng = np.random.default_rng(51)
+    for name, img in (("64x64 workload image", synth.make_batch(0)[0]),
+                      ("19x37 random", rng.integers(0, 256, (19, 37, 3), dtype=np.uint8))):
+        _log("diagonal: encode_probs %s" % name)
+        h, w, _ = img.shape
+        params, bits = codec_diagonal.pcc_encode_probs(_dev(img[None]))
+        torch.cuda.synchronize()
+        got = params.cpu().numpy().astype(np.float64)[0]
+        exact = orc_diagonal.params_rows(img, range(h), po.MODE_EXACT)
+        err = np.abs(got - exact).max()
+        _log("max |params - oracle(exact)| = %.3g" % err)
+        assert err <= PARAM_ATOL
+        assert np.abs(got - orc_diagonal.params_rows(img, range(h), po.MODE_SPLIT)).max() <= PARAM_ATOL_SPLIT
+        # the copied neighbours matter: the wavefront model of the same weights gives other outputs
+        assert np.abs(got - orc_paper.params_rows(img, range(h), po.MODE_EXACT)).max() > 10 * PARAM_ATOL
+        _, wbits = orc_diagonal.encode(img[None], po.MODE_EXACT)
+        gbits = bits.cpu().numpy().astype(np.float64)
+        _log("bits/pixel gpu %.5f oracle %.5f" % (gbits.mean(), wbits.mean()))
+        assert abs(gbits.sum() / wbits.sum() - 1) <= BITS_RTOL
+
+
+def test_diagonal_container_bit_exact(codec_diagonal, codec_diagonal_sharp):
+    rng = np.random.default_rng(52)
+    imgs = rng.integers(0, 256, (2, 17, 33, 3), dtype=np.uint8)
+    for c in (codec_diagonal, codec_diagonal_sharp):
+        stream = c.pcc_encode(_dev(imgs))
+        iv = c.pcc_copy_intervals(2, 17, 33)
+        torch.cuda.synchronize()
+        iv = iv.cpu().numpy().view(np.uint32)
+        sf = iv.reshape(2 * 17, 3 * 33)
+        payloads = [po.rans_encode(row & 0xFFFF, (row >> 16) + 1) for row in sf]
+        offs = np.concatenate([[0], np.cumsum([len(p) for p in payloads])]).astype("<u8")
+        want = struct.pack("<8I", 0x31434350, 1, 2, 17, 33, TAG_DIAGONAL, 0, 0) + offs.tobytes() + b"".join(payloads)
+        assert stream.cpu().numpy().tobytes() == want
+
+
+def test_diagonal_roundtrip_edge_shapes(codec_diagonal, codec_diagonal_sharp):
+    for name, imgs in _edge_images():
+        for which, c in (("default", codec_diagonal), ("sharp", codec_diagonal_sharp)):
+            _log("diagonal roundtrip %s %s" % (name, which))
+            _, out = _roundtrip(c, imgs)
+            np.testing.assert_array_equal(out, imgs, err_msg="%s %s" % (name, which))
+
+
+def test_diagonal_512x512_and_pass_count(codec_diagonal, codec_paper):
+    from paper_2212_01185_amd import binding
+    img = synth.make_image(7, synth.ImageSpec(512, 512, 24, 8.0, 64.0))[None]
+    _log("diagonal 512x512 round trip")
+    stream, out = _roundtrip(codec_diagonal, img)
+    assert np.array_equal(out, img)
+    assert binding.pcc_wavefront_steps(512, 512, codec_diagonal.delay) == 2 * 512 - 1      # Eq. (7)
+    # a batch taller than wide with ragged bands, several images
+    imgs = np.stack([synth.make_image(s, synth.ImageSpec(45, 83, 6, 3.0, 12.0)) for s in range(3)])
+    _, out = _roundtrip(codec_diagonal, imgs)
+    assert np.array_equal(out, imgs)
+    # streams name their decoding order: the wavefront model refuses a diagonal stream and vice versa
+    with pytest.raises(binding.PccError) as e:
+        codec_paper.pcc_decode(stream, 1, 512, 512)
+    assert e.value.code == binding.PCC_E_STREAM
+    s2 = codec_paper.pcc_encode(_dev(img))
+    with pytest.raises(binding.PccError) as e:
+        codec_diagonal.pcc_decode(s2, 1, 512, 512)
+    assert e.value.code == binding.PCC_E_STREAM
