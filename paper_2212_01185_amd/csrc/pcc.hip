@@ -38,7 +38,7 @@ constexpr uint32_t model_tag() { return (uint32_t)Net::K | ((uint32_t)Net::kNbhd
 // Encode kernel variants: tiles of 16 pixels per wave per iteration x threads per workgroup.
 // More tiles per wave reuse each LDS weight read more often but need more registers.
 struct EncodeVariant { int tiles, threads; };
-constexpr EncodeVariant kEncodeVariants[3] = {{1, 512}, {2, 512}, {1, 1024}};
+constexpr EncodeVariant kEncodeVariants[4] = {{1, 512}, {2, 512}, {1, 1024}, {4, 256}};
 constexpr int kDefaultEncodeVariant = 1;
 
 // status words in device memory
@@ -702,8 +702,8 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
     // search role: pixel q of the band, lane j of its group
     const int q = 4 * wave + (lane >> 4), j = lane & 15;
 
-    // Bands take tickets in start order: a band only ever waits for the band
-    // above it, which holds a smaller ticket and is therefore already running.
+    // Bands take tickets in start order: a band only ever waits for the band above it
+    // (same image), which holds a smaller ticket and is therefore already running.
     if (tid == 0) { misc[0] = atomicAdd(&status[kStTicket], 1); misc[1] = 0; }
     {
         const float2* src = reinterpret_cast<const float2*>(model + Lay::kLutOff);
@@ -716,9 +716,12 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
     net.load(model, lane, wave);
     __syncthreads();
 
+    // Tickets are handed out band-major (band 0 of every image, then band 1 of every image, ...):
+    // the order in which bands become runnable.  A workgroup slot is then held by a band that can
+    // run rather than by one that waits for hundreds of steps, and all images advance together.
     const int ticket = misc[0];
-    const int im = ticket / nbands, band = ticket - im * nbands;
-    if (im >= n) return;
+    const int band = ticket / n, im = ticket - band * n;
+    if (band >= nbands) return;
     const float lut_scale = *reinterpret_cast<const float*>(model + Lay::kLutScaleOff);
 
     const int r0 = band * kBandRows;
@@ -1174,6 +1177,8 @@ bool set_kernel_attributes() {
                                    hipFuncAttributeMaxDynamicSharedMemorySize, enc) == hipSuccess;
     ok = ok && hipFuncSetAttribute(reinterpret_cast<const void*>(&encode_kernel<Net, 1, 1024>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, enc) == hipSuccess;
+    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void*>(&encode_kernel<Net, 4, 256>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, enc) == hipSuccess;
     ok = ok && hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_kernel<Net, 1>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, dec) == hipSuccess;
     ok = ok && hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_kernel<Net, 2>),
@@ -1200,9 +1205,13 @@ int launch_encode(pcc_ctx* ctx, const uint8_t* d_img, int n, int H, int W, uint3
             hipLaunchKernelGGL((encode_kernel<Net, 2, 512>), dim3(blocks), dim3(512), kLds, st, ctx->d_model, d_img, H, W, P,
                                sf, params, bits, ctx->d_status);
             break;
-        default:
+        case 2:
             hipLaunchKernelGGL((encode_kernel<Net, 1, 1024>), dim3(blocks), dim3(1024), kLds, st, ctx->d_model, d_img, H, W,
                                P, sf, params, bits, ctx->d_status);
+            break;
+        default:
+            hipLaunchKernelGGL((encode_kernel<Net, 4, 256>), dim3(blocks), dim3(256), kLds, st, ctx->d_model, d_img, H, W, P,
+                               sf, params, bits, ctx->d_status);
             break;
     }
     return hipGetLastError() == hipSuccess ? PCC_OK : PCC_E_HIP;
@@ -1296,7 +1305,7 @@ int pcc_create(pcc_ctx** out, const void* h_blob, size_t blob_bytes, int hip_dev
     ok = ok && with_net(net, [](auto tag) { return set_kernel_attributes<decltype(tag)>(); });
     if (const char* e = getenv("PCC_ENCODE_VARIANT")) {
         const int v = atoi(e);
-        if (v >= 0 && v < 3) ctx->encode_variant = v;
+        if (v >= 0 && v < 4) ctx->encode_variant = v;
     }
     if (!ok) { (void)hipGetLastError(); pcc_destroy(ctx); return PCC_E_HIP; }
     ctx->d_total = reinterpret_cast<uint64_t*>(ctx->d_status + kStWords);
