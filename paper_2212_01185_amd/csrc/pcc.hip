@@ -630,6 +630,9 @@ struct WaveNet {
             lds_barrier();
             u32x4_t nxt[Net::kb(L + 1)][2];
             dec_load_act<Net::kb(L + 1)>(out, lane, nxt);
+            // scheduling only: every read of the layer's input is issued before its first MFMA, so
+            // the LDS latency is paid once per layer and not once per k-block
+            __builtin_amdgcn_sched_barrier(0);
             rest.run(nxt, lane, wave, act0, act1, headout);
         }
     }
