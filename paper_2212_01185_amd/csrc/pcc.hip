@@ -465,15 +465,17 @@ __device__ __forceinline__ uint32_t row_allmin(uint32_t v) {
 }
 
 // rANS reader of one row, replicated in the 16 lanes of the pixel's group.  The
-// next 32 stream words sit in registers, lane j holding words base+j and
-// base+16+j, so a renormalisation never waits for memory: the refill issued
-// when a 16-word block is used up is not needed for another 16 words.
+// stream words of two consecutive blocks of 16 sit in registers, lane j holding
+// words 16 blk + j and 16 (blk + 1) + j, so a renormalisation never waits for
+// memory: a pixel consumes at most three words, and the refill issued at the end
+// of the step in which a block is used up is not needed for another 13 words.
 struct RowReader {
     uint64_t x;
     const uint32_t* payload;  // the row's payload: 8-byte state, then the words
     uint32_t last;            // index of the payload's last 32-bit word (>= 1: the state is two words)
     uint32_t nwords, pos;     // words after the state; words consumed so far
-    uint32_t cur, nxt;        // words[(pos & ~15) + j], words[(pos & ~15) + 16 + j]
+    uint32_t blk;             // block held in cur; pos >> 4 is blk or, within a step, blk + 1
+    uint32_t cur, nxt;
     bool bad;
 };
 
@@ -489,7 +491,8 @@ __device__ __forceinline__ uint32_t reader_word(const RowReader& rd, uint32_t i)
 // A reader over no words at all (rows outside the image, rows whose offsets are
 // damaged): `safe` is any readable pair of words; every renormalisation then counts as an over-read.
 __device__ __forceinline__ void reader_init_empty(RowReader& rd, const uint32_t* safe, bool bad) {
-    rd.x = kRansL; rd.payload = safe; rd.last = 1; rd.nwords = 0; rd.pos = 0; rd.cur = 0; rd.nxt = 0; rd.bad = bad;
+    rd.x = kRansL; rd.payload = safe; rd.last = 1; rd.nwords = 0; rd.pos = 0; rd.blk = 0; rd.cur = 0; rd.nxt = 0;
+    rd.bad = bad;
 }
 
 __device__ __forceinline__ void reader_init(RowReader& rd, const uint32_t* payload, uint32_t nwords_total, int j) {
@@ -498,28 +501,36 @@ __device__ __forceinline__ void reader_init(RowReader& rd, const uint32_t* paylo
     rd.last = nwords_total - 1;
     rd.nwords = nwords_total - 2;
     rd.pos = 0;
+    rd.blk = 0;
     rd.cur = reader_word(rd, (uint32_t)j);
     rd.nxt = reader_word(rd, (uint32_t)j + 16u);
     rd.bad = false;
     if (rd.x < kRansL || (rd.x >> 63)) { rd.bad = true; rd.x = kRansL; }
 }
 
+// D(x) for the symbol found at (start, freq), and the renormalisation read.  No branches:
+// the next channel's search only waits for the arithmetic, never for control flow.
 __device__ __forceinline__ void reader_advance(RowReader& rd, uint32_t slot, uint32_t start, uint32_t freq, int j,
                                                bool active) {
-    const uint32_t w = row_allmax((uint32_t)j == (rd.pos & 15u) ? rd.cur : 0u);   // words[pos], in every lane of the group
+    const uint32_t held = (rd.pos >> 4) != rd.blk ? rd.nxt : rd.cur;
+    const uint32_t w = row_allmax((uint32_t)j == (rd.pos & 15u) ? held : 0u);   // words[pos], in every lane of the group
     const uint64_t x1 = (uint64_t)freq * (rd.x >> 16) + slot - start;
     const bool renorm = active && x1 < kRansL;
-    if (active) rd.x = renorm ? ((x1 << 32) | w) : x1;
-    if (renorm) {
-        if (rd.pos >= rd.nwords) rd.bad = true;
-        rd.pos += 1;
-        if ((rd.pos & 15u) == 0u) {
-            rd.cur = rd.nxt;
-            // scheduling only: the copy is made before the load is issued, so that the load can
-            // write rd.nxt in place and stay in flight (no wait) until the next block change
-            asm volatile("" : "+v"(rd.cur));
-            rd.nxt = reader_word(rd, rd.pos + 16u + (uint32_t)j);
-        }
+    rd.x = active ? (renorm ? ((x1 << 32) | w) : x1) : rd.x;
+    rd.bad = rd.bad | (renorm & (rd.pos >= rd.nwords));
+    rd.pos += renorm ? 1u : 0u;
+}
+
+// Once per step, after the pixel's three symbols: when a block has been used up, move on
+// and request the block after the next.
+__device__ __forceinline__ void reader_refill(RowReader& rd, int j) {
+    if ((rd.pos >> 4) != rd.blk) {
+        rd.blk += 1;
+        rd.cur = rd.nxt;
+        // scheduling only: the copy is made before the load is issued, so that the load can
+        // write rd.nxt in place and stay in flight
+        asm volatile("" : "+v"(rd.cur));
+        rd.nxt = reader_word(rd, 16u * (rd.blk + 1u) + (uint32_t)j);
     }
 }
 
@@ -648,14 +659,17 @@ template <int K>
 __device__ __forceinline__ int group_search(const ChanParams<K>& cp, uint32_t slot, const float2* __restrict__ lut, int lane,
                                             uint32_t& start, uint32_t& freq) {
     const int j = lane & 15, shift = lane & 48;
-    // round 1: Cq(16 j); lanes 0..b satisfy Cq <= slot (Cq is increasing and Cq(0) = 0)
-    const uint32_t c1 = j == 0 ? 0u : cq_eval<K>(cp, 16 * j, lut);
+    // round 1: Cq(16 j); lanes 0..b satisfy Cq <= slot (Cq is increasing and Cq(0) = 0).
+    // Lane 0 evaluates too and discards the value: no branch.
+    const uint32_t e1 = cq_eval<K>(cp, 16 * j, lut);
+    const uint32_t c1 = j == 0 ? 0u : e1;
     const bool p1 = c1 <= slot;
     const int b = __popcll((__ballot(p1) >> shift) & 0xFFFFull) - 1;
     const uint32_t lo1 = row_allmax(p1 ? c1 : 0u);           // Cq(16 b)
     const uint32_t hi1 = row_allmin(p1 ? 65536u : c1);       // Cq(16 b + 16)
     // round 2: Cq(16 b + j)
-    const uint32_t c2 = j == 0 ? lo1 : cq_eval<K>(cp, 16 * b + j, lut);
+    const uint32_t e2 = cq_eval<K>(cp, 16 * b + j, lut);
+    const uint32_t c2 = j == 0 ? lo1 : e2;
     const bool p2 = c2 <= slot;
     const int cnt2 = __popcll((__ballot(p2) >> shift) & 0xFFFFull);
     start = row_allmax(p2 ? c2 : 0u);
@@ -921,6 +935,7 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
         slot = (uint32_t)rd.x & 0xFFFFu;
         const int sb = group_search<K>(cpb, slot, lut, lane, start, freq);
         reader_advance(rd, slot, start, freq, j, active);
+        reader_refill(rd, j);
 
         // ---- publish
         if (j == 0 && active) {
