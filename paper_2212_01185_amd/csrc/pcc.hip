@@ -794,30 +794,39 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
     };
     // Bring columns 0 .. ahead of the two rows above the band into the ring, then keep
     // one column ahead: the step at t needs column (t - t_begin) + ahead.
-    auto fetch_column = [&](int cc, uint32_t have) -> bool {   // returns false on abort
+    // wait_word: the published word of column cc (`have` if that already is one); clears ok on abort.
+    auto wait_word = [&](int cc, uint32_t have, bool& ok) -> uint32_t {
         uint32_t v = have, spins = 0;
         while (!(v & kMailTag)) {
             v = __hip_atomic_load(mail_row + cc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (v & kMailTag) break;
             ++spins;
-            if (spins > spin_limit) { set_error(status, PCC_E_INTERNAL); return false; }
+            if (spins > spin_limit) { set_error(status, PCC_E_INTERNAL); ok = false; break; }
             if ((spins & 63u) == 0u &&
-                __hip_atomic_load(&status[kStAbort], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)
-                return false;
+                __hip_atomic_load(&status[kStAbort], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+                ok = false;
+                break;
+            }
             __builtin_amdgcn_s_sleep(1);
         }
-        ring_put(tid & 1, cc, v);
-        return true;
+        return v;
+    };
+    auto give_up = [&]() {
+        __hip_atomic_store(&status[kStAbort], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        misc[1] = 1;
     };
     if (fetcher) {
         bool ok = true;
-        for (int cc = 0; cc <= ahead; ++cc)
-            if (ok && cc < W) ok = fetch_column(cc, 0u);
-        if (ok && W > ahead + 1) pf = __hip_atomic_load(mail_row + ahead + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (!ok) {
-            __hip_atomic_store(&status[kStAbort], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            misc[1] = 1;
+        for (int cc = 0; cc <= ahead; ++cc) {
+            if (ok && cc < W) {
+                const uint32_t v = wait_word(cc, 0u, ok);
+                if (ok) ring_put(tid & 1, cc, v);
+            }
         }
+        // Start one column further behind the band above than the data requires: the word requested a
+        // step ahead has then been published when it is asked for, and is not waited for at the step's end.
+        if (ok && W > ahead + 1) pf = wait_word(ahead + 1, 0u, ok);
+        if (!ok) give_up();
     }
     lds_barrier();
 
@@ -957,11 +966,11 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
             const int cc = t - t_begin + ahead + 1;
             if (cc >= W && cc < W + kMaxReach) ring_put(tid & 1, cc, 0u);    // the columns right of the image read as zero
             if (cc < W && t < t_end) {
-                if (!fetch_column(cc, pf)) {
-                    __hip_atomic_store(&status[kStAbort], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    misc[1] = 1;
-                }
-                pf = (cc + 1 < W) ? __hip_atomic_load(mail_row + cc + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
+                bool ok = true;
+                const uint32_t v = wait_word(cc, pf, ok);
+                if (ok) ring_put(tid & 1, cc, v);
+                pf = (ok && cc + 1 < W) ? __hip_atomic_load(mail_row + cc + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
+                if (!ok) give_up();
             }
         }
         lds_barrier();
