@@ -39,7 +39,7 @@ PEAK_BF16_TFLOPS = 2500.0        # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch of the encode kernel at 768x512 from rocprofv3 FETCH_SIZE / WRITE_SIZE,
 # scaled by what the same counters read for a plain 64 MiB copy (summary under profiles/).
-ENCODE_KERNEL_TRAFFIC_768x512 = {"fetch_bytes": 6.42e6, "write_bytes": 4.72e6, "algorithmic_bytes": 15 * 393216}
+ENCODE_KERNEL_TRAFFIC_768x512 = {"fetch_bytes": 5.74e6, "write_bytes": 4.72e6, "algorithmic_bytes": 15 * 393216}
 
 
 def cpu_baseline(blob, imgs, rows):
