@@ -241,20 +241,21 @@ encode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ img
 }
 
 // ---------------------------------------------------------------------------
-// rANS encode, one lane per row.  A workgroup is one wave owning 64 rows; the
-// rows' (start, freq) words are staged through LDS in chunks of 64 symbols
-// (coalesced reads, next chunk in flight while the current one is coded), so
-// the serial chain per row never waits for memory.
+// rANS encode, one lane per row.  A workgroup owns 64 rows: the lanes of wave 0
+// each run one row's serial chain, and waves 1-3 feed it -- they fetch the rows'
+// (start, freq) words chunk by chunk (coalesced), compute the fp64 reciprocal of
+// every frequency, and stage both in LDS one chunk ahead.  The coding wave's
+// instruction stream, which bounds the kernel, then holds only the chain itself.
 // ---------------------------------------------------------------------------
 constexpr int kRansRows = 64;
-constexpr int kRansChunk = 64;
+constexpr int kRansChunk = 32;
+constexpr int kRansThreads = 256;
 // Padding symbol (start 0, frequency 2^16): pushing it leaves the state unchanged
 // and never renormalises, so every chunk can be coded as a full one.
 constexpr uint32_t kRansNop = 0xFFFF0000u;
 
 // 1/f in fp64 for 1 <= f < 2^17: hardware estimate plus two Newton steps
-// (relative error ~2^-52).  Independent of the coder state, so several of these
-// are computed ahead of the serial chain.
+// (relative error ~2^-52).  Independent of the coder state.
 __device__ __forceinline__ double rans_recip(uint32_t f32) {
     const double fd = (double)f32;
     double rf = __builtin_amdgcn_rcp(fd);
@@ -279,69 +280,102 @@ __device__ __forceinline__ void rans_push(uint64_t& x, uint32_t f, uint32_t star
     x = (q << 16) + (uint64_t)((uint32_t)rem + start);
 }
 
-__global__ void __launch_bounds__(kRansRows)
+__global__ void __launch_bounds__(kRansThreads)
 rans_rows_kernel(const uint32_t* __restrict__ sf, int W, uint32_t rows, uint32_t* __restrict__ slabs,
                  uint32_t* __restrict__ row_words) {
-    __shared__ uint32_t buf[2][kRansRows][kRansChunk + 1];
-    const int lane = threadIdx.x;
+    // [buffer][row][symbol of the chunk]; the odd row strides keep the coding wave's column accesses off shared banks
+    __shared__ uint32_t sym[2][kRansRows][kRansChunk + 1];
+    __shared__ double rcp[2][kRansRows][kRansChunk + 1];
+    // renormalisation words the coding wave produced in a chunk, in the order produced; [row][kRansChunk] = their number
+    __shared__ uint32_t outw[2][kRansRows][kRansChunk + 1];
+    __shared__ uint32_t outpos[2][kRansRows];   // the row's slab position (words) before the chunk
+    const int tid = threadIdx.x, lane = tid & 63;
+    const bool coder = tid < 64;
     const uint32_t row0 = blockIdx.x * kRansRows;
     const uint32_t row = row0 + lane;
     const uint32_t nsym = 3u * (uint32_t)W;
     const int nchunks = (int)((nsym + kRansChunk - 1) / kRansChunk);
     const uint32_t live_rows = min((uint32_t)kRansRows, rows - row0);
     const size_t sw = slab_words(W);
-    uint32_t* slab = slabs + (size_t)min(row, rows - 1) * sw;
-    size_t wp = sw;
+    uint32_t wp = (uint32_t)sw;     // slabs fill from the end: the decoder reads the words in reverse order of production
     uint64_t x = kRansL;
 
-    uint32_t pre[kRansRows];   // chunk being fetched: element r is symbol k*64 + lane of row row0 + r
-    auto fetch = [&](int k) {
-        const uint32_t idx = (uint32_t)k * kRansChunk + lane;
+    constexpr int kFeeders = kRansThreads - 64;
+    constexpr int kPerFeeder = (kRansRows * kRansChunk + kFeeders - 1) / kFeeders;
+    // waves 1-3: chunk k of all 64 rows into buffer b.  All of a thread's loads are issued before the first is used.
+    auto produce = [&](int k, int b) {
+        uint32_t v[kPerFeeder];
 #pragma unroll
-        for (int r = 0; r < kRansRows; ++r)
-            pre[r] = ((uint32_t)r < live_rows && idx < nsym) ? sf[(size_t)(row0 + r) * nsym + idx] : kRansNop;
-    };
-    auto stage = [&](int b) {
+        for (int it = 0; it < kPerFeeder; ++it) {
+            const int e = tid - 64 + it * kFeeders;
+            const uint32_t r = (uint32_t)e / kRansChunk, i = (uint32_t)e % kRansChunk;
+            const uint32_t idx = (uint32_t)k * kRansChunk + i;
+            v[it] = (r < live_rows && idx < nsym) ? sf[(size_t)(row0 + r) * nsym + idx] : kRansNop;   // r >= 64 fails r < live_rows
+        }
 #pragma unroll
-        for (int r = 0; r < kRansRows; ++r) buf[b][r][lane] = pre[r];
+        for (int it = 0; it < kPerFeeder; ++it) {
+            const int e = tid - 64 + it * kFeeders;
+            if (e < kRansRows * kRansChunk) {
+                const uint32_t r = (uint32_t)e / kRansChunk, i = (uint32_t)e % kRansChunk;
+                sym[b][r][i] = v[it];
+                rcp[b][r][i] = rans_recip((v[it] >> 16) + 1u);
+            }
+        }
     };
-    fetch(nchunks - 1);
-    stage((nchunks - 1) & 1);
+    // waves 1-3: the words of a finished chunk from buffer b to the rows' slabs (consecutive lanes, consecutive words)
+    auto flush = [&](int b) {
+#pragma unroll
+        for (int it = 0; it < kPerFeeder; ++it) {
+            const int e = tid - 64 + it * kFeeders;
+            const uint32_t r = (uint32_t)e / kRansChunk, i = (uint32_t)e % kRansChunk;
+            if (r < live_rows && i < outw[b][r][kRansChunk])
+                slabs[(size_t)(row0 + r) * sw + (outpos[b][r] - 1u - i)] = outw[b][r][i];
+        }
+    };
+    if (!coder) produce(nchunks - 1, (nchunks - 1) & 1);
     __syncthreads();
     for (int k = nchunks - 1; k >= 0; --k) {
-        if (k > 0) fetch(k - 1);
-        if (row < rows) {
-            constexpr int kU = 8;   // reciprocals of the next 8 symbols are computed side by side
+        const int b = k & 1;
+        if (!coder) {
+            if (k + 1 < nchunks) flush(b ^ 1);           // what the coding wave produced in the previous chunk
+            if (k > 0) produce(k - 1, b ^ 1);
+        } else {
+            uint32_t cnt = 0;
+            constexpr int kU = 8;   // symbols fetched from LDS side by side
             for (int i0 = kRansChunk; i0 > 0; i0 -= kU) {
                 uint32_t v[kU];
                 double rf[kU];
 #pragma unroll
                 for (int u = 0; u < kU; ++u) {
-                    v[u] = buf[k & 1][lane][i0 - 1 - u];
-                    rf[u] = rans_recip((v[u] >> 16) + 1u);
+                    v[u] = sym[b][lane][i0 - 1 - u];
+                    rf[u] = rcp[b][lane][i0 - 1 - u];
                 }
-                // scheduling only: the eight reciprocals are finished before the serial chain starts
+                // scheduling only: one batch of LDS reads before the serial chain starts
                 asm volatile("" : "+v"(rf[0]), "+v"(rf[1]), "+v"(rf[2]), "+v"(rf[3]), "+v"(rf[4]), "+v"(rf[5]), "+v"(rf[6]), "+v"(rf[7]));
 #pragma unroll
                 for (int u = 0; u < kU; ++u) {
                     const uint32_t start = v[u] & 0xFFFFu, f = (v[u] >> 16) + 1u;
                     // renormalise when x >= f * 2^47; the word is stored either way and only
-                    // kept (wp moves) when it was due: no branch on the serial chain
+                    // kept (cnt moves) when it was due: no branch on the serial chain
                     const bool emit = (uint32_t)(x >> 47) >= f;
-                    slab[wp - 1] = (uint32_t)x;
-                    wp -= emit ? 1 : 0;
+                    outw[b][lane][cnt] = (uint32_t)x;
+                    cnt += emit ? 1u : 0u;
                     x = emit ? (x >> 32) : x;
                     rans_push(x, f, start, rf[u]);
                 }
             }
+            outw[b][lane][kRansChunk] = cnt;
+            outpos[b][lane] = wp;
+            wp -= cnt;
         }
-        if (k > 0) stage((k - 1) & 1);
         __syncthreads();
     }
-    if (row < rows) {
-        slab[--wp] = (uint32_t)(x >> 32);
-        slab[--wp] = (uint32_t)x;
-        row_words[row] = (uint32_t)(sw - wp);
+    if (!coder) flush(0);                                // chunk 0 lives in buffer 0
+    if (coder && row < rows) {
+        uint32_t* slab = slabs + (size_t)row * sw;
+        slab[wp - 1] = (uint32_t)(x >> 32);
+        slab[wp - 2] = (uint32_t)x;
+        row_words[row] = (uint32_t)sw - (wp - 2u);
     }
 }
 
@@ -1404,7 +1438,7 @@ int pcc_encode(pcc_ctx* ctx, const uint8_t* d_img, int n, int H, int W, uint8_t*
     if (rc != PCC_OK) return rc;
     prof_end(ctx, PCC_T_ENCODE_PIXELS, st);
     prof_begin(ctx, PCC_T_ENCODE_RANS, st);
-    hipLaunchKernelGGL(rans_rows_kernel, dim3((rows + kRansRows - 1) / kRansRows), dim3(kRansRows), 0, st, d_sf, W, rows,
+    hipLaunchKernelGGL(rans_rows_kernel, dim3((rows + kRansRows - 1) / kRansRows), dim3(kRansThreads), 0, st, d_sf, W, rows,
                        d_slabs, d_rw);
     prof_end(ctx, PCC_T_ENCODE_RANS, st);
     prof_begin(ctx, PCC_T_ENCODE_SCAN, st);
