@@ -470,7 +470,8 @@ struct DecLds {
     static constexpr int kRingRowElems = 2 * Net::kRingCols * 3;
     static constexpr int kRingOff = kCpOff + 16 * 3 * 16 * 4;
     static constexpr int kMiscOff = kRingOff + 18 * kRingRowElems * 2; // ticket, abort flag
-    static constexpr int kBytes = kMiscOff + 64;
+    static constexpr int kDumpOff = (kMiscOff + 64 + 15) / 16 * 16;    // 2 KB nobody reads: stores of out-blocks a wave does not own
+    static constexpr int kBytes = kDumpOff + 2 * 64 * 16;
     static_assert(kAct0Off % 16 == 0 && kHeadOff % 16 == 0 && kCpOff % 16 == 0, "vector alignment");
     static_assert((16 * kHS) % 16 == 0 && (kRingRowElems * 2) % 4 == 0, "vector alignment");
     // A ring row is read by the two rows below it, which trail by delay and 2 * delay columns and
@@ -599,35 +600,37 @@ struct WaveLayer {
 
 // One hidden layer on this wave's out-blocks.  Same arithmetic per output element
 // as hidden_layer<> in pcc_device.h: bias, then k-blocks in order, each hi then
-// lo; activation; split into hi + lo.
+// lo; activation; split into hi + lo.  The out-blocks are taken one after the
+// other (an accumulation chain of MFMAs issues back to back at full rate), so that
+// the activation and split of one block run in the shadow of the next block's MFMAs.
+// A block this wave does not own (ob >= NOB) is computed on a copy of the layer's
+// last block and stored to `dump`: no branch, one scheduling region per layer.
 template <int NOB, int NKB, int SLOTS, bool SPLIT_IN, bool LEAKY>
 __device__ __forceinline__ void dec_hidden_layer(const WaveLayer<NOB, NKB, SLOTS>& wl, int lane, int wave,
-                                                 const u32x4_t (&in)[NKB][2], uint8_t* __restrict__ act_out) {
+                                                 const u32x4_t (&in)[NKB][2], uint8_t* __restrict__ act_out,
+                                                 uint8_t* __restrict__ dump) {
+    auto finish = [&](int s, const f32x4_t& acc) {
+        const int ob = wave + 4 * s;
+        uint32_t l0, l1;
+        const uint32_t h0 = act_split_bf16<LEAKY>(acc.x, acc.y, l0);
+        const uint32_t h1 = act_split_bf16<LEAKY>(acc.z, acc.w, l1);
+        // out-block ob is half (ob & 1) of k-block ob/2 of the next layer's operand
+        uint8_t* dst = ob < NOB ? act_out + (((ob >> 1) * 2) * 64 + lane) * 16 + 8 * (ob & 1) : dump + lane * 16;
+        *reinterpret_cast<uint2*>(dst) = make_uint2(h0, h1);
+        *reinterpret_cast<uint2*>(dst + 64 * 16) = make_uint2(l0, l1);
+    };
     f32x4_t acc[SLOTS];
 #pragma unroll
-    for (int s = 0; s < SLOTS; ++s) acc[s] = wl.bias[s];
-#pragma unroll
-    for (int kb = 0; kb < NKB; ++kb) {
-#pragma unroll
-        for (int s = 0; s < SLOTS; ++s) acc[s] = mfma16(wl.a[s][kb], in[kb][0], acc[s]);
-        if (SPLIT_IN) {
-#pragma unroll
-            for (int s = 0; s < SLOTS; ++s) acc[s] = mfma16(wl.a[s][kb], in[kb][1], acc[s]);
-        }
-    }
-#pragma unroll
     for (int s = 0; s < SLOTS; ++s) {
-        const int ob = wave + 4 * s;
-        if (ob < NOB) {
-            uint32_t l0, l1;
-            const uint32_t h0 = act_split_bf16<LEAKY>(acc[s].x, acc[s].y, l0);
-            const uint32_t h1 = act_split_bf16<LEAKY>(acc[s].z, acc[s].w, l1);
-            // out-block ob is half (ob & 1) of k-block ob/2 of the next layer's operand
-            uint8_t* dst = act_out + (((ob >> 1) * 2) * 64 + lane) * 16 + 8 * (ob & 1);
-            *reinterpret_cast<uint2*>(dst) = make_uint2(h0, h1);
-            *reinterpret_cast<uint2*>(dst + 64 * 16) = make_uint2(l0, l1);
+        acc[s] = wl.bias[s];
+#pragma unroll
+        for (int kb = 0; kb < NKB; ++kb) {
+            acc[s] = mfma16(wl.a[s][kb], in[kb][0], acc[s]);
+            if (SPLIT_IN) acc[s] = mfma16(wl.a[s][kb], in[kb][1], acc[s]);
         }
+        if (s > 0) finish(s - 1, acc[s - 1]);
     }
+    finish(SLOTS - 1, acc[SLOTS - 1]);
 }
 
 template <int NKB>
@@ -655,7 +658,8 @@ struct WaveNet {
         rest.load(model, lane, wave);
     }
     __device__ __forceinline__ void run(const u32x4_t (&in)[NKB][2], int lane, int wave, uint8_t* __restrict__ act0,
-                                        uint8_t* __restrict__ act1, float* __restrict__ headout) const {
+                                        uint8_t* __restrict__ act1, float* __restrict__ headout,
+                                        uint8_t* __restrict__ dump) const {
         if constexpr (kHead) {
             static_assert(SLOTS == 1, "the head has at most four out-blocks, one per wave");
             f32x4_t acc = wl.bias[0];
@@ -671,14 +675,14 @@ struct WaveNet {
             lds_barrier();
         } else {
             uint8_t* out = (L & 1) ? act1 : act0;
-            dec_hidden_layer<NOB, NKB, SLOTS, (L > 0), Net::kLeaky>(wl, lane, wave, in, out);
+            dec_hidden_layer<NOB, NKB, SLOTS, (L > 0), Net::kLeaky>(wl, lane, wave, in, out, dump);
             lds_barrier();
             u32x4_t nxt[Net::kb(L + 1)][2];
             dec_load_act<Net::kb(L + 1)>(out, lane, nxt);
             // scheduling only: every read of the layer's input is issued before its first MFMA, so
             // the LDS latency is paid once per layer and not once per k-block
             __builtin_amdgcn_sched_barrier(0);
-            rest.run(nxt, lane, wave, act0, act1, headout);
+            rest.run(nxt, lane, wave, act0, act1, headout, dump);
         }
     }
 };
@@ -746,6 +750,7 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
     float* cpbuf = reinterpret_cast<float*>(lds + D::kCpOff);
     uint16_t* ring = reinterpret_cast<uint16_t*>(lds + D::kRingOff);
     int* misc = reinterpret_cast<int*>(lds + D::kMiscOff);            // [0] ticket, [1] abort
+    uint8_t* dump = lds + D::kDumpOff;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     // network role: pixel nl of the tile, k-slot group g
@@ -915,7 +920,7 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
         }
 
         // ---- network, layers meeting in LDS
-        net.run(in1, lane, wave, act0, act1, headout);
+        net.run(in1, lane, wave, act0, act1, headout, dump);
 
         // ---- mixtures: lane j < 3K of pixel q prepares component j % K of channel j / K
         if (j < 3 * K) {
