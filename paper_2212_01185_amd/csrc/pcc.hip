@@ -604,8 +604,8 @@ struct WaveLayer {
 // other (an accumulation chain of MFMAs issues back to back at full rate), so that
 // the activation and split of one block run in the shadow of the next block's MFMAs.
 // A block this wave does not own (ob >= NOB) is computed on a copy of the layer's
-// last block and stored to `dump`: no branch, one scheduling region per layer.
-template <int NOB, int NKB, int SLOTS, bool SPLIT_IN, bool LEAKY>
+// last block (or not at all, SKIP_UNOWNED) and stored to `dump`.
+template <int NOB, int NKB, int SLOTS, bool SPLIT_IN, bool LEAKY, bool SKIP_UNOWNED>
 __device__ __forceinline__ void dec_hidden_layer(const WaveLayer<NOB, NKB, SLOTS>& wl, int lane, int wave,
                                                  const u32x4_t (&in)[NKB][2], uint8_t* __restrict__ act_out,
                                                  uint8_t* __restrict__ dump) {
@@ -623,10 +623,15 @@ __device__ __forceinline__ void dec_hidden_layer(const WaveLayer<NOB, NKB, SLOTS
 #pragma unroll
     for (int s = 0; s < SLOTS; ++s) {
         acc[s] = wl.bias[s];
+        // Two workgroups per CU share the matrix cores: there a wave without this block skips its MFMAs
+        // (`wave` is a scalar, the dump store below still runs).  With one workgroup per CU the pipe is
+        // idle anyway, and a branch here would keep the previous block's split from running under them.
+        if (!SKIP_UNOWNED || 4 * s + 3 < NOB || wave + 4 * s < NOB) {
 #pragma unroll
-        for (int kb = 0; kb < NKB; ++kb) {
-            acc[s] = mfma16(wl.a[s][kb], in[kb][0], acc[s]);
-            if (SPLIT_IN) acc[s] = mfma16(wl.a[s][kb], in[kb][1], acc[s]);
+            for (int kb = 0; kb < NKB; ++kb) {
+                acc[s] = mfma16(wl.a[s][kb], in[kb][0], acc[s]);
+                if (SPLIT_IN) acc[s] = mfma16(wl.a[s][kb], in[kb][1], acc[s]);
+            }
         }
         if (s > 0) finish(s - 1, acc[s - 1]);
     }
@@ -657,6 +662,7 @@ struct WaveNet {
         wl.load(model + Layout<Net>::w_off(L), reinterpret_cast<const float*>(model + Layout<Net>::b_off(L)), lane, wave);
         rest.load(model, lane, wave);
     }
+    template <bool SKIP_UNOWNED>
     __device__ __forceinline__ void run(const u32x4_t (&in)[NKB][2], int lane, int wave, uint8_t* __restrict__ act0,
                                         uint8_t* __restrict__ act1, float* __restrict__ headout,
                                         uint8_t* __restrict__ dump) const {
@@ -675,14 +681,14 @@ struct WaveNet {
             lds_barrier();
         } else {
             uint8_t* out = (L & 1) ? act1 : act0;
-            dec_hidden_layer<NOB, NKB, SLOTS, (L > 0), Net::kLeaky>(wl, lane, wave, in, out, dump);
+            dec_hidden_layer<NOB, NKB, SLOTS, (L > 0), Net::kLeaky, SKIP_UNOWNED>(wl, lane, wave, in, out, dump);
             lds_barrier();
             u32x4_t nxt[Net::kb(L + 1)][2];
             dec_load_act<Net::kb(L + 1)>(out, lane, nxt);
             // scheduling only: every read of the layer's input is issued before its first MFMA, so
             // the LDS latency is paid once per layer and not once per k-block
             __builtin_amdgcn_sched_barrier(0);
-            rest.run(nxt, lane, wave, act0, act1, headout, dump);
+            rest.template run<SKIP_UNOWNED>(nxt, lane, wave, act0, act1, headout, dump);
         }
     }
 };
@@ -752,7 +758,9 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
     int* misc = reinterpret_cast<int*>(lds + D::kMiscOff);            // [0] ticket, [1] abort
     uint8_t* dump = lds + D::kDumpOff;
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63;
+    // a scalar where a branch on it pays (two workgroups per CU); measured slower as a scalar otherwise
+    const int wave = MINBLOCKS > 1 ? __builtin_amdgcn_readfirstlane(tid >> 6) : tid >> 6;
     // network role: pixel nl of the tile, k-slot group g
     const int g = lane >> 4, nl = lane & 15;
     // search role: pixel q of the band, lane j of its group
@@ -920,7 +928,7 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
         }
 
         // ---- network, layers meeting in LDS
-        net.run(in1, lane, wave, act0, act1, headout, dump);
+        net.template run<(MINBLOCKS > 1)>(in1, lane, wave, act0, act1, headout, dump);
 
         // ---- mixtures: lane j < 3K of pixel q prepares component j % K of channel j / K
         if (j < 3 * K) {
