@@ -71,7 +71,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=1, help="workload id 0..4 (1 = 768x512, the headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-rows", type=int, default=48)
+    ap.add_argument("--cpu-rows", type=int, default=256, help="rows of image 0 the oracle baseline codes (about 13 s)")
     ap.add_argument("--network", choices=("workload", "paper", "diagonal"), default="workload")
     ap.add_argument("--image", default=None, help="WxH of one synthetic image instead of a numbered config")
     ap.add_argument("--traffic-probe", action="store_true",
@@ -170,7 +170,10 @@ def main():
             "kernel": "encode_kernel (gather + network on MFMA + mixture CDF, all pixels)",
             "bound": "mfma", "achieved": enc_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
             "frac": enc_tflops / PEAK_BF16_TFLOPS,
-            "traffic": ENCODE_KERNEL_TRAFFIC_768x512 if headline else None,
+            # HBM bytes per launch (fetched + written, rocprofv3 counters scaled by a plain copy's reading)
+            "traffic": (ENCODE_KERNEL_TRAFFIC_768x512["fetch_bytes"] + ENCODE_KERNEL_TRAFFIC_768x512["write_bytes"])
+                       if headline else None,
+            "traffic_detail": ENCODE_KERNEL_TRAFFIC_768x512 if headline else None,
         },
         "roofline_decode": {
             "kernel": "decode_kernel (persistent wavefront)", "bound": "dependency chain",
