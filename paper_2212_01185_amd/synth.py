@@ -199,6 +199,34 @@ def make_paper_blob(seed: int = 0, sharp: bool = False, dist: int = DIST_GAUSSIA
                      act=ACT_LEAKY, dist=dist)
 
 
+def make_predictor_weights(sigma_levels: float = 6.0):
+    """Hand-structured weights of the default shape: every mixture component of channel ch is a Gaussian
+    around the plane prediction left + up - upleft of that channel, with a fixed width of
+    ``sigma_levels`` grey levels; no coupling.  All weights are 0, 1 or -1 (bf16-exact).  Not trained:
+    a stand-in that makes the coder actually compress smooth images, and whose head outputs have a
+    closed form (a pin for gather order, layer chaining and head layout)."""
+    dims = DEFAULT_DIMS
+    k = DEFAULT_K
+    layers = [[np.zeros((o, i), dtype=np.float32), np.zeros(o, dtype=np.float32)] for i, o in zip(dims[:-1], dims[1:])]
+    left, up, upleft = 9, 6, 5                       # neighbour indices in raster order: (0,-1), (-1,0), (-1,-1)
+    for ch in range(3):
+        for sign, unit in ((1.0, 2 * ch), (-1.0, 2 * ch + 1)):    # positive and negative part survive the ReLUs
+            layers[0][0][unit, 3 * left + ch] = sign
+            layers[0][0][unit, 3 * up + ch] = sign
+            layers[0][0][unit, 3 * upleft + ch] = -sign
+            layers[1][0][unit, unit] = 1.0
+            layers[2][0][unit, unit] = 1.0
+        for comp in range(k):
+            layers[3][0][3 * k * ch + k + comp, 2 * ch] = 1.0        # mean = positive part - negative part
+            layers[3][0][3 * k * ch + k + comp, 2 * ch + 1] = -1.0
+            layers[3][1][3 * k * ch + 2 * k + comp] = np.log(sigma_levels / 256.0)
+    return [(w, b) for w, b in layers]
+
+
+def make_predictor_blob(sigma_levels: float = 6.0) -> bytes:
+    return pack_blob(make_predictor_weights(sigma_levels))
+
+
 def make_diagonal_blob(seed: int = 0, sharp: bool = False, dist: int = DIST_GAUSSIAN) -> bytes:
     """The paper's network shape for the diagonal decoding order (Sec. III-C, Eq. (7)): same layers and
     12-pixel input, rows trail by one column (delay 1), three inputs are copies (the coder's business)."""

@@ -82,3 +82,15 @@ def diagonal_sharp_blob():
 def orc_diagonal(diagonal_blob):
     from oracle import pcc_oracle
     return pcc_oracle.Oracle(diagonal_blob)
+
+
+@pytest.fixture(scope="session")
+def predictor_blob():
+    from paper_2212_01185_amd import synth
+    return synth.make_predictor_blob()
+
+
+@pytest.fixture(scope="session")
+def orc_predictor(predictor_blob):
+    from oracle import pcc_oracle
+    return pcc_oracle.Oracle(predictor_blob)

@@ -342,3 +342,41 @@ def test_batch_of_24(codec, orc):
     _log("config 2: round trip")
     _, out = _roundtrip(codec, imgs)
     assert np.array_equal(out, imgs)
+
+
+# ----------------------------------------------------------------- hand-structured weights (closed-form head outputs)
+
+def test_plane_predictor_weights(predictor_blob, orc_predictor):
+    """Weights whose means are exactly left + up - upleft: the GPU reproduces the closed form (the hi + lo
+    activations carry multiples of 1/256 exactly), codes smooth images well below 8 bits per sub-pixel,
+    and agrees with the oracle on the code length."""
+    from paper_2212_01185_amd import binding
+    c = binding.Codec(predictor_blob, 0)
+    try:
+        imgs = np.stack([synth.make_image(s, synth.ImageSpec(96, 80, 6, 6.0, 24.0)) for s in range(2)])
+        n, h, w, _ = imgs.shape
+        params, bits = c.pcc_encode_probs(_dev(imgs))
+        torch.cuda.synchronize()
+        got = params.cpu().numpy().astype(np.float64)
+        pad = np.zeros((n, h + 1, w + 1, 3), dtype=np.int64)
+        pad[:, 1:, 1:] = imgs
+        pred = (pad[:, 1:, :-1] + pad[:, :-1, 1:] - pad[:, :-1, :-1]) / 256.0
+        for ch in range(3):
+            np.testing.assert_array_equal(got[..., 15 * ch:15 * ch + 5], 0.0)
+            for k in range(5):
+                np.testing.assert_array_equal(got[..., 15 * ch + 5 + k], pred[..., ch])
+        np.testing.assert_array_equal(got[..., 45:], 0.0)
+        _, want = orc_predictor.encode(imgs, po.MODE_EXACT)
+        gbits = bits.cpu().numpy().astype(np.float64)
+        bpsp = gbits.sum() / imgs.size
+        _log("plane predictor: %.3f bits per sub-pixel (oracle %.3f)" % (bpsp, want.sum() / imgs.size))
+        assert abs(gbits.sum() / want.sum() - 1) <= BITS_RTOL
+        assert bpsp < 5.5
+        stream, out = _roundtrip(c, imgs)
+        np.testing.assert_array_equal(out, imgs)
+        rows = n * h
+        payload = stream.numel() - (32 + 8 * (rows + 1))               # without header and offsets
+        over = 8.0 * payload - gbits.sum()                             # per row: the 64-bit state, less what it carries
+        assert 32 * rows - 64 <= over <= 96 * rows + 64
+    finally:
+        c.close()

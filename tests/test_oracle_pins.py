@@ -377,6 +377,44 @@ def test_paper_network_roundtrip(orc_paper):
             assert f.min() >= 1 and f.sum() == 65536
 
 
+# ----------------------------------------------------------------- hand-structured weights with a closed form
+
+def test_plane_predictor_weights_have_closed_form_outputs(orc_predictor):
+    """With the plane-predictor weights every mean is exactly (left + up - upleft)/256 of its channel (zero
+    padding outside), every log-sigma log(6/256), every logit and coupling coefficient 0: pins the
+    neighbour order of the gather, the chaining of the four layers and the head layout at once."""
+    rng = np.random.default_rng(51)
+    img = rng.integers(0, 256, size=(7, 9, 3), dtype=np.uint8)
+    pad = np.zeros((8, 10, 3), dtype=np.int64)
+    pad[1:, 1:] = img
+    for r in range(7):
+        for c in range(9):
+            o = orc_predictor.params_at(img, r, c)
+            pred = (pad[r + 1, c] + pad[r, c + 1] - pad[r, c]) / 256.0      # left + up - upleft
+            for ch in range(3):
+                np.testing.assert_array_equal(o[15 * ch:15 * ch + 5], 0.0)
+                np.testing.assert_allclose(o[15 * ch + 5:15 * ch + 10], pred[ch], rtol=0, atol=1e-15)
+                np.testing.assert_allclose(o[15 * ch + 10:15 * ch + 15], np.log(np.float32(6.0 / 256.0)), rtol=0, atol=1e-12)
+            np.testing.assert_array_equal(o[45:], 0.0)
+    # and the pmf is the single discretised Gaussian of Eq. (1) around the prediction
+    from scipy.stats import norm
+    o = orc_predictor.params_at(img, 3, 4)
+    pmf = orc_predictor.pmf(o, 1, 0, 0)
+    mu = 256.0 * o[15 + 5]
+    sig = 256.0 * np.exp(o[15 + 10])
+    edges = np.concatenate([[-np.inf], np.arange(1, 256) - 0.5, [np.inf]])
+    np.testing.assert_allclose(pmf, np.diff(norm.cdf((edges - mu) / sig)), rtol=0, atol=1e-12)
+
+
+def test_plane_predictor_weights_compress_smooth_images(orc_predictor, orc):
+    imgs = synth.make_image(3, synth.ImageSpec(48, 32, 4, 6.0, 20.0))[None]
+    stream, bits = orc_predictor.encode(imgs)
+    np.testing.assert_array_equal(orc_predictor.decode(stream, 1, 32, 48, order=po.ORDER_WAVEFRONT), imgs)
+    bpsp = bits.sum() / imgs.size
+    _, bits_random = orc.encode(imgs)
+    assert bpsp < 5.5 < bits_random.sum() / imgs.size      # noise of sigma 3 under a 4-tap predictor: about 4.7 bits
+
+
 # ----------------------------------------------------------------- diagonal decoding order (Sec. III-C, Eq. (7))
 
 def test_diagonal_pass_count_is_eq7():
