@@ -227,6 +227,27 @@ def make_predictor_blob(sigma_levels: float = 6.0) -> bytes:
     return pack_blob(make_predictor_weights(sigma_levels))
 
 
+PROBE_TAPS = (11, 4, 5)     # of the 12 neighbours in raster order: (0,-1), (-2,+2), (-1,-2)
+
+
+def make_tap_probe_blob(delay: int = PAPER_DELAY) -> bytes:
+    """The paper's network shape with hand-set weights: the mean of component k of channel ch is the
+    value of neighbour PROBE_TAPS[k], channel ch, passed unchanged through the four LeakyReLU layers
+    (inputs are non-negative); logits and coupling 0, sigma 6 grey levels.  Closed-form head outputs
+    that pin the order of the 12 neighbours (delay 3) and the copies of the diagonal order (delay 1)."""
+    dims = PAPER_DIMS
+    layers = [[np.zeros((o, i), dtype=np.float32), np.zeros(o, dtype=np.float32)] for i, o in zip(dims[:-1], dims[1:])]
+    for k, tap in enumerate(PROBE_TAPS):
+        for ch in range(3):
+            unit = 3 * k + ch
+            layers[0][0][unit, 3 * tap + ch] = 1.0
+            for l in (1, 2, 3):
+                layers[l][0][unit, unit] = 1.0
+            layers[4][0][3 * PAPER_K * ch + PAPER_K + k, unit] = 1.0
+            layers[4][1][3 * PAPER_K * ch + 2 * PAPER_K + k] = np.log(6.0 / 256.0)
+    return pack_blob([(w, b) for w, b in layers], k=PAPER_K, nbhd=PAPER_NBHD, delay=delay, act=ACT_LEAKY)
+
+
 def make_diagonal_blob(seed: int = 0, sharp: bool = False, dist: int = DIST_GAUSSIAN) -> bytes:
     """The paper's network shape for the diagonal decoding order (Sec. III-C, Eq. (7)): same layers and
     12-pixel input, rows trail by one column (delay 1), three inputs are copies (the coder's business)."""

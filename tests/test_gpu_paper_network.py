@@ -308,3 +308,36 @@ def test_diagonal_512x512_and_pass_count(codec_diagonal, codec_paper):
     with pytest.raises(binding.PccError) as e:
         codec_diagonal.pcc_decode(s2, 1, 512, 512)
     assert e.value.code == binding.PCC_E_STREAM
+
+
+# ----------------------------------------------------------------- hand-set weights with closed-form head outputs
+
+@pytest.mark.parametrize("delay", [3, 1])
+def test_tap_probe_weights(delay):
+    """Means that are single neighbours' values: pins the 12-neighbour order (and, in the diagonal order, the
+    copied inputs) of the GPU gather and weight packing against a closed form, exactly."""
+    from paper_2212_01185_amd import binding
+    blob = synth.make_tap_probe_blob(delay)
+    c = binding.Codec(blob, 0)
+    try:
+        rng = np.random.default_rng(53)
+        imgs = rng.integers(1, 256, (2, 21, 35, 3), dtype=np.uint8)
+        n, h, w, _ = imgs.shape
+        params, _ = c.pcc_encode_probs(_dev(imgs))
+        torch.cuda.synchronize()
+        got = params.cpu().numpy().astype(np.float64)
+        pad = np.zeros((n, h + 2, w + 4, 3), dtype=np.float64)
+        pad[:, 2:, 2:-2] = imgs / 256.0
+        offsets = [(-2, -2), (-2, -1), (-2, 0), (-2, 1), (-2, 2), (-1, -2), (-1, -1), (-1, 0), (-1, 1), (-1, 2), (0, -2), (0, -1)]
+        for k, tap in enumerate(synth.PROBE_TAPS):
+            dr, dc = offsets[tap]
+            if delay == 1 and dr + dc >= 0:
+                dr, dc = -1, 0
+            want = pad[:, 2 + dr:2 + dr + h, 2 + dc:2 + dc + w]
+            for ch in range(3):
+                np.testing.assert_array_equal(got[..., 9 * ch + 3 + k], want[..., ch], err_msg="tap %d ch %d" % (tap, ch))
+        np.testing.assert_array_equal(got[..., 27:], 0.0)
+        _, out = _roundtrip(c, imgs)
+        np.testing.assert_array_equal(out, imgs)
+    finally:
+        c.close()

@@ -415,6 +415,35 @@ def test_plane_predictor_weights_compress_smooth_images(orc_predictor, orc):
     assert bpsp < 5.5 < bits_random.sum() / imgs.size      # noise of sigma 3 under a 4-tap predictor: about 4.7 bits
 
 
+def _probe_expected(img, r, c, diagonal):
+    """Means [3 channels][3 components] of the tap-probe weights at (r, c): the probed neighbours' values / 256."""
+    h, w, _ = img.shape
+    out = np.zeros((3, 3))
+    for k, tap in enumerate(synth.PROBE_TAPS):
+        dr, dc = OFFSETS12[tap]
+        if diagonal and dr + dc >= 0:
+            dr, dc = -1, 0
+        rr, cc = r + dr, c + dc
+        if 0 <= rr < h and 0 <= cc < w:
+            out[:, k] = img[rr, cc] / 256.0
+    return out
+
+
+@pytest.mark.parametrize("delay", [3, 1])
+def test_tap_probe_weights_have_closed_form_outputs(delay):
+    orc_probe = po.Oracle(synth.make_tap_probe_blob(delay))
+    rng = np.random.default_rng(52)
+    img = rng.integers(1, 256, size=(6, 8, 3), dtype=np.uint8)
+    for r in range(6):
+        for c in range(8):
+            o = orc_probe.params_at(img, r, c)
+            want = _probe_expected(img, r, c, delay == 1)
+            for ch in range(3):
+                np.testing.assert_array_equal(o[9 * ch:9 * ch + 3], 0.0)
+                np.testing.assert_array_equal(o[9 * ch + 3:9 * ch + 6], want[ch])
+            np.testing.assert_array_equal(o[27:], 0.0)
+
+
 # ----------------------------------------------------------------- diagonal decoding order (Sec. III-C, Eq. (7))
 
 def test_diagonal_pass_count_is_eq7():
