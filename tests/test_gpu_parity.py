@@ -380,3 +380,16 @@ def test_plane_predictor_weights(predictor_blob, orc_predictor):
         assert 32 * rows - 64 <= over <= 96 * rows + 64
     finally:
         c.close()
+
+
+def test_roundtrip_extreme_aspect_ratios(codec, codec_sharp):
+    """One very wide image (hundreds of coder chunks per row, a single band) and one very tall one (dozens of
+    bands, rows shorter than the neighbourhood's reach plus the fetch lag)."""
+    rng = np.random.default_rng(16)
+    wide = synth.make_image(9, synth.ImageSpec(4100, 3, 40, 8.0, 64.0))[None]
+    tall = rng.integers(0, 256, (1, 700, 5, 3), dtype=np.uint8)
+    for name, imgs in (("3x4100", wide), ("700x5", tall)):
+        for which, c in (("default", codec), ("sharp", codec_sharp)):
+            _log("roundtrip %s %s" % (name, which))
+            _, out = _roundtrip(c, imgs)
+            np.testing.assert_array_equal(out, imgs, err_msg="%s %s" % (name, which))
