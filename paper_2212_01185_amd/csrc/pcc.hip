@@ -462,13 +462,17 @@ struct DecLds {
     static constexpr int kLutOff = 0;
     static constexpr int kAct0Off = (kLutEntries + 1) * 8;
     static constexpr int kAct1Off = kAct0Off + kActBytes;
-    static constexpr int kHeadOff = kAct1Off + kActBytes;              // [16 pixels][4 groups][kHS] fp32, (group, register) layout
-    static constexpr int kCpOff = kHeadOff + 16 * 4 * kHS * 4;         // [16 pixels][3 channels][16] fp32: pi[K], mu[K], a[K], pad
+    // Strides in floats, padded by one 16-byte vector: consecutive pixels (and channels) then start
+    // four LDS banks apart instead of on the same bank.
+    static constexpr int kHeadStride = 4 * kHS + 4;                    // head outputs of one pixel: [4 groups][kHS]
+    static constexpr int kCpStride = 20;                               // mixture of one (pixel, channel): pi[K], mu[K], a[K]
+    static constexpr int kHeadOff = kAct1Off + kActBytes;              // [16 pixels][kHeadStride] fp32, (group, register) layout
+    static constexpr int kCpOff = kHeadOff + 16 * kHeadStride * 4;     // [16 pixels][3 channels][kCpStride] fp32
     // Ring of recently decoded pixels as first-layer inputs: [18 rows][2 * kRingCols columns][3] bf16.
     // Rows 0,1 are the two rows above the band.  Column c lives at slots c mod kRingCols and
     // that + kRingCols, so the values of a run of neighbour columns are always contiguous.
     static constexpr int kRingRowElems = 2 * Net::kRingCols * 3;
-    static constexpr int kRingOff = kCpOff + 16 * 3 * 16 * 4;
+    static constexpr int kRingOff = kCpOff + 16 * 3 * kCpStride * 4;
     static constexpr int kMiscOff = kRingOff + 18 * kRingRowElems * 2; // ticket, abort flag
     static constexpr int kDumpOff = (kMiscOff + 64 + 15) / 16 * 16;    // 2 KB nobody reads: stores of out-blocks a wave does not own
     static constexpr int kBytes = kDumpOff + 2 * 64 * 16;
@@ -677,7 +681,7 @@ struct WaveNet {
             // registers s = 4 wave + i of group g, kept in (group, register) order
             constexpr int HS = Layout<Net>::kHeadSlots;
             if (wave < NOB)
-                *reinterpret_cast<f32x4_t*>(headout + (lane & 15) * (4 * HS) + (lane >> 4) * HS + 4 * wave) = acc;
+                *reinterpret_cast<f32x4_t*>(headout + (lane & 15) * DecLds<Net>::kHeadStride + (lane >> 4) * HS + 4 * wave) = acc;
             lds_barrier();
         } else {
             uint8_t* out = (L & 1) ? act1 : act0;
@@ -934,13 +938,13 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
         if (j < 3 * K) {
             const int ch = j / K, k = j - K * ch;
             float raw[3 * K];
-            lds_read_floats<3 * K>(headout + q * (4 * HS) + ch * HS, raw);
+            lds_read_floats<3 * K>(headout + q * D::kHeadStride + ch * HS, raw);
             ChanParams<K> all;
             channel_setup<K>(raw, lut_scale, all);
             float pk = all.pi[0], mk = all.mu[0], ak = all.a[0];
 #pragma unroll
             for (int kk = 1; kk < K; ++kk) if (k == kk) { pk = all.pi[kk]; mk = all.mu[kk]; ak = all.a[kk]; }
-            float* dst = cpbuf + (q * 3 + ch) * 16 + k;
+            float* dst = cpbuf + (q * 3 + ch) * D::kCpStride + k;
             dst[0] = pk; dst[K] = mk; dst[2 * K] = ak;
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
@@ -953,14 +957,14 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
         {
             auto load_cp = [&](int ch, ChanParams<K>& cp) {
                 float v[3 * K];
-                lds_read_floats<3 * K>(cpbuf + (q * 3 + ch) * 16, v);
+                lds_read_floats<3 * K>(cpbuf + (q * 3 + ch) * D::kCpStride, v);
 #pragma unroll
                 for (int k = 0; k < K; ++k) { cp.pi[k] = v[k]; cp.mu[k] = v[K + k]; cp.a[k] = v[2 * K + k]; }
             };
             load_cp(0, cpr); load_cp(1, cpg); load_cp(2, cpb);
             // coupling coefficients: canonical head outputs 9K.. (alpha), 10K.. (beta), 11K.. (gamma), wherever
             // the head's (group, register) layout put them
-            const float* hq = headout + q * (4 * HS);
+            const float* hq = headout + q * D::kHeadStride;
             float g3[HS];                           // group 3 holds most of them: whole vector reads
             lds_read_floats<HS>(hq + 3 * HS, g3);
             static_for<0, K>([&](auto kc) {
