@@ -471,7 +471,8 @@ struct DecLds {
     // Ring of recently decoded pixels as first-layer inputs: [18 rows][2 * kRingCols columns][3] bf16.
     // Rows 0,1 are the two rows above the band.  Column c lives at slots c mod kRingCols and
     // that + kRingCols, so the values of a run of neighbour columns are always contiguous.
-    static constexpr int kRingRowElems = 2 * Net::kRingCols * 3;
+    // The pad keeps the 16 rows of a gather off each other's LDS banks; which pad is fastest was measured per network.
+    static constexpr int kRingRowElems = 2 * Net::kRingCols * 3 + Net::kRingPad;
     static constexpr int kRingOff = kCpOff + 16 * 3 * kCpStride * 4;
     static constexpr int kMiscOff = kRingOff + 18 * kRingRowElems * 2; // ticket, abort flag
     static constexpr int kDumpOff = (kMiscOff + 64 + 15) / 16 * 16;    // 2 KB nobody reads: stores of out-blocks a wave does not own

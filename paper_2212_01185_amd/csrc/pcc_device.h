@@ -49,6 +49,7 @@ struct NetWorkload {
     static constexpr int kReach1 = 1, kReach2 = 1;   // columns right of c that rows r-1 and r-2 are read at
     static constexpr int kUpBytes = 12;       // bytes of one upper row's neighbours (columns c-2..c+1)
     static constexpr int kRingCols = 8;       // decoder ring columns (power of two)
+    static constexpr int kRingPad = 2;        // extra 16-bit elements per ring row
     static constexpr bool kLeaky = false;
     __host__ __device__ static constexpr int dim(int l) { return l == 0 ? 30 : l == 1 ? 160 : l == 2 ? 160 : l == 3 ? 128 : 60; }
     __host__ __device__ static constexpr int ob(int l) { return l == 0 ? 10 : l == 1 ? 10 : l == 2 ? 8 : 4; }
@@ -82,6 +83,7 @@ struct NetPaper {
     static constexpr int kReach1 = 2, kReach2 = 2;
     static constexpr int kUpBytes = 15;
     static constexpr int kRingCols = 16;
+    static constexpr int kRingPad = 4;
     static constexpr bool kLeaky = true;
     __host__ __device__ static constexpr int dim(int l) { return l == 0 ? 36 : l == 5 ? 36 : 128; }
     __host__ __device__ static constexpr int ob(int l) { return l == 4 ? 3 : 8; }
@@ -108,6 +110,7 @@ struct NetDiagonal : NetPaper {
     static constexpr int kDelay = 1;
     static constexpr int kReach1 = 0, kReach2 = 1;   // row r-1 is read up to column c, row r-2 up to c+1
     static constexpr int kRingCols = 8;
+    static constexpr int kRingPad = 4;
     __host__ __device__ static constexpr bool run_desc(int kbi, int g, int half, int& dr, int& off) {
         if (kbi == 0) {
             if (g == 0) { dr = -2; off = 4 * half; }                          // row r-2, bytes 0..7
