@@ -938,13 +938,23 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
         // ---- mixtures: lane j < 3K of pixel q prepares component j % K of channel j / K
         if (j < 3 * K) {
             const int ch = j / K, k = j - K * ch;
-            float raw[3 * K];
-            lds_read_floats<3 * K>(headout + q * D::kHeadStride + ch * HS, raw);
-            ChanParams<K> all;
-            channel_setup<K>(raw, lut_scale, all);
-            float pk = all.pi[0], mk = all.mu[0], ak = all.a[0];
+            const float* hc = headout + q * D::kHeadStride + ch * HS;
+            float pk, mk, ak;
+            if constexpr (K >= 5) {
+                // only this component's sigma and weight are computed (measured faster for K = 5, slower for K = 3)
+                float logits[K];
+                lds_read_floats<K>(hc, logits);                       // the channel's logits (for the softmax sum) ...
+                const float logit_k = hc[k], mu_k = hc[K + k], ls_k = hc[2 * K + k];   // ... and this component's own three values
+                channel_setup_one<K>(logits, logit_k, mu_k, ls_k, lut_scale, pk, mk, ak);
+            } else {
+                float raw[3 * K];
+                lds_read_floats<3 * K>(hc, raw);
+                ChanParams<K> all;
+                channel_setup<K>(raw, lut_scale, all);
+                pk = all.pi[0]; mk = all.mu[0]; ak = all.a[0];
 #pragma unroll
-            for (int kk = 1; kk < K; ++kk) if (k == kk) { pk = all.pi[kk]; mk = all.mu[kk]; ak = all.a[kk]; }
+                for (int kk = 1; kk < K; ++kk) if (k == kk) { pk = all.pi[kk]; mk = all.mu[kk]; ak = all.a[kk]; }
+            }
             float* dst = cpbuf + (q * 3 + ch) * D::kCpStride + k;
             dst[0] = pk; dst[K] = mk; dst[2 * K] = ak;
         }

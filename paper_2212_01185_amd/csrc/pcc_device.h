@@ -392,6 +392,28 @@ __device__ __forceinline__ void channel_setup(const float (&raw)[3 * K], float l
     }
 }
 
+// One component of channel_setup: the same operations on the same inputs in the same order,
+// so pi, mu, a equal cp.pi[k], cp.mu[k], cp.a[k] bit for bit.  logits[0..K) are the channel's
+// logits; logit_k, mu_k, ls_k the component's own three head outputs.
+template <int K>
+__device__ __forceinline__ void channel_setup_one(const float (&logits)[K], float logit_k, float mu_k, float ls_k,
+                                                  float lut_scale, float& pi, float& mu, float& a) {
+    float m = logits[0];
+#pragma unroll
+    for (int k = 1; k < K; ++k) m = fmaxf(m, logits[k]);
+    float e[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) e[k] = __builtin_amdgcn_exp2f((logits[k] - m) * kLog2e);
+    float sum = e[0];
+#pragma unroll
+    for (int k = 1; k < K; ++k) sum = sum + e[k];
+    const float inv = __builtin_amdgcn_rcpf(sum);
+    pi = __builtin_amdgcn_exp2f((logit_k - m) * kLog2e) * inv;
+    mu = mu_k;
+    const float ls = fminf(fmaxf(ls_k, -8.0f), 4.0f);
+    a = __builtin_amdgcn_exp2f(-(ls * kLog2e)) * lut_scale;
+}
+
 // Eq. (3): mu_g += alpha * r/256.   Eq. (4): mu_b += beta * r/256 + gamma * g/256.
 template <int K>
 __device__ __forceinline__ void couple_green(ChanParams<K>& cp, const float (&alpha)[K], float rhat) {
