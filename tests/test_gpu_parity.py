@@ -393,3 +393,25 @@ def test_roundtrip_extreme_aspect_ratios(codec, codec_sharp):
             _log("roundtrip %s %s" % (name, which))
             _, out = _roundtrip(c, imgs)
             np.testing.assert_array_equal(out, imgs, err_msg="%s %s" % (name, which))
+
+
+def test_roundtrip_random_shapes(codec, codec_sharp, paper_blob, diagonal_blob):
+    """A seeded sweep of small shapes (widths and heights around the tile, band, ring and chunk sizes) through
+    every model: each must round-trip exactly."""
+    from paper_2212_01185_amd import binding
+    rng = np.random.default_rng(17)
+    shapes = [(int(rng.integers(1, 4)), int(rng.integers(1, 70)), int(rng.integers(1, 90))) for _ in range(20)]
+    shapes += [(1, 16, 8), (1, 17, 9), (1, 32, 11), (1, 33, 10), (2, 15, 16), (1, 48, 32), (1, 2, 64), (1, 31, 1)]
+    extra = [binding.Codec(paper_blob, 0), binding.Codec(diagonal_blob, 0)]
+    try:
+        for n, h, w in shapes:
+            imgs = rng.integers(0, 256, (n, h, w, 3), dtype=np.uint8)
+            if (n + h + w) % 3 == 0:          # some smooth ones: long runs of equal symbols
+                imgs = (imgs // 64 * 64).astype(np.uint8)
+            for which, c in (("default", codec), ("sharp", codec_sharp), ("paper", extra[0]), ("diagonal", extra[1])):
+                _log("random shape %dx%dx%d %s" % (n, h, w, which))
+                _, out = _roundtrip(c, imgs)
+                np.testing.assert_array_equal(out, imgs, err_msg="%dx%dx%d %s" % (n, h, w, which))
+    finally:
+        for c in extra:
+            c.close()
