@@ -2,9 +2,11 @@
 //
 // Kernels (templated on the network description, see pcc_device.h)
 //   encode_kernel      gather + network (MFMA) + mixture -> (start,freq) of the
-//                      true sub-pixels, all pixels in parallel
+//                      true sub-pixels, all pixels in parallel, the rows' right
+//                      ends first
 //   rans_rows_kernel   one lane per image row: push the row's symbols last to
-//                      first into a per-row slab, written backwards
+//                      first into a per-row slab, written backwards; for a small
+//                      job it runs beside encode_kernel and follows its progress
 //   scan_kernel        exclusive prefix sum of row payload sizes, header, offsets
 //   compact_kernel     slabs -> contiguous stream
 //   decode_kernel      persistent wavefront decoder: one workgroup (4 waves) per
@@ -126,11 +128,21 @@ __device__ __forceinline__ void lane_head_setup(const f32x4_t (&o)[Layout<Net>::
 
 // ---------------------------------------------------------------------------
 // encode: all pixels in parallel
+//
+// A work item is a strip of 16 T consecutive pixels of one image row; strips are
+// numbered from the right edge of the image, item = strip * rows + row, and wave
+// w of the grid's G waves takes the items w, w + G, w + 2G, ...  The rows' right
+// ends are therefore finished first, which is where the row coder starts (it
+// pushes the symbols last to first).  The row coder may run beside this kernel:
+// then progress[w] = epoch << 32 | number of items wave w has finished (the epoch
+// tells this launch's words from an earlier launch's, so nothing has to clear them),
+// and the row coder works out from those which of its rows' strips are complete.
 // ---------------------------------------------------------------------------
 template <class Net, int T, int THREADS>
 __global__ void __launch_bounds__(THREADS)
-encode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ img, int H, int W, uint32_t P,
-              uint32_t* __restrict__ sf, float* __restrict__ params, float* __restrict__ bits, int* status) {
+encode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ img, int n, int H, int W,
+              uint32_t* __restrict__ sf, float* __restrict__ params, float* __restrict__ bits, int* status,
+              uint64_t* progress, uint32_t epoch) {
     using Lay = Layout<Net>;
     constexpr int K = Net::K, KB0 = Net::kb(0), HEAD = Net::dim(Net::kLayers);
     extern __shared__ __align__(16) uint8_t lds[];
@@ -138,26 +150,44 @@ encode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ img
     __syncthreads();
     const float2* lut = reinterpret_cast<const float2*>(lds + Lay::kLutOff);
     const float lut_scale = *reinterpret_cast<const float*>(lds + Lay::kLutScaleOff);
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
+    const int lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // a scalar: the item's row and strip are scalars too
     const int g = lane >> 4, nl = lane & 15;
-    const uint32_t groups = (P + 16 * T - 1) / (16 * T);
+    const uint32_t rows = (uint32_t)n * (uint32_t)H;
+    const uint32_t P = rows * (uint32_t)W;
+    const uint32_t nstrips = ((uint32_t)W + 16 * T - 1) / (16 * T);
+    const uint32_t items = nstrips * rows;
+    // The stores of an item are published an item later, when they have long completed.  With a follower the
+    // results are written through to device scope (relaxed atomic stores), so that all the publishing wave has
+    // to do is wait for its own stores (a release fence would write back the whole L2 once per item), and a wave
+    // publishes into a word of its own (counters shared by all waves cost more than the row coder saves).
+    uint32_t finished = 0;
+    auto publish = [&]() {
+        if (progress != nullptr && finished != 0) {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            if (lane == 0)
+                __hip_atomic_store(&progress[blockIdx.x * nwaves + wave], ((uint64_t)epoch << 32) | finished, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+        }
+    };
 
-    for (uint32_t grp = blockIdx.x * nwaves + wave; grp < groups; grp += gridDim.x * nwaves) {
+    for (uint32_t item = blockIdx.x * nwaves + wave; item < items; item += gridDim.x * nwaves) {
+        const uint32_t strip = item / rows, rowg = item - strip * rows;
+        const uint32_t im = rowg / (uint32_t)H;
+        const int r = (int)(rowg - im * (uint32_t)H);
+        const int c0 = W - 16 * T * (int)(strip + 1);           // negative in the leftmost strip of a ragged width
+        const uint8_t* base = img + (size_t)im * H * W * 3;
         u32x4_t in[T][KB0][2];
         uint32_t pix[T];   // the pixel's own bytes r | g<<8 | b<<16
 #pragma unroll
         for (int t = 0; t < T; ++t) {
-            const uint32_t p = grp * (16 * T) + 16 * t + nl;
+            const int c = c0 + 16 * t + nl;
             uint32_t runs[KB0][2];
 #pragma unroll
             for (int kbi = 0; kbi < KB0; ++kbi) { runs[kbi][0] = 0; runs[kbi][1] = 0; }
             pix[t] = 0;
-            if (p < P) {
-                const uint32_t rowg = p / (uint32_t)W;
-                const int c = (int)(p - rowg * (uint32_t)W);
-                const uint32_t im = rowg / (uint32_t)H;
-                const int r = (int)(rowg - im * (uint32_t)H);
-                const uint8_t* base = img + (size_t)im * H * W * 3;
+            if (c >= 0) {
+                const uint32_t p = rowg * (uint32_t)W + (uint32_t)c;
                 const int me = (r * W + c) * 3;
                 if (p + 1 < P) {
                     uint32_t v;
@@ -200,14 +230,16 @@ encode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ img
                 in[t][kbi][1] = in[t][kbi][0];   // unused (layer-1 inputs are exact)
             }
         }
+        publish();
 
         f32x4_t out[T][Lay::kHeadOB];
         mlp_from<Net, T, (T == 1 && THREADS <= 512), 0>(lds + opaque_zero(), lane, in, out);
 
 #pragma unroll
         for (int t = 0; t < T; ++t) {
-            const uint32_t p = grp * (16 * T) + 16 * t + nl;
-            const bool live = p < P;
+            const int c = c0 + 16 * t + nl;
+            const bool live = c >= 0;
+            const uint32_t p = rowg * (uint32_t)W + (uint32_t)c;
             if (params != nullptr && live) {
 #pragma unroll
                 for (int ob = 0; ob < Lay::kHeadOB; ++ob) {
@@ -230,14 +262,20 @@ encode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ img
             const uint32_t hi = cq_full<K>(h.cp, x + 1, lut);
             uint32_t freq = hi - lo;
             if (g < 3 && live && (hi <= lo || freq > 65536u)) { set_error(status, PCC_E_INTERNAL); freq = 1; }
-            if (sf != nullptr && g < 3 && live) sf[(size_t)p * 3 + g] = lo | ((freq - 1u) << 16);
+            if (sf != nullptr && g < 3 && live) {
+                const uint32_t word = lo | ((freq - 1u) << 16);
+                if (progress != nullptr) __hip_atomic_store(&sf[(size_t)p * 3 + g], word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                else sf[(size_t)p * 3 + g] = word;
+            }
             if (bits != nullptr) {
                 const float mine = 16.0f - __builtin_amdgcn_logf((float)freq);
                 const float tot = (__shfl(mine, nl) + __shfl(mine, nl + 16)) + __shfl(mine, nl + 32);
                 if (g == 0 && live) bits[p] = tot;
             }
         }
+        ++finished;
     }
+    publish();
 }
 
 // ---------------------------------------------------------------------------
@@ -250,6 +288,10 @@ encode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ img
 constexpr int kRansRows = 64;
 constexpr int kRansChunk = 32;
 constexpr int kRansThreads = 256;
+constexpr uint32_t kRansBesideMaxGroups = 48;      // row-coder workgroups that may run beside the pixel kernel
+constexpr uint32_t kXcds = 8;
+constexpr uint32_t kMaxCus = 256, kProgressBytes = kMaxCus * 16 * 8;   // a progress word per wave of the pixel kernel
+constexpr uint32_t kRansSpinLimit = 1u << 22;       // polls of a progress counter before the row coder gives up (seconds)
 // Padding symbol (start 0, frequency 2^16): pushing it leaves the state unchanged
 // and never renormalises, so every chunk can be coded as a full one.
 constexpr uint32_t kRansNop = 0xFFFF0000u;
@@ -280,9 +322,21 @@ __device__ __forceinline__ void rans_push(uint64_t& x, uint32_t f, uint32_t star
     x = (q << 16) + (uint64_t)((uint32_t)rem + start);
 }
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for
+// every outstanding global access (stores, polls, prefetches), which would put
+// memory latency on the critical path of every round of the row coder and several
+// times on every step of the decoder; neither hands global data from thread to
+// thread across such a barrier.
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 __global__ void __launch_bounds__(kRansThreads)
 rans_rows_kernel(const uint32_t* __restrict__ sf, int W, uint32_t rows, uint32_t* __restrict__ slabs,
-                 uint32_t* __restrict__ row_words) {
+                 uint32_t* __restrict__ row_words, const uint64_t* progress, uint32_t epoch, uint32_t pixel_waves,
+                 uint32_t strip_cols, int* status, uint32_t spin_limit) {
     // [buffer][row][symbol of the chunk]; the odd row strides keep the coding wave's column accesses off shared banks
     __shared__ uint32_t sym[2][kRansRows][kRansChunk + 1];
     __shared__ double rcp[2][kRansRows][kRansChunk + 1];
@@ -302,23 +356,74 @@ rans_rows_kernel(const uint32_t* __restrict__ sf, int W, uint32_t rows, uint32_t
 
     constexpr int kFeeders = kRansThreads - 64;
     constexpr int kPerFeeder = (kRansRows * kRansChunk + kFeeders - 1) / kFeeders;
-    // waves 1-3: chunk k of all 64 rows into buffer b.  All of a thread's loads are issued before the first is used.
-    auto produce = [&](int k, int b) {
-        uint32_t v[kPerFeeder];
+    // Waves 1-3 feed the coding wave through a pipeline, one stage per round (a round = the coding wave codes a
+    // chunk; rounds end in a workgroup barrier), so that no feeder waits for memory inside a round:
+    //   round k + 4  the progress words for chunk k are requested          (only beside a running pixel kernel)
+    //   round k + 3  ... and waited for
+    //   round k + 2  the chunk's symbols are requested from global memory into registers
+    //   round k + 1  reciprocals are computed, symbols and reciprocals go to LDS buffer k & 1
+    //   round k      the coding wave codes the chunk
+    //   round k - 1  the words it produced are copied to the rows' slabs
+    //
+    // The pixel kernel may run beside this one (progress != nullptr); it finishes the image strip by strip from
+    // the right edge.  Item strip * rows + row of the pixel kernel is the (item / G + 1)-th item of its wave
+    // item % G: the first feeder wave follows, one lane per row, the progress words of the waves that own this
+    // workgroup's rows of a strip.  A barrier lies between that wait and the loads of the chunk, and the loads
+    // bypass the caches that are not coherent with the pixel kernel's stores.
+    const bool follower = progress != nullptr && tid < 128 && (uint32_t)(tid - 64) < live_rows;
+    uint32_t strips_asked = 0;          // strips [0, strips_asked) have been waited for or are being waited for
+    uint32_t wait_first = 0, wait_end = 0;   // the strips the next wait covers
+    uint64_t seen = 0;                  // the progress word of strip wait_first, requested a round ahead
+    auto progress_slot = [&](uint32_t s, uint64_t& need) {
+        const uint32_t item = s * rows + row0 + (uint32_t)(tid - 64);
+        need = ((uint64_t)epoch << 32) | (item / pixel_waves + 1u);   // epochs only grow
+        return item % pixel_waves;
+    };
+    auto ask_for_chunk = [&](int k) {
+        const uint32_t s_hi = ((uint32_t)W - 1u - ((uint32_t)k * kRansChunk) / 3u) / strip_cols;
+        if (!follower || s_hi < strips_asked) return;
+        wait_first = strips_asked;
+        wait_end = s_hi + 1u;
+        strips_asked = wait_end;
+        uint64_t need;
+        seen = __hip_atomic_load(&progress[progress_slot(wait_first, need)], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    };
+    auto wait_for_asked = [&]() {
+        for (uint32_t s = wait_first; s < wait_end; ++s) {
+            uint64_t need;
+            const uint32_t w = progress_slot(s, need);
+            uint32_t spins = 0;
+            uint64_t have = s == wait_first ? seen : 0;
+            while (have < need) {
+                if (++spins > spin_limit) { set_error(status, PCC_E_INTERNAL); break; }
+                __builtin_amdgcn_s_sleep(4);
+                have = __hip_atomic_load(&progress[w], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+        wait_first = wait_end;
+    };
+    uint32_t staged[kPerFeeder];
+    auto request = [&](int k) {
 #pragma unroll
         for (int it = 0; it < kPerFeeder; ++it) {
             const int e = tid - 64 + it * kFeeders;
             const uint32_t r = (uint32_t)e / kRansChunk, i = (uint32_t)e % kRansChunk;
             const uint32_t idx = (uint32_t)k * kRansChunk + i;
-            v[it] = (r < live_rows && idx < nsym) ? sf[(size_t)(row0 + r) * nsym + idx] : kRansNop;   // r >= 64 fails r < live_rows
+            const size_t at = (size_t)(row0 + r) * nsym + idx;
+            uint32_t v = kRansNop;
+            if (r < live_rows && idx < nsym)   // r >= 64 fails r < live_rows
+                v = progress != nullptr ? __hip_atomic_load(&sf[at], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : sf[at];
+            staged[it] = v;
         }
+    };
+    auto deposit = [&](int b) {
 #pragma unroll
         for (int it = 0; it < kPerFeeder; ++it) {
             const int e = tid - 64 + it * kFeeders;
             if (e < kRansRows * kRansChunk) {
                 const uint32_t r = (uint32_t)e / kRansChunk, i = (uint32_t)e % kRansChunk;
-                sym[b][r][i] = v[it];
-                rcp[b][r][i] = rans_recip((v[it] >> 16) + 1u);
+                sym[b][r][i] = staged[it];
+                rcp[b][r][i] = rans_recip((staged[it] >> 16) + 1u);
             }
         }
     };
@@ -332,14 +437,15 @@ rans_rows_kernel(const uint32_t* __restrict__ sf, int W, uint32_t rows, uint32_t
                 slabs[(size_t)(row0 + r) * sw + (outpos[b][r] - 1u - i)] = outw[b][r][i];
         }
     };
-    if (!coder) produce(nchunks - 1, (nchunks - 1) & 1);
-    __syncthreads();
-    for (int k = nchunks - 1; k >= 0; --k) {
+    for (int k = nchunks + 3; k >= 0; --k) {
         const int b = k & 1;
         if (!coder) {
-            if (k + 1 < nchunks) flush(b ^ 1);           // what the coding wave produced in the previous chunk
-            if (k > 0) produce(k - 1, b ^ 1);
-        } else {
+            if (k >= 1 && k - 1 < nchunks) deposit(b ^ 1);
+            if (k >= 2 && k - 2 < nchunks) request(k - 2);
+            if (k + 1 < nchunks) flush(b ^ 1);
+            if (k >= 3 && k - 3 < nchunks) wait_for_asked();
+            if (k >= 4 && k - 4 < nchunks) ask_for_chunk(k - 4);
+        } else if (k < nchunks) {
             uint32_t cnt = 0;
             constexpr int kU = 8;   // symbols fetched from LDS side by side
             for (int i0 = kRansChunk; i0 > 0; i0 -= kU) {
@@ -368,7 +474,7 @@ rans_rows_kernel(const uint32_t* __restrict__ sf, int W, uint32_t rows, uint32_t
             outpos[b][lane] = wp;
             wp -= cnt;
         }
-        __syncthreads();
+        lds_barrier();   // all that crosses threads here is in LDS; a feeder's global loads stay in flight
     }
     if (!coder) flush(0);                                // chunk 0 lives in buffer 0
     if (coder && row < rows) {
@@ -572,16 +678,6 @@ __device__ __forceinline__ void reader_refill(RowReader& rd, int j) {
         asm volatile("" : "+v"(rd.cur));
         rd.nxt = reader_word(rd, 16u * (rd.blk + 1u) + (uint32_t)j);
     }
-}
-
-// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for
-// every outstanding global access (pixel stores, mailbox traffic, stream-word and
-// mailbox prefetches), which would put HBM latency on the step's critical path
-// several times per step; nothing here hands global data from thread to thread.
-__device__ __forceinline__ void lds_barrier() {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
 // This wave's weight slices of one layer: out-blocks ob = wave + 4 s.  Where the
@@ -1095,6 +1191,11 @@ struct pcc_ctx {
     int num_cus = 0;
     uint32_t dist = 0;             // written to / checked against stream header word 6
     int encode_variant = kDefaultEncodeVariant;
+    // the row coder of a small job runs beside the pixel kernel, on a stream of its own
+    bool overlap = true;
+    hipStream_t side = nullptr;
+    uint64_t* d_progress = nullptr;   // kProgressBytes, zero at creation
+    uint32_t epoch = 0;               // of the last launch that used d_progress
     // optional per-kernel timing
     bool profiling = false;
     hipEvent_t ev[2 * PCC_N_TIMINGS] = {};
@@ -1275,41 +1376,48 @@ bool set_kernel_attributes() {
     return ok;
 }
 
+// Workgroups of the pixel kernel.  reserve_cus: compute units left free for a kernel that runs beside it.
+uint32_t encode_blocks(const pcc_ctx* ctx, int n, int H, int W, uint32_t reserve_cus) {
+    const EncodeVariant ev = kEncodeVariants[ctx->encode_variant];
+    const uint64_t strips = ((uint64_t)W + 16u * ev.tiles - 1) / (16u * ev.tiles);
+    const uint64_t items = strips * (uint64_t)n * H;          // dims_ok: below 2^31
+    const uint32_t per_block = ev.threads / 64;
+    const uint64_t blocks = (items + per_block - 1) / per_block;
+    const uint32_t cus = (ctx->num_cus > 0 ? (uint32_t)ctx->num_cus : 256u) - reserve_cus;
+    return blocks > cus ? cus : (uint32_t)blocks;   // persistent: one workgroup per CU, looping over the items
+}
+
+// progress: see encode_kernel; one word per wave of the grid
 template <class Net>
 int launch_encode(pcc_ctx* ctx, const uint8_t* d_img, int n, int H, int W, uint32_t* sf, float* params, float* bits,
-                  hipStream_t st) {
+                  uint64_t* progress, uint32_t reserve_cus, hipStream_t st) {
     constexpr int kLds = Layout<Net>::kModelBytes;
-    const uint32_t P = (uint32_t)((uint64_t)n * H * W);
-    const EncodeVariant ev = kEncodeVariants[ctx->encode_variant];
-    const uint32_t per_block = 16u * ev.tiles * (ev.threads / 64);
-    uint32_t blocks = (P + per_block - 1) / per_block;
-    const uint32_t cus = ctx->num_cus > 0 ? (uint32_t)ctx->num_cus : 256u;
-    if (blocks > cus) blocks = cus;   // persistent: one workgroup per CU, looping over pixel groups
+    const uint32_t blocks = encode_blocks(ctx, n, H, W, reserve_cus);
     switch (ctx->encode_variant) {
         case 0:
-            hipLaunchKernelGGL((encode_kernel<Net, 1, 512>), dim3(blocks), dim3(512), kLds, st, ctx->d_model, d_img, H, W, P,
-                               sf, params, bits, ctx->d_status);
+            hipLaunchKernelGGL((encode_kernel<Net, 1, 512>), dim3(blocks), dim3(512), kLds, st, ctx->d_model, d_img, n, H, W,
+                               sf, params, bits, ctx->d_status, progress, ctx->epoch);
             break;
         case 1:
-            hipLaunchKernelGGL((encode_kernel<Net, 2, 512>), dim3(blocks), dim3(512), kLds, st, ctx->d_model, d_img, H, W, P,
-                               sf, params, bits, ctx->d_status);
+            hipLaunchKernelGGL((encode_kernel<Net, 2, 512>), dim3(blocks), dim3(512), kLds, st, ctx->d_model, d_img, n, H, W,
+                               sf, params, bits, ctx->d_status, progress, ctx->epoch);
             break;
         case 2:
-            hipLaunchKernelGGL((encode_kernel<Net, 1, 1024>), dim3(blocks), dim3(1024), kLds, st, ctx->d_model, d_img, H, W,
-                               P, sf, params, bits, ctx->d_status);
+            hipLaunchKernelGGL((encode_kernel<Net, 1, 1024>), dim3(blocks), dim3(1024), kLds, st, ctx->d_model, d_img, n, H, W,
+                               sf, params, bits, ctx->d_status, progress, ctx->epoch);
             break;
         default:
-            hipLaunchKernelGGL((encode_kernel<Net, 4, 256>), dim3(blocks), dim3(256), kLds, st, ctx->d_model, d_img, H, W, P,
-                               sf, params, bits, ctx->d_status);
+            hipLaunchKernelGGL((encode_kernel<Net, 4, 256>), dim3(blocks), dim3(256), kLds, st, ctx->d_model, d_img, n, H, W,
+                               sf, params, bits, ctx->d_status, progress, ctx->epoch);
             break;
     }
     return hipGetLastError() == hipSuccess ? PCC_OK : PCC_E_HIP;
 }
 
 int launch_encode_any(pcc_ctx* ctx, const uint8_t* d_img, int n, int H, int W, uint32_t* sf, float* params, float* bits,
-                      hipStream_t st) {
+                      uint64_t* progress, uint32_t reserve_cus, hipStream_t st) {
     return with_net(ctx->net, [&](auto net) {
-        return launch_encode<decltype(net)>(ctx, d_img, n, H, W, sf, params, bits, st);
+        return launch_encode<decltype(net)>(ctx, d_img, n, H, W, sf, params, bits, progress, reserve_cus, st);
     });
 }
 
@@ -1396,6 +1504,10 @@ int pcc_create(pcc_ctx** out, const void* h_blob, size_t blob_bytes, int hip_dev
         const int v = atoi(e);
         if (v >= 0 && v < 4) ctx->encode_variant = v;
     }
+    if (const char* e = getenv("PCC_ENCODE_OVERLAP")) ctx->overlap = atoi(e) != 0;
+    ok = ok && hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking) == hipSuccess;
+    ok = ok && hipMalloc((void**)&ctx->d_progress, kProgressBytes) == hipSuccess;
+    ok = ok && hipMemset(ctx->d_progress, 0, kProgressBytes) == hipSuccess;
     if (!ok) { (void)hipGetLastError(); pcc_destroy(ctx); return PCC_E_HIP; }
     ctx->d_total = reinterpret_cast<uint64_t*>(ctx->d_status + kStWords);
     *out = ctx;
@@ -1410,6 +1522,8 @@ void pcc_destroy(pcc_ctx* ctx) {
     if (ctx->d_status) (void)hipFree(ctx->d_status);
     if (ctx->h_status) (void)hipHostFree(ctx->h_status);
     for (hipEvent_t e : ctx->ev) if (e) (void)hipEventDestroy(e);
+    if (ctx->d_progress) (void)hipFree(ctx->d_progress);
+    if (ctx->side) (void)hipStreamDestroy(ctx->side);
     delete ctx;
 }
 
@@ -1433,7 +1547,7 @@ int pcc_encode_probs(pcc_ctx* ctx, const uint8_t* d_img, int n, int H, int W, fl
     if (!ctx || !d_img || !d_params || !dims_ok(n, H, W)) return PCC_E_ARG;
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return PCC_E_HIP;
-    return launch_encode_any(ctx, d_img, n, H, W, nullptr, d_params, d_bits, (hipStream_t)hip_stream);
+    return launch_encode_any(ctx, d_img, n, H, W, nullptr, d_params, d_bits, nullptr, 0, (hipStream_t)hip_stream);
 }
 
 int pcc_encode(pcc_ctx* ctx, const uint8_t* d_img, int n, int H, int W, uint8_t* d_stream, size_t cap_bytes,
@@ -1451,6 +1565,8 @@ int pcc_encode(pcc_ctx* ctx, const uint8_t* d_img, int n, int H, int W, uint8_t*
     const size_t sf_bytes = align_up(P * 3 * sizeof(uint32_t), 256);
     const size_t slab_bytes = align_up((size_t)rows * slab_words(W) * 4, 256);
     const size_t rw_bytes = align_up((size_t)rows * 4, 256);
+    const EncodeVariant variant = kEncodeVariants[ctx->encode_variant];
+    const uint32_t strip_cols = 16u * variant.tiles;
     int rc = ensure_workspace(ctx, sf_bytes + slab_bytes + rw_bytes);
     if (rc != PCC_OK) return rc;
     uint32_t* d_sf = reinterpret_cast<uint32_t*>(ctx->d_ws);
@@ -1459,28 +1575,68 @@ int pcc_encode(pcc_ctx* ctx, const uint8_t* d_img, int n, int H, int W, uint8_t*
     ctx->d_sf = d_sf;
     ctx->sf_count = (size_t)P * 3;
 
+    // A small job's row coder is a handful of workgroups bound by the latency of their serial chains.  It runs
+    // beside the pixel kernel, on compute units the pixel kernel's grid leaves free (a pixel workgroup fills a
+    // unit's LDS, so the workgroups of both kernels are resident whatever order the dispatcher takes them in),
+    // and follows the pixel kernel's progress words.  The row coder and what comes after it go to a stream of
+    // the context's own; nothing orders that stream after the caller's, so this is only done when the caller's
+    // stream is idle and the pixel kernel starts at once.  A large job's row coder needs the whole chip and
+    // runs after the pixel kernel, on the caller's stream.
+    const uint32_t groups = (rows + kRansRows - 1) / kRansRows;
+    const uint32_t cus = ctx->num_cus > 0 ? (uint32_t)ctx->num_cus : 256u;
+    bool beside = ctx->overlap && groups <= kRansBesideMaxGroups && cus >= 4 * kRansBesideMaxGroups && cus <= kMaxCus;
+    if (beside) {
+        const hipError_t busy = hipStreamQuery(st);
+        if (busy != hipSuccess) { (void)hipGetLastError(); beside = false; }
+    }
+    uint64_t* progress = nullptr;
+    if (beside) {
+        if (++ctx->epoch == 0) {      // wrapped: the words of old launches would look finished
+            if (hipMemset(ctx->d_progress, 0, kProgressBytes) != hipSuccess) return PCC_E_HIP;
+            ctx->epoch = 1;
+        }
+        progress = ctx->d_progress;
+    }
+    // Workgroups go to the chip's eight dies in turn and stay there: a die must have room for its share of both
+    // kernels, or a pixel workgroup waits for a compute unit until others of its die have ended and then works
+    // through its share of the items alone.
+    const uint32_t reserve = beside ? kXcds * ((groups + kXcds - 1) / kXcds) : 0u;
+    const uint32_t pixel_waves = encode_blocks(ctx, n, H, W, reserve) * (variant.threads / 64);
+    hipStream_t tail = beside ? ctx->side : st;
+
     if (hipMemsetAsync(ctx->d_status, 0, kStWords * sizeof(int) + sizeof(uint64_t), st) != hipSuccess) return PCC_E_HIP;
     prof_reset(ctx);
+    auto launch_rans = [&]() {
+        prof_begin(ctx, PCC_T_ENCODE_RANS, tail);
+        hipLaunchKernelGGL(rans_rows_kernel, dim3(groups), dim3(kRansThreads), 0, tail, d_sf, W, rows, d_slabs, d_rw, progress,
+                           ctx->epoch, pixel_waves, strip_cols, ctx->d_status, kRansSpinLimit);
+        prof_end(ctx, PCC_T_ENCODE_RANS, tail);
+    };
+    // beside: the row coder goes first and is in place, polling, when the pixel kernel starts
+    if (beside) launch_rans();
     prof_begin(ctx, PCC_T_ENCODE_PIXELS, st);
-    rc = launch_encode_any(ctx, d_img, n, H, W, d_sf, nullptr, nullptr, st);
-    if (rc != PCC_OK) return rc;
+    rc = launch_encode_any(ctx, d_img, n, H, W, d_sf, nullptr, nullptr, progress, reserve, st);
+    if (rc != PCC_OK) {
+        if (beside) (void)hipStreamSynchronize(ctx->side);   // the row coder gives up once its polls run out
+        return rc;
+    }
     prof_end(ctx, PCC_T_ENCODE_PIXELS, st);
-    prof_begin(ctx, PCC_T_ENCODE_RANS, st);
-    hipLaunchKernelGGL(rans_rows_kernel, dim3((rows + kRansRows - 1) / kRansRows), dim3(kRansThreads), 0, st, d_sf, W, rows,
-                       d_slabs, d_rw);
-    prof_end(ctx, PCC_T_ENCODE_RANS, st);
-    prof_begin(ctx, PCC_T_ENCODE_SCAN, st);
+    if (!beside) launch_rans();
+    prof_begin(ctx, PCC_T_ENCODE_SCAN, tail);
     const uint32_t tag = with_net(ctx->net, [](auto net) { return model_tag<decltype(net)>(); });
-    hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), 0, st, d_rw, rows, n, H, W, tag, ctx->dist, d_stream, ctx->d_total);
-    prof_end(ctx, PCC_T_ENCODE_SCAN, st);
-    prof_begin(ctx, PCC_T_ENCODE_COMPACT, st);
-    hipLaunchKernelGGL(compact_kernel, dim3(rows), dim3(64), 0, st, d_slabs, d_rw, W, rows, d_stream,
+    hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), 0, tail, d_rw, rows, n, H, W, tag, ctx->dist, d_stream, ctx->d_total);
+    prof_end(ctx, PCC_T_ENCODE_SCAN, tail);
+    prof_begin(ctx, PCC_T_ENCODE_COMPACT, tail);
+    hipLaunchKernelGGL(compact_kernel, dim3(rows), dim3(64), 0, tail, d_slabs, d_rw, W, rows, d_stream,
                        (uint64_t)cap_bytes, ctx->d_status);
-    prof_end(ctx, PCC_T_ENCODE_COMPACT, st);
+    prof_end(ctx, PCC_T_ENCODE_COMPACT, tail);
     if (hipGetLastError() != hipSuccess) return PCC_E_HIP;
     if (hipMemcpyAsync(ctx->h_status, ctx->d_status, kStWords * sizeof(int) + sizeof(uint64_t), hipMemcpyDeviceToHost,
-                       st) != hipSuccess) return PCC_E_HIP;
-    if (hipStreamSynchronize(st) != hipSuccess) { (void)hipGetLastError(); return PCC_E_HIP; }
+                       tail) != hipSuccess) return PCC_E_HIP;
+    // the row coder ends after the pixel kernel's last store; the caller's stream is waited for as well so that
+    // the pixel kernel has retired when this returns
+    if (hipStreamSynchronize(tail) != hipSuccess) { (void)hipGetLastError(); return PCC_E_HIP; }
+    if (beside && hipStreamSynchronize(st) != hipSuccess) { (void)hipGetLastError(); return PCC_E_HIP; }
     prof_collect(ctx);
     if (ctx->h_status[kStErr] != 0) return ctx->h_status[kStErr];
     uint64_t total;

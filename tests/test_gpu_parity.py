@@ -415,3 +415,32 @@ def test_roundtrip_random_shapes(codec, codec_sharp, paper_blob, diagonal_blob):
     finally:
         for c in extra:
             c.close()
+
+
+def test_row_coder_beside_after_and_busy_stream_agree(blob, paper_blob, monkeypatch):
+    """The row coder of a small job runs beside the pixel kernel, that of a large job or of a caller whose stream
+    has work pending runs after it: all three must write the same bytes (and bytes the oracle-coded rows give
+    are covered by the container tests)."""
+    from paper_2212_01185_amd import binding
+    rng = np.random.default_rng(23)
+    shapes = [(1, 70, 45), (3, 33, 100), (1, 130, 1), (1, 64, 11), (2, 200, 37), (1, 1, 300)]
+    for name, b in (("workload", blob), ("paper", paper_blob)):
+        beside = binding.Codec(b, 0)
+        monkeypatch.setenv("PCC_ENCODE_OVERLAP", "0")
+        after = binding.Codec(b, 0)
+        monkeypatch.delenv("PCC_ENCODE_OVERLAP")
+        try:
+            for n, h, w in shapes:
+                _log("row coder beside/after %s %dx%dx%d" % (name, n, h, w))
+                imgs = _dev(rng.integers(0, 256, (n, h, w, 3), dtype=np.uint8))
+                want = after.pcc_encode(imgs).cpu().numpy().tobytes()
+                assert beside.pcc_encode(imgs).cpu().numpy().tobytes() == want
+                # pending work on the caller's stream: the encode must order itself behind it
+                big = torch.ones(1 << 27, device="cuda")
+                for _ in range(16):
+                    big.mul_(1.0001)
+                assert beside.pcc_encode(imgs).cpu().numpy().tobytes() == want
+                torch.cuda.synchronize()
+        finally:
+            beside.close()
+            after.close()
