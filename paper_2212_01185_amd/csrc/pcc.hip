@@ -9,6 +9,7 @@
 //                      job it runs beside encode_kernel and follows its progress
 //   scan_kernel        exclusive prefix sum of row payload sizes, header, offsets
 //   compact_kernel     slabs -> contiguous stream
+//   compact_scan_kernel  both of the above in one launch, for jobs of few rows
 //   decode_kernel      persistent wavefront decoder: one workgroup (4 waves) per
 //                      band of 16 rows, step t handles pixel (r, t - delay*r) of each row
 //   cdf_tables_kernel  test hook: full integer CDF tables from given parameters
@@ -296,30 +297,37 @@ constexpr uint32_t kRansSpinLimit = 1u << 22;       // polls of a progress count
 // and never renormalises, so every chunk can be coded as a full one.
 constexpr uint32_t kRansNop = 0xFFFF0000u;
 
-// 1/f in fp64 for 1 <= f < 2^17: hardware estimate plus two Newton steps
-// (relative error ~2^-52).  Independent of the coder state.
-__device__ __forceinline__ double rans_recip(uint32_t f32) {
+// A value just below 1/f in fp64 for 1 <= f < 2^17: hardware estimate plus two
+// Newton steps (relative error about 2^-52 either way), then pulled down by
+// 2^-50.  Independent of the coder state.
+__device__ __forceinline__ double rans_recip_below(uint32_t f32) {
     const double fd = (double)f32;
     double rf = __builtin_amdgcn_rcp(fd);
     rf = __builtin_fma(__builtin_fma(-fd, rf, 1.0), rf, rf);
     rf = __builtin_fma(__builtin_fma(-fd, rf, 1.0), rf, rf);
-    return rf;
+    return rf * (1.0 - 0x1p-50);
 }
 
-// x <- C(x, (start, f)) with an exact x / f for x < 2^47 * f: the fp64 quotient
-// estimate is within one of the truth, so the remainder x - q f lies in (-f, 2f)
-// and its low 32 bits decide the correction.  Branch-free.
-__device__ __forceinline__ void rans_push(uint64_t& x, uint32_t f, uint32_t start, double rf) {
-    const double xd = __builtin_fma((double)(uint32_t)(x >> 32), 4294967296.0, (double)(uint32_t)x);
-    // round(xd * rf) read off the mantissa after adding 2^52 (the quotient is below 2^47)
-    const double qd = __builtin_fma(xd, rf, 4503599627370496.0);
-    uint64_t q = (uint64_t)__double_as_longlong(qd) & 0x000FFFFFFFFFFFFFull;
-    int32_t rem = (int32_t)((uint32_t)x - (uint32_t)q * f);
-    const int32_t neg = rem < 0 ? 1 : 0, over = rem >= (int32_t)f ? 1 : 0;
-    rem += neg ? (int32_t)f : 0;
-    rem -= over ? (int32_t)f : 0;
-    q += (uint64_t)(int64_t)(over - neg);
-    x = (q << 16) + (uint64_t)((uint32_t)rem + start);
+// The coding wave rounds its fp64 arithmetic toward zero (MODE.FP_ROUND bits 3:2 = 3).  Written as
+// assembly: the compiler would put the default mode back in front of the wave's fp64 instructions.
+__device__ __forceinline__ void rans_round_toward_zero() {
+    asm volatile("s_setreg_imm32_b32 hwreg(HW_REG_MODE, 2, 2), 3" ::: "memory");
+}
+
+// x <- C(x, (start, f)) with an exact x / f for x = xh 2^32 + xl < 2^47 * f.  Needs
+// rans_round_toward_zero(): the state converted to fp64 (at most x), times a value
+// below 1/f, plus 2^52, each rounded toward zero, leaves an estimate of the quotient
+// in the mantissa that is the quotient or one less (all the errors together are
+// below 2^47 * 2^-49), so the remainder x - q f lies in [0, 2f) and its low 32 bits
+// decide the one correction.  Branch-free.
+__device__ __forceinline__ void rans_push(uint32_t& xl, uint32_t& xh, uint32_t f, uint32_t start, double rf_below) {
+    const double xd = __builtin_fma((double)xh, 4294967296.0, (double)xl);
+    const uint64_t qb = (uint64_t)__double_as_longlong(__builtin_fma(xd, rf_below, 4503599627370496.0));
+    const uint32_t rem = xl - (uint32_t)qb * f;
+    const uint32_t z = rem + start + (rem >= f ? 65536u - f : 0u);   // a quotient one short: carry 2^16 - f
+    const uint64_t x = (qb << 16) + z;                               // the exponent bits of qb leave at the top
+    xl = (uint32_t)x;
+    xh = (uint32_t)(x >> 32);
 }
 
 // Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for
@@ -333,6 +341,9 @@ __device__ __forceinline__ void lds_barrier() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
+// BESIDE: the pixel kernel is running; progress is followed and sf is read past the caches that are not
+// coherent with its stores.
+template <bool BESIDE>
 __global__ void __launch_bounds__(kRansThreads)
 rans_rows_kernel(const uint32_t* __restrict__ sf, int W, uint32_t rows, uint32_t* __restrict__ slabs,
                  uint32_t* __restrict__ row_words, const uint64_t* progress, uint32_t epoch, uint32_t pixel_waves,
@@ -340,9 +351,9 @@ rans_rows_kernel(const uint32_t* __restrict__ sf, int W, uint32_t rows, uint32_t
     // [buffer][row][symbol of the chunk]; the odd row strides keep the coding wave's column accesses off shared banks
     __shared__ uint32_t sym[2][kRansRows][kRansChunk + 1];
     __shared__ double rcp[2][kRansRows][kRansChunk + 1];
-    // renormalisation words the coding wave produced in a chunk, in the order produced; [row][kRansChunk] = their number
+    // renormalisation words the coding wave produced in a chunk, in the order produced
     __shared__ uint32_t outw[2][kRansRows][kRansChunk + 1];
-    __shared__ uint32_t outpos[2][kRansRows];   // the row's slab position (words) before the chunk
+    __shared__ uint32_t outmeta[2][kRansRows];  // the row's slab position (words) before the chunk << 6 | words produced in it
     const int tid = threadIdx.x, lane = tid & 63;
     const bool coder = tid < 64;
     const uint32_t row0 = blockIdx.x * kRansRows;
@@ -352,135 +363,173 @@ rans_rows_kernel(const uint32_t* __restrict__ sf, int W, uint32_t rows, uint32_t
     const uint32_t live_rows = min((uint32_t)kRansRows, rows - row0);
     const size_t sw = slab_words(W);
     uint32_t wp = (uint32_t)sw;     // slabs fill from the end: the decoder reads the words in reverse order of production
-    uint64_t x = kRansL;
+    uint32_t xl = (uint32_t)kRansL, xh = (uint32_t)(kRansL >> 32);   // the coder state x = xh 2^32 + xl
 
-    constexpr int kFeeders = kRansThreads - 64;
-    constexpr int kPerFeeder = (kRansRows * kRansChunk + kFeeders - 1) / kFeeders;
-    // Waves 1-3 feed the coding wave through a pipeline, one stage per round (a round = the coding wave codes a
-    // chunk; rounds end in a workgroup barrier), so that no feeder waits for memory inside a round:
-    //   round k + 4  the progress words for chunk k are requested          (only beside a running pixel kernel)
-    //   round k + 3  ... and waited for
-    //   round k + 2  the chunk's symbols are requested from global memory into registers
+    // Wave 0 codes; waves 2 and 3 load (symbols from global memory, reciprocals, both to LDS); wave 1 stores (the
+    // words the coding wave produced, from LDS to the rows' slabs).  Loads and stores are kept in different waves
+    // because a wave's loads and stores complete out of order with each other under one counter: a wave that
+    // has stores in flight can only wait for a load by waiting for everything.
+    const bool storer = tid >= 64 && tid < 128, loader = tid >= 128;
+    constexpr int kLoaders = kRansThreads - 128;
+    constexpr int kPerLoader = (kRansRows * kRansChunk + kLoaders - 1) / kLoaders;
+    static_assert(kRansRows * kRansChunk % kLoaders == 0 && kRansChunk == 32 && kRansRows == 64, "whole elements per thread");
+    // The pipeline, one stage per round (a round = the coding wave codes a chunk; rounds end in a workgroup
+    // barrier), so that no wave waits for memory inside a round:
+    //   round k + 5  the progress words for chunk k are requested          (only beside a running pixel kernel)
+    //   round k + 4  ... and waited for
+    //   round k + 3  the chunk's symbols are requested from global memory into registers (two sets, by round parity)
     //   round k + 1  reciprocals are computed, symbols and reciprocals go to LDS buffer k & 1
     //   round k      the coding wave codes the chunk
     //   round k - 1  the words it produced are copied to the rows' slabs
     //
-    // The pixel kernel may run beside this one (progress != nullptr); it finishes the image strip by strip from
+    // The pixel kernel may run beside this one (BESIDE); it finishes the image strip by strip from
     // the right edge.  Item strip * rows + row of the pixel kernel is the (item / G + 1)-th item of its wave
-    // item % G: the first feeder wave follows, one lane per row, the progress words of the waves that own this
+    // item % G: the first loading wave follows, one lane per row, the progress words of the waves that own this
     // workgroup's rows of a strip.  A barrier lies between that wait and the loads of the chunk, and the loads
     // bypass the caches that are not coherent with the pixel kernel's stores.
-    const bool follower = progress != nullptr && tid < 128 && (uint32_t)(tid - 64) < live_rows;
+    const bool follower = BESIDE && tid >= 128 && tid < 192 && (uint32_t)(tid - 128) < live_rows;
+    // Every loader lane reads one progress word per round, whether it follows a row and has a strip to wait for
+    // or not (then word 0, needing nothing): loads in straight-line code are loads the compiler can count, so
+    // the wait for this word does not become a wait for the symbol loads issued after it.
     uint32_t strips_asked = 0;          // strips [0, strips_asked) have been waited for or are being waited for
     uint32_t wait_first = 0, wait_end = 0;   // the strips the next wait covers
     uint64_t seen = 0;                  // the progress word of strip wait_first, requested a round ahead
     auto progress_slot = [&](uint32_t s, uint64_t& need) {
-        const uint32_t item = s * rows + row0 + (uint32_t)(tid - 64);
+        const uint32_t item = s * rows + row0 + (uint32_t)(tid - 128);
         need = ((uint64_t)epoch << 32) | (item / pixel_waves + 1u);   // epochs only grow
         return item % pixel_waves;
     };
     auto ask_for_chunk = [&](int k) {
         const uint32_t s_hi = ((uint32_t)W - 1u - ((uint32_t)k * kRansChunk) / 3u) / strip_cols;
-        if (!follower || s_hi < strips_asked) return;
-        wait_first = strips_asked;
-        wait_end = s_hi + 1u;
-        strips_asked = wait_end;
+        const bool fresh = follower && s_hi >= strips_asked;
+        wait_first = fresh ? strips_asked : 0u;
+        wait_end = fresh ? s_hi + 1u : 0u;
+        strips_asked = fresh ? wait_end : strips_asked;
         uint64_t need;
-        seen = __hip_atomic_load(&progress[progress_slot(wait_first, need)], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const uint32_t w = fresh ? progress_slot(wait_first, need) : 0u;
+        seen = __hip_atomic_load(&progress[w], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     };
     auto wait_for_asked = [&]() {
+        uint64_t have = seen;
         for (uint32_t s = wait_first; s < wait_end; ++s) {
             uint64_t need;
             const uint32_t w = progress_slot(s, need);
             uint32_t spins = 0;
-            uint64_t have = s == wait_first ? seen : 0;
             while (have < need) {
                 if (++spins > spin_limit) { set_error(status, PCC_E_INTERNAL); break; }
                 __builtin_amdgcn_s_sleep(4);
                 have = __hip_atomic_load(&progress[w], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
+            have = 0;
         }
-        wait_first = wait_end;
+        wait_end = wait_first;
     };
-    uint32_t staged[kPerFeeder];
-    auto request = [&](int k) {
+    uint32_t staged[2][kPerLoader];
+    auto request = [&](int k, uint32_t (&staged)[kPerLoader]) {
 #pragma unroll
-        for (int it = 0; it < kPerFeeder; ++it) {
-            const int e = tid - 64 + it * kFeeders;
+        for (int it = 0; it < kPerLoader; ++it) {
+            const int e = tid - 128 + it * kLoaders;
             const uint32_t r = (uint32_t)e / kRansChunk, i = (uint32_t)e % kRansChunk;
             const uint32_t idx = (uint32_t)k * kRansChunk + i;
-            const size_t at = (size_t)(row0 + r) * nsym + idx;
-            uint32_t v = kRansNop;
-            if (r < live_rows && idx < nsym)   // r >= 64 fails r < live_rows
-                v = progress != nullptr ? __hip_atomic_load(&sf[at], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : sf[at];
-            staged[it] = v;
+            // every lane loads (a padding element loads the buffer's first word): with no branch round the loads
+            // the compiler can count them, and waits for one register set while the other's loads are in flight
+            const bool real = r < live_rows && idx < nsym;
+            const size_t at = real ? (size_t)(row0 + r) * nsym + idx : 0;
+            staged[it] = BESIDE ? __hip_atomic_load(&sf[at], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : sf[at];
         }
     };
-    auto deposit = [&](int b) {
-#pragma unroll
-        for (int it = 0; it < kPerFeeder; ++it) {
-            const int e = tid - 64 + it * kFeeders;
-            if (e < kRansRows * kRansChunk) {
-                const uint32_t r = (uint32_t)e / kRansChunk, i = (uint32_t)e % kRansChunk;
-                sym[b][r][i] = staged[it];
-                rcp[b][r][i] = rans_recip((staged[it] >> 16) + 1u);
-            }
-        }
-    };
-    // waves 1-3: the words of a finished chunk from buffer b to the rows' slabs (consecutive lanes, consecutive words)
-    auto flush = [&](int b) {
-#pragma unroll
-        for (int it = 0; it < kPerFeeder; ++it) {
-            const int e = tid - 64 + it * kFeeders;
-            const uint32_t r = (uint32_t)e / kRansChunk, i = (uint32_t)e % kRansChunk;
-            if (r < live_rows && i < outw[b][r][kRansChunk])
-                slabs[(size_t)(row0 + r) * sw + (outpos[b][r] - 1u - i)] = outw[b][r][i];
-        }
-    };
-    for (int k = nchunks + 3; k >= 0; --k) {
+    auto deposit = [&](int k, const uint32_t (&staged)[kPerLoader]) {
         const int b = k & 1;
-        if (!coder) {
-            if (k >= 1 && k - 1 < nchunks) deposit(b ^ 1);
-            if (k >= 2 && k - 2 < nchunks) request(k - 2);
-            if (k + 1 < nchunks) flush(b ^ 1);
-            if (k >= 3 && k - 3 < nchunks) wait_for_asked();
-            if (k >= 4 && k - 4 < nchunks) ask_for_chunk(k - 4);
-        } else if (k < nchunks) {
+#pragma unroll
+        for (int it = 0; it < kPerLoader; ++it) {
+            const int e = tid - 128 + it * kLoaders;
+            const uint32_t r = (uint32_t)e / kRansChunk, i = (uint32_t)e % kRansChunk;
+            const uint32_t v = (r < live_rows && (uint32_t)k * kRansChunk + i < nsym) ? staged[it] : kRansNop;
+            sym[b][r][i] = v;
+            rcp[b][r][i] = rans_recip_below((v >> 16) + 1u);
+        }
+    };
+    // wave 1: the words of a finished chunk from buffer b to the rows' slabs.  Lane = word index within the chunk
+    // in both halves of the wave, the halves take the even and the odd rows: consecutive lanes write consecutive
+    // words.  All LDS reads are issued before the first store.
+    auto flush = [&](int b) {
+        const uint32_t i = (uint32_t)(tid - 64) % kRansChunk, odd = (uint32_t)(tid - 64) / kRansChunk;
+        uint32_t word[kRansRows / 2], meta[kRansRows / 2];
+#pragma unroll
+        for (int it = 0; it < kRansRows / 2; ++it) {
+            word[it] = outw[b][2 * it + odd][i];
+            meta[it] = outmeta[b][2 * it + odd];
+        }
+#pragma unroll
+        for (int it = 0; it < kRansRows / 2; ++it) {
+            const uint32_t r = 2 * it + odd;
+            if (r < live_rows && i < (meta[it] & 63u))
+                slabs[(size_t)(row0 + r) * sw + ((meta[it] >> 6) - 1u - i)] = word[it];
+        }
+    };
+    // The coding wave's serial chain sets the pace: it goes first wherever the compute unit's waves compete.
+    if (coder) {
+        rans_round_toward_zero();
+        __builtin_amdgcn_s_setprio(3);
+    }
+    // one round; P = the round's parity, which picks the loaders' register set
+    auto round = [&](int k, auto parity) {
+        constexpr int P = decltype(parity)::value;
+        const int b = k & 1;
+        if (loader) {
+            if (k >= 1 && k - 1 < nchunks) deposit(k - 1, staged[P]);
+            if constexpr (BESIDE) {
+                wait_for_asked();                                 // what the last round asked for
+                ask_for_chunk(min(max(k - 5, 0), nchunks - 1));   // outside the chunks: asks again or for nothing
+            }
+            request(min(max(k - 3, 0), nchunks - 1), staged[P]);     // outside the chunks: loads nobody uses
+        } else if (storer) {
+            if (k >= -1 && k + 1 < nchunks) flush(b ^ 1);
+        } else if (k >= 0 && k < nchunks) {
             uint32_t cnt = 0;
-            constexpr int kU = 8;   // symbols fetched from LDS side by side
-            for (int i0 = kRansChunk; i0 > 0; i0 -= kU) {
-                uint32_t v[kU];
-                double rf[kU];
+            // Symbols and reciprocals come from LDS in batches of kU; the next batch is requested before the
+            // serial chain of the current one starts, so that only the round's first read waits for LDS.
+            constexpr int kU = 8, kBatches = kRansChunk / kU;
+            uint32_t v[2][kU];
+            double rf[2][kU];
+            auto fetch = [&](int n) {
 #pragma unroll
                 for (int u = 0; u < kU; ++u) {
-                    v[u] = sym[b][lane][i0 - 1 - u];
-                    rf[u] = rcp[b][lane][i0 - 1 - u];
+                    v[n & 1][u] = sym[b][lane][kRansChunk - 1 - n * kU - u];
+                    rf[n & 1][u] = rcp[b][lane][kRansChunk - 1 - n * kU - u];
                 }
-                // scheduling only: one batch of LDS reads before the serial chain starts
-                asm volatile("" : "+v"(rf[0]), "+v"(rf[1]), "+v"(rf[2]), "+v"(rf[3]), "+v"(rf[4]), "+v"(rf[5]), "+v"(rf[6]), "+v"(rf[7]));
+            };
+            fetch(0);
+#pragma unroll
+            for (int n = 0; n < kBatches; ++n) {
+                if (n + 1 < kBatches) fetch(n + 1);
 #pragma unroll
                 for (int u = 0; u < kU; ++u) {
-                    const uint32_t start = v[u] & 0xFFFFu, f = (v[u] >> 16) + 1u;
+                    const uint32_t start = v[n & 1][u] & 0xFFFFu, f = (v[n & 1][u] >> 16) + 1u;
                     // renormalise when x >= f * 2^47; the word is stored either way and only
                     // kept (cnt moves) when it was due: no branch on the serial chain
-                    const bool emit = (uint32_t)(x >> 47) >= f;
-                    outw[b][lane][cnt] = (uint32_t)x;
+                    const bool emit = (xh >> 15) >= f;
+                    outw[b][lane][cnt] = xl;
                     cnt += emit ? 1u : 0u;
-                    x = emit ? (x >> 32) : x;
-                    rans_push(x, f, start, rf[u]);
+                    xl = emit ? xh : xl;
+                    xh = emit ? 0u : xh;
+                    rans_push(xl, xh, f, start, rf[n & 1][u]);
                 }
             }
-            outw[b][lane][kRansChunk] = cnt;
-            outpos[b][lane] = wp;
+            outmeta[b][lane] = (wp << 6) | cnt;   // wp < 2^25, cnt <= 32
             wp -= cnt;
         }
-        lds_barrier();   // all that crosses threads here is in LDS; a feeder's global loads stay in flight
+        lds_barrier();   // all that crosses threads here is in LDS; the loaders' global loads stay in flight
+    };
+    // rounds nchunks + 4 (or + 5, for an even number of rounds) down to -1, where chunk 0's words are stored
+    for (int k = nchunks + 4 + (nchunks & 1); k >= 0; k -= 2) {
+        round(k, std::integral_constant<int, 0>());
+        round(k - 1, std::integral_constant<int, 1>());
     }
-    if (!coder) flush(0);                                // chunk 0 lives in buffer 0
     if (coder && row < rows) {
         uint32_t* slab = slabs + (size_t)row * sw;
-        slab[wp - 1] = (uint32_t)(x >> 32);
-        slab[wp - 2] = (uint32_t)x;
+        slab[wp - 1] = xh;
+        slab[wp - 2] = xl;
         row_words[row] = (uint32_t)sw - (wp - 2u);
     }
 }
@@ -536,6 +585,53 @@ compact_kernel(const uint32_t* __restrict__ slabs, const uint32_t* __restrict__ 
     const uint32_t* src = slabs + (size_t)row * sw + (sw - nw);
     uint32_t* dst = reinterpret_cast<uint32_t*>(stream + table + off);
     for (uint32_t i = threadIdx.x; i < nw; i += blockDim.x) dst[i] = src[i];
+}
+
+// scan_kernel and compact_kernel in one launch for jobs of few rows: every workgroup sums the sizes of the rows
+// before its own (the sizes stay in L2), so nothing has to wait for a scan.  Quadratic in the rows.
+constexpr uint32_t kCompactScanMaxRows = 4096;
+constexpr int kCompactScanThreads = 256;
+
+__global__ void __launch_bounds__(kCompactScanThreads)
+compact_scan_kernel(const uint32_t* __restrict__ slabs, const uint32_t* __restrict__ row_words, int n, int H, int W,
+                    uint32_t rows, uint32_t tag, uint32_t dist, uint8_t* __restrict__ stream, uint64_t cap_bytes,
+                    uint64_t* __restrict__ total_bytes, int* status) {
+    __shared__ unsigned long long part[kCompactScanThreads / 64];
+    const uint32_t row = blockIdx.x;
+    unsigned long long words_before = 0;
+    for (uint32_t j = threadIdx.x; j < row; j += kCompactScanThreads) words_before += row_words[j];
+    for (int d = 32; d >= 1; d >>= 1) words_before += __shfl_xor(words_before, d);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = words_before;
+    __syncthreads();
+    words_before = 0;
+    for (int w = 0; w < kCompactScanThreads / 64; ++w) words_before += part[w];
+
+    const size_t sw = slab_words(W);
+    const uint64_t table = (uint64_t)kStreamHeader + 8ull * (rows + 1);
+    const uint64_t off = 4ull * words_before;
+    const uint32_t nw = row_words[row];
+    // header, this row's offset and, from the last row, the end offset and the total: all inside the table,
+    // which the host has checked against the capacity
+    uint64_t* offsets = reinterpret_cast<uint64_t*>(stream + kStreamHeader);
+    if (threadIdx.x == 0) {
+        offsets[row] = off;
+        if (row == 0) {
+            uint32_t* hdr = reinterpret_cast<uint32_t*>(stream);
+            hdr[0] = kStreamMagic; hdr[1] = 1; hdr[2] = (uint32_t)n; hdr[3] = (uint32_t)H; hdr[4] = (uint32_t)W;
+            hdr[5] = tag; hdr[6] = dist; hdr[7] = 0;
+        }
+        if (row + 1 == rows) {
+            offsets[rows] = off + 4ull * nw;
+            *total_bytes = table + off + 4ull * nw;
+        }
+    }
+    if (table + off + 4ull * nw > cap_bytes) {
+        if (threadIdx.x == 0) set_error(status, PCC_E_CAP);
+        return;
+    }
+    const uint32_t* src = slabs + (size_t)row * sw + (sw - nw);
+    uint32_t* dst = reinterpret_cast<uint32_t*>(stream + table + off);
+    for (uint32_t i = threadIdx.x; i < nw; i += kCompactScanThreads) dst[i] = src[i];
 }
 
 // ---------------------------------------------------------------------------
@@ -1608,8 +1704,12 @@ int pcc_encode(pcc_ctx* ctx, const uint8_t* d_img, int n, int H, int W, uint8_t*
     prof_reset(ctx);
     auto launch_rans = [&]() {
         prof_begin(ctx, PCC_T_ENCODE_RANS, tail);
-        hipLaunchKernelGGL(rans_rows_kernel, dim3(groups), dim3(kRansThreads), 0, tail, d_sf, W, rows, d_slabs, d_rw, progress,
-                           ctx->epoch, pixel_waves, strip_cols, ctx->d_status, kRansSpinLimit);
+        if (beside)
+            hipLaunchKernelGGL(rans_rows_kernel<true>, dim3(groups), dim3(kRansThreads), 0, tail, d_sf, W, rows, d_slabs, d_rw,
+                               progress, ctx->epoch, pixel_waves, strip_cols, ctx->d_status, kRansSpinLimit);
+        else
+            hipLaunchKernelGGL(rans_rows_kernel<false>, dim3(groups), dim3(kRansThreads), 0, tail, d_sf, W, rows, d_slabs, d_rw,
+                               progress, ctx->epoch, pixel_waves, strip_cols, ctx->d_status, kRansSpinLimit);
         prof_end(ctx, PCC_T_ENCODE_RANS, tail);
     };
     // beside: the row coder goes first and is in place, polling, when the pixel kernel starts
@@ -1622,14 +1722,21 @@ int pcc_encode(pcc_ctx* ctx, const uint8_t* d_img, int n, int H, int W, uint8_t*
     }
     prof_end(ctx, PCC_T_ENCODE_PIXELS, st);
     if (!beside) launch_rans();
-    prof_begin(ctx, PCC_T_ENCODE_SCAN, tail);
     const uint32_t tag = with_net(ctx->net, [](auto net) { return model_tag<decltype(net)>(); });
-    hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), 0, tail, d_rw, rows, n, H, W, tag, ctx->dist, d_stream, ctx->d_total);
-    prof_end(ctx, PCC_T_ENCODE_SCAN, tail);
-    prof_begin(ctx, PCC_T_ENCODE_COMPACT, tail);
-    hipLaunchKernelGGL(compact_kernel, dim3(rows), dim3(64), 0, tail, d_slabs, d_rw, W, rows, d_stream,
-                       (uint64_t)cap_bytes, ctx->d_status);
-    prof_end(ctx, PCC_T_ENCODE_COMPACT, tail);
+    if (rows <= kCompactScanMaxRows) {
+        prof_begin(ctx, PCC_T_ENCODE_COMPACT, tail);
+        hipLaunchKernelGGL(compact_scan_kernel, dim3(rows), dim3(kCompactScanThreads), 0, tail, d_slabs, d_rw, n, H, W, rows,
+                           tag, ctx->dist, d_stream, (uint64_t)cap_bytes, ctx->d_total, ctx->d_status);
+        prof_end(ctx, PCC_T_ENCODE_COMPACT, tail);
+    } else {
+        prof_begin(ctx, PCC_T_ENCODE_SCAN, tail);
+        hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), 0, tail, d_rw, rows, n, H, W, tag, ctx->dist, d_stream, ctx->d_total);
+        prof_end(ctx, PCC_T_ENCODE_SCAN, tail);
+        prof_begin(ctx, PCC_T_ENCODE_COMPACT, tail);
+        hipLaunchKernelGGL(compact_kernel, dim3(rows), dim3(64), 0, tail, d_slabs, d_rw, W, rows, d_stream,
+                           (uint64_t)cap_bytes, ctx->d_status);
+        prof_end(ctx, PCC_T_ENCODE_COMPACT, tail);
+    }
     if (hipGetLastError() != hipSuccess) return PCC_E_HIP;
     if (hipMemcpyAsync(ctx->h_status, ctx->d_status, kStWords * sizeof(int) + sizeof(uint64_t), hipMemcpyDeviceToHost,
                        tail) != hipSuccess) return PCC_E_HIP;
