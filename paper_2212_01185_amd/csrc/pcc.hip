@@ -6,7 +6,8 @@
 //                      ends first
 //   rans_rows_kernel   one lane per image row: push the row's symbols last to
 //                      first into a per-row slab, written backwards; for a small
-//                      job it runs beside encode_kernel and follows its progress
+//                      job it runs beside encode_kernel, taking the symbols as
+//                      they appear
 //   scan_kernel        exclusive prefix sum of row payload sizes, header, offsets
 //   compact_kernel     slabs -> contiguous stream
 //   compact_scan_kernel  both of the above in one launch, for jobs of few rows
@@ -135,15 +136,16 @@ __device__ __forceinline__ void lane_head_setup(const f32x4_t (&o)[Layout<Net>::
 // w of the grid's G waves takes the items w, w + G, w + 2G, ...  The rows' right
 // ends are therefore finished first, which is where the row coder starts (it
 // pushes the symbols last to first).  The row coder may run beside this kernel:
-// then progress[w] = epoch << 32 | number of items wave w has finished (the epoch
-// tells this launch's words from an earlier launch's, so nothing has to clear them),
-// and the row coder works out from those which of its rows' strips are complete.
+// then the results go to sf_tagged instead of sf, one 64-bit word per symbol with
+// this launch's epoch in the high half, written through to device scope.  A
+// reader that finds the epoch has the symbol; nothing else is published and
+// nothing has to be cleared between launches (epochs only grow).
 // ---------------------------------------------------------------------------
 template <class Net, int T, int THREADS>
 __global__ void __launch_bounds__(THREADS)
 encode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ img, int n, int H, int W,
               uint32_t* __restrict__ sf, float* __restrict__ params, float* __restrict__ bits, int* status,
-              uint64_t* progress, uint32_t epoch) {
+              uint64_t* sf_tagged, uint32_t epoch) {
     using Lay = Layout<Net>;
     constexpr int K = Net::K, KB0 = Net::kb(0), HEAD = Net::dim(Net::kLayers);
     extern __shared__ __align__(16) uint8_t lds[];
@@ -158,20 +160,6 @@ encode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ img
     const uint32_t P = rows * (uint32_t)W;
     const uint32_t nstrips = ((uint32_t)W + 16 * T - 1) / (16 * T);
     const uint32_t items = nstrips * rows;
-    // The stores of an item are published an item later, when they have long completed.  With a follower the
-    // results are written through to device scope (relaxed atomic stores), so that all the publishing wave has
-    // to do is wait for its own stores (a release fence would write back the whole L2 once per item), and a wave
-    // publishes into a word of its own (counters shared by all waves cost more than the row coder saves).
-    uint32_t finished = 0;
-    auto publish = [&]() {
-        if (progress != nullptr && finished != 0) {
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            if (lane == 0)
-                __hip_atomic_store(&progress[blockIdx.x * nwaves + wave], ((uint64_t)epoch << 32) | finished, __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_AGENT);
-        }
-    };
-
     for (uint32_t item = blockIdx.x * nwaves + wave; item < items; item += gridDim.x * nwaves) {
         const uint32_t strip = item / rows, rowg = item - strip * rows;
         const uint32_t im = rowg / (uint32_t)H;
@@ -231,8 +219,6 @@ encode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ img
                 in[t][kbi][1] = in[t][kbi][0];   // unused (layer-1 inputs are exact)
             }
         }
-        publish();
-
         f32x4_t out[T][Lay::kHeadOB];
         mlp_from<Net, T, (T == 1 && THREADS <= 512), 0>(lds + opaque_zero(), lane, in, out);
 
@@ -263,10 +249,12 @@ encode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ img
             const uint32_t hi = cq_full<K>(h.cp, x + 1, lut);
             uint32_t freq = hi - lo;
             if (g < 3 && live && (hi <= lo || freq > 65536u)) { set_error(status, PCC_E_INTERNAL); freq = 1; }
-            if (sf != nullptr && g < 3 && live) {
+            if (g < 3 && live) {
                 const uint32_t word = lo | ((freq - 1u) << 16);
-                if (progress != nullptr) __hip_atomic_store(&sf[(size_t)p * 3 + g], word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                else sf[(size_t)p * 3 + g] = word;
+                if (sf_tagged != nullptr)
+                    __hip_atomic_store(&sf_tagged[(size_t)p * 3 + g], ((uint64_t)epoch << 32) | word, __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+                else if (sf != nullptr) sf[(size_t)p * 3 + g] = word;
             }
             if (bits != nullptr) {
                 const float mine = 16.0f - __builtin_amdgcn_logf((float)freq);
@@ -274,9 +262,7 @@ encode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ img
                 if (g == 0 && live) bits[p] = tot;
             }
         }
-        ++finished;
     }
-    publish();
 }
 
 // ---------------------------------------------------------------------------
@@ -291,8 +277,7 @@ constexpr int kRansChunk = 32;
 constexpr int kRansThreads = 256;
 constexpr uint32_t kRansBesideMaxGroups = 48;      // row-coder workgroups that may run beside the pixel kernel
 constexpr uint32_t kXcds = 8;
-constexpr uint32_t kMaxCus = 256, kProgressBytes = kMaxCus * 16 * 8;   // a progress word per wave of the pixel kernel
-constexpr uint32_t kRansSpinLimit = 1u << 22;       // polls of a progress counter before the row coder gives up (seconds)
+constexpr uint32_t kRansSpinLimit = 1u << 22;       // polls for one symbol before the row coder gives up (seconds)
 // Padding symbol (start 0, frequency 2^16): pushing it leaves the state unchanged
 // and never renormalises, so every chunk can be coded as a full one.
 constexpr uint32_t kRansNop = 0xFFFF0000u;
@@ -341,13 +326,12 @@ __device__ __forceinline__ void lds_barrier() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-// BESIDE: the pixel kernel is running; progress is followed and sf is read past the caches that are not
-// coherent with its stores.
+// BESIDE: the pixel kernel is running; the symbols are read from sf_tagged, past the caches that are not
+// coherent with the pixel kernel's stores, and each is waited for until it carries this launch's epoch.
 template <bool BESIDE>
 __global__ void __launch_bounds__(kRansThreads)
-rans_rows_kernel(const uint32_t* __restrict__ sf, int W, uint32_t rows, uint32_t* __restrict__ slabs,
-                 uint32_t* __restrict__ row_words, const uint64_t* progress, uint32_t epoch, uint32_t pixel_waves,
-                 uint32_t strip_cols, int* status, uint32_t spin_limit) {
+rans_rows_kernel(const uint32_t* __restrict__ sf, const uint64_t* sf_tagged, uint32_t epoch, int W, uint32_t rows,
+                 uint32_t* __restrict__ slabs, uint32_t* __restrict__ row_words, int* status, uint32_t spin_limit) {
     // [buffer][row][symbol of the chunk]; the odd row strides keep the coding wave's column accesses off shared banks
     __shared__ uint32_t sym[2][kRansRows][kRansChunk + 1];
     __shared__ double rcp[2][kRansRows][kRansChunk + 1];
@@ -375,57 +359,14 @@ rans_rows_kernel(const uint32_t* __restrict__ sf, int W, uint32_t rows, uint32_t
     static_assert(kRansRows * kRansChunk % kLoaders == 0 && kRansChunk == 32 && kRansRows == 64, "whole elements per thread");
     // The pipeline, one stage per round (a round = the coding wave codes a chunk; rounds end in a workgroup
     // barrier), so that no wave waits for memory inside a round:
-    //   round k + 5  the progress words for chunk k are requested          (only beside a running pixel kernel)
-    //   round k + 4  ... and waited for
     //   round k + 3  the chunk's symbols are requested from global memory into registers (two sets, by round parity)
-    //   round k + 1  reciprocals are computed, symbols and reciprocals go to LDS buffer k & 1
+    //   round k + 1  (beside the pixel kernel: symbols it has not written yet are waited for,) reciprocals are
+    //                computed, symbols and reciprocals go to LDS buffer k & 1
     //   round k      the coding wave codes the chunk
     //   round k - 1  the words it produced are copied to the rows' slabs
-    //
-    // The pixel kernel may run beside this one (BESIDE); it finishes the image strip by strip from
-    // the right edge.  Item strip * rows + row of the pixel kernel is the (item / G + 1)-th item of its wave
-    // item % G: the first loading wave follows, one lane per row, the progress words of the waves that own this
-    // workgroup's rows of a strip.  A barrier lies between that wait and the loads of the chunk, and the loads
-    // bypass the caches that are not coherent with the pixel kernel's stores.
-    const bool follower = BESIDE && tid >= 128 && tid < 192 && (uint32_t)(tid - 128) < live_rows;
-    // Every loader lane reads one progress word per round, whether it follows a row and has a strip to wait for
-    // or not (then word 0, needing nothing): loads in straight-line code are loads the compiler can count, so
-    // the wait for this word does not become a wait for the symbol loads issued after it.
-    uint32_t strips_asked = 0;          // strips [0, strips_asked) have been waited for or are being waited for
-    uint32_t wait_first = 0, wait_end = 0;   // the strips the next wait covers
-    uint64_t seen = 0;                  // the progress word of strip wait_first, requested a round ahead
-    auto progress_slot = [&](uint32_t s, uint64_t& need) {
-        const uint32_t item = s * rows + row0 + (uint32_t)(tid - 128);
-        need = ((uint64_t)epoch << 32) | (item / pixel_waves + 1u);   // epochs only grow
-        return item % pixel_waves;
-    };
-    auto ask_for_chunk = [&](int k) {
-        const uint32_t s_hi = ((uint32_t)W - 1u - ((uint32_t)k * kRansChunk) / 3u) / strip_cols;
-        const bool fresh = follower && s_hi >= strips_asked;
-        wait_first = fresh ? strips_asked : 0u;
-        wait_end = fresh ? s_hi + 1u : 0u;
-        strips_asked = fresh ? wait_end : strips_asked;
-        uint64_t need;
-        const uint32_t w = fresh ? progress_slot(wait_first, need) : 0u;
-        seen = __hip_atomic_load(&progress[w], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    };
-    auto wait_for_asked = [&]() {
-        uint64_t have = seen;
-        for (uint32_t s = wait_first; s < wait_end; ++s) {
-            uint64_t need;
-            const uint32_t w = progress_slot(s, need);
-            uint32_t spins = 0;
-            while (have < need) {
-                if (++spins > spin_limit) { set_error(status, PCC_E_INTERNAL); break; }
-                __builtin_amdgcn_s_sleep(4);
-                have = __hip_atomic_load(&progress[w], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
-            have = 0;
-        }
-        wait_end = wait_first;
-    };
-    uint32_t staged[2][kPerLoader];
-    auto request = [&](int k, uint32_t (&staged)[kPerLoader]) {
+    using Staged = std::conditional_t<BESIDE, uint64_t, uint32_t>;
+    Staged staged[2][kPerLoader];
+    auto request = [&](int k, Staged (&staged)[kPerLoader]) __attribute__((always_inline)) {
 #pragma unroll
         for (int it = 0; it < kPerLoader; ++it) {
             const int e = tid - 128 + it * kLoaders;
@@ -435,16 +376,47 @@ rans_rows_kernel(const uint32_t* __restrict__ sf, int W, uint32_t rows, uint32_t
             // the compiler can count them, and waits for one register set while the other's loads are in flight
             const bool real = r < live_rows && idx < nsym;
             const size_t at = real ? (size_t)(row0 + r) * nsym + idx : 0;
-            staged[it] = BESIDE ? __hip_atomic_load(&sf[at], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : sf[at];
+            if constexpr (BESIDE) staged[it] = __hip_atomic_load(&sf_tagged[at], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            else staged[it] = sf[at];
         }
     };
-    auto deposit = [&](int k, const uint32_t (&staged)[kPerLoader]) {
+    auto deposit = [&](int k, Staged (&staged)[kPerLoader]) __attribute__((always_inline)) {
         const int b = k & 1;
+        if constexpr (BESIDE) {
+            // Symbols the pixel kernel has not written yet (seldom once the pixel kernel, the faster of the two, is
+            // ahead): the lane polls one of them, sleeping in between so that the polls of a coder that has
+            // caught up do not load the memory system, and then loads its whole set again, all loads at once.
+            // Every wait is bounded.
+            uint32_t spins = 0;
+            for (;;) {
+                size_t stale_at = 0;
+                bool stale = false;
+#pragma unroll
+                for (int it = 0; it < kPerLoader; ++it) {
+                    const int e = tid - 128 + it * kLoaders;
+                    const uint32_t r = (uint32_t)e / kRansChunk, i = (uint32_t)e % kRansChunk;
+                    const uint32_t idx = (uint32_t)k * kRansChunk + i;
+                    if (r < live_rows && idx < nsym && (uint32_t)(staged[it] >> 32) != epoch) {
+                        stale = true;
+                        stale_at = (size_t)(row0 + r) * nsym + idx;
+                    }
+                }
+                if (!stale) break;
+                bool gave_up = false;
+                while ((uint32_t)(__hip_atomic_load(&sf_tagged[stale_at], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >> 32) != epoch) {
+                    if (++spins > spin_limit) { set_error(status, PCC_E_INTERNAL); gave_up = true; break; }
+                    __builtin_amdgcn_s_sleep(32);
+                }
+                if (gave_up) break;
+                request(k, staged);
+            }
+        }
 #pragma unroll
         for (int it = 0; it < kPerLoader; ++it) {
             const int e = tid - 128 + it * kLoaders;
             const uint32_t r = (uint32_t)e / kRansChunk, i = (uint32_t)e % kRansChunk;
-            const uint32_t v = (r < live_rows && (uint32_t)k * kRansChunk + i < nsym) ? staged[it] : kRansNop;
+            const bool real = r < live_rows && (uint32_t)k * kRansChunk + i < nsym;
+            const uint32_t v = real ? (uint32_t)staged[it] : kRansNop;
             sym[b][r][i] = v;
             rcp[b][r][i] = rans_recip_below((v >> 16) + 1u);
         }
@@ -452,7 +424,7 @@ rans_rows_kernel(const uint32_t* __restrict__ sf, int W, uint32_t rows, uint32_t
     // wave 1: the words of a finished chunk from buffer b to the rows' slabs.  Lane = word index within the chunk
     // in both halves of the wave, the halves take the even and the odd rows: consecutive lanes write consecutive
     // words.  All LDS reads are issued before the first store.
-    auto flush = [&](int b) {
+    auto flush = [&](int b) __attribute__((always_inline)) {
         const uint32_t i = (uint32_t)(tid - 64) % kRansChunk, odd = (uint32_t)(tid - 64) / kRansChunk;
         uint32_t word[kRansRows / 2], meta[kRansRows / 2];
 #pragma unroll
@@ -467,21 +439,13 @@ rans_rows_kernel(const uint32_t* __restrict__ sf, int W, uint32_t rows, uint32_t
                 slabs[(size_t)(row0 + r) * sw + ((meta[it] >> 6) - 1u - i)] = word[it];
         }
     };
-    // The coding wave's serial chain sets the pace: it goes first wherever the compute unit's waves compete.
-    if (coder) {
-        rans_round_toward_zero();
-        __builtin_amdgcn_s_setprio(3);
-    }
+    if (coder) rans_round_toward_zero();
     // one round; P = the round's parity, which picks the loaders' register set
-    auto round = [&](int k, auto parity) {
+    auto round = [&](int k, auto parity) __attribute__((always_inline)) {
         constexpr int P = decltype(parity)::value;
         const int b = k & 1;
         if (loader) {
             if (k >= 1 && k - 1 < nchunks) deposit(k - 1, staged[P]);
-            if constexpr (BESIDE) {
-                wait_for_asked();                                 // what the last round asked for
-                ask_for_chunk(min(max(k - 5, 0), nchunks - 1));   // outside the chunks: asks again or for nothing
-            }
             request(min(max(k - 3, 0), nchunks - 1), staged[P]);     // outside the chunks: loads nobody uses
         } else if (storer) {
             if (k >= -1 && k + 1 < nchunks) flush(b ^ 1);
@@ -521,8 +485,8 @@ rans_rows_kernel(const uint32_t* __restrict__ sf, int W, uint32_t rows, uint32_t
         }
         lds_barrier();   // all that crosses threads here is in LDS; the loaders' global loads stay in flight
     };
-    // rounds nchunks + 4 (or + 5, for an even number of rounds) down to -1, where chunk 0's words are stored
-    for (int k = nchunks + 4 + (nchunks & 1); k >= 0; k -= 2) {
+    // rounds nchunks + 2 (or + 3, for an even number of rounds) down to -1, where chunk 0's words are stored
+    for (int k = nchunks + 2 + (nchunks & 1); k >= 0; k -= 2) {
         round(k, std::integral_constant<int, 0>());
         round(k - 1, std::integral_constant<int, 1>());
     }
@@ -585,6 +549,12 @@ compact_kernel(const uint32_t* __restrict__ slabs, const uint32_t* __restrict__ 
     const uint32_t* src = slabs + (size_t)row * sw + (sw - nw);
     uint32_t* dst = reinterpret_cast<uint32_t*>(stream + table + off);
     for (uint32_t i = threadIdx.x; i < nw; i += blockDim.x) dst[i] = src[i];
+}
+
+// test hook: the symbols of a tagged buffer without their epochs
+__global__ void __launch_bounds__(256)
+untag_kernel(const uint64_t* __restrict__ tagged, size_t count, uint32_t* __restrict__ out) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (size_t)gridDim.x * 256) out[i] = (uint32_t)tagged[i];
 }
 
 // scan_kernel and compact_kernel in one launch for jobs of few rows: every workgroup sums the sizes of the rows
@@ -1290,8 +1260,12 @@ struct pcc_ctx {
     // the row coder of a small job runs beside the pixel kernel, on a stream of its own
     bool overlap = true;
     hipStream_t side = nullptr;
-    uint64_t* d_progress = nullptr;   // kProgressBytes, zero at creation
-    uint32_t epoch = 0;               // of the last launch that used d_progress
+    // symbols handed from the pixel kernel to a row coder running beside it: epoch << 32 | start | (freq - 1) << 16.
+    // Zero when allocated and written by nothing else, so a word carries an epoch only if that launch wrote it.
+    uint64_t* d_tagged = nullptr;
+    size_t tagged_count = 0;
+    uint32_t epoch = 0;               // of the last launch that wrote d_tagged
+    bool last_tagged = false;         // the last encode left its symbols in d_tagged, not in d_sf
     // optional per-kernel timing
     bool profiling = false;
     hipEvent_t ev[2 * PCC_N_TIMINGS] = {};
@@ -1330,6 +1304,16 @@ int ensure_workspace(pcc_ctx* ctx, size_t bytes) {
     const size_t want = bytes + bytes / 8 + 4096;
     if (hipMalloc((void**)&ctx->d_ws, want) != hipSuccess) { (void)hipGetLastError(); return PCC_E_HIP; }
     ctx->ws_bytes = want;
+    return PCC_OK;
+}
+
+int ensure_tagged(pcc_ctx* ctx, size_t count) {
+    if (count <= ctx->tagged_count) return PCC_OK;
+    if (ctx->d_tagged) { (void)hipFree(ctx->d_tagged); ctx->d_tagged = nullptr; ctx->tagged_count = 0; }
+    const size_t want = count + count / 8 + 512;
+    if (hipMalloc((void**)&ctx->d_tagged, want * sizeof(uint64_t)) != hipSuccess) { (void)hipGetLastError(); return PCC_E_HIP; }
+    if (hipMemset(ctx->d_tagged, 0, want * sizeof(uint64_t)) != hipSuccess) { (void)hipGetLastError(); return PCC_E_HIP; }
+    ctx->tagged_count = want;
     return PCC_OK;
 }
 
@@ -1483,37 +1467,37 @@ uint32_t encode_blocks(const pcc_ctx* ctx, int n, int H, int W, uint32_t reserve
     return blocks > cus ? cus : (uint32_t)blocks;   // persistent: one workgroup per CU, looping over the items
 }
 
-// progress: see encode_kernel; one word per wave of the grid
+// sf_tagged: see encode_kernel
 template <class Net>
 int launch_encode(pcc_ctx* ctx, const uint8_t* d_img, int n, int H, int W, uint32_t* sf, float* params, float* bits,
-                  uint64_t* progress, uint32_t reserve_cus, hipStream_t st) {
+                  uint64_t* sf_tagged, uint32_t reserve_cus, hipStream_t st) {
     constexpr int kLds = Layout<Net>::kModelBytes;
     const uint32_t blocks = encode_blocks(ctx, n, H, W, reserve_cus);
     switch (ctx->encode_variant) {
         case 0:
             hipLaunchKernelGGL((encode_kernel<Net, 1, 512>), dim3(blocks), dim3(512), kLds, st, ctx->d_model, d_img, n, H, W,
-                               sf, params, bits, ctx->d_status, progress, ctx->epoch);
+                               sf, params, bits, ctx->d_status, sf_tagged, ctx->epoch);
             break;
         case 1:
             hipLaunchKernelGGL((encode_kernel<Net, 2, 512>), dim3(blocks), dim3(512), kLds, st, ctx->d_model, d_img, n, H, W,
-                               sf, params, bits, ctx->d_status, progress, ctx->epoch);
+                               sf, params, bits, ctx->d_status, sf_tagged, ctx->epoch);
             break;
         case 2:
             hipLaunchKernelGGL((encode_kernel<Net, 1, 1024>), dim3(blocks), dim3(1024), kLds, st, ctx->d_model, d_img, n, H, W,
-                               sf, params, bits, ctx->d_status, progress, ctx->epoch);
+                               sf, params, bits, ctx->d_status, sf_tagged, ctx->epoch);
             break;
         default:
             hipLaunchKernelGGL((encode_kernel<Net, 4, 256>), dim3(blocks), dim3(256), kLds, st, ctx->d_model, d_img, n, H, W,
-                               sf, params, bits, ctx->d_status, progress, ctx->epoch);
+                               sf, params, bits, ctx->d_status, sf_tagged, ctx->epoch);
             break;
     }
     return hipGetLastError() == hipSuccess ? PCC_OK : PCC_E_HIP;
 }
 
 int launch_encode_any(pcc_ctx* ctx, const uint8_t* d_img, int n, int H, int W, uint32_t* sf, float* params, float* bits,
-                      uint64_t* progress, uint32_t reserve_cus, hipStream_t st) {
+                      uint64_t* sf_tagged, uint32_t reserve_cus, hipStream_t st) {
     return with_net(ctx->net, [&](auto net) {
-        return launch_encode<decltype(net)>(ctx, d_img, n, H, W, sf, params, bits, progress, reserve_cus, st);
+        return launch_encode<decltype(net)>(ctx, d_img, n, H, W, sf, params, bits, sf_tagged, reserve_cus, st);
     });
 }
 
@@ -1602,8 +1586,6 @@ int pcc_create(pcc_ctx** out, const void* h_blob, size_t blob_bytes, int hip_dev
     }
     if (const char* e = getenv("PCC_ENCODE_OVERLAP")) ctx->overlap = atoi(e) != 0;
     ok = ok && hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking) == hipSuccess;
-    ok = ok && hipMalloc((void**)&ctx->d_progress, kProgressBytes) == hipSuccess;
-    ok = ok && hipMemset(ctx->d_progress, 0, kProgressBytes) == hipSuccess;
     if (!ok) { (void)hipGetLastError(); pcc_destroy(ctx); return PCC_E_HIP; }
     ctx->d_total = reinterpret_cast<uint64_t*>(ctx->d_status + kStWords);
     *out = ctx;
@@ -1618,7 +1600,7 @@ void pcc_destroy(pcc_ctx* ctx) {
     if (ctx->d_status) (void)hipFree(ctx->d_status);
     if (ctx->h_status) (void)hipHostFree(ctx->h_status);
     for (hipEvent_t e : ctx->ev) if (e) (void)hipEventDestroy(e);
-    if (ctx->d_progress) (void)hipFree(ctx->d_progress);
+    if (ctx->d_tagged) (void)hipFree(ctx->d_tagged);
     if (ctx->side) (void)hipStreamDestroy(ctx->side);
     delete ctx;
 }
@@ -1661,8 +1643,6 @@ int pcc_encode(pcc_ctx* ctx, const uint8_t* d_img, int n, int H, int W, uint8_t*
     const size_t sf_bytes = align_up(P * 3 * sizeof(uint32_t), 256);
     const size_t slab_bytes = align_up((size_t)rows * slab_words(W) * 4, 256);
     const size_t rw_bytes = align_up((size_t)rows * 4, 256);
-    const EncodeVariant variant = kEncodeVariants[ctx->encode_variant];
-    const uint32_t strip_cols = 16u * variant.tiles;
     int rc = ensure_workspace(ctx, sf_bytes + slab_bytes + rw_bytes);
     if (rc != PCC_OK) return rc;
     uint32_t* d_sf = reinterpret_cast<uint32_t*>(ctx->d_ws);
@@ -1674,30 +1654,31 @@ int pcc_encode(pcc_ctx* ctx, const uint8_t* d_img, int n, int H, int W, uint8_t*
     // A small job's row coder is a handful of workgroups bound by the latency of their serial chains.  It runs
     // beside the pixel kernel, on compute units the pixel kernel's grid leaves free (a pixel workgroup fills a
     // unit's LDS, so the workgroups of both kernels are resident whatever order the dispatcher takes them in),
-    // and follows the pixel kernel's progress words.  The row coder and what comes after it go to a stream of
+    // and takes each symbol when it finds it written.  The row coder and what comes after it go to a stream of
     // the context's own; nothing orders that stream after the caller's, so this is only done when the caller's
     // stream is idle and the pixel kernel starts at once.  A large job's row coder needs the whole chip and
     // runs after the pixel kernel, on the caller's stream.
     const uint32_t groups = (rows + kRansRows - 1) / kRansRows;
     const uint32_t cus = ctx->num_cus > 0 ? (uint32_t)ctx->num_cus : 256u;
-    bool beside = ctx->overlap && groups <= kRansBesideMaxGroups && cus >= 4 * kRansBesideMaxGroups && cus <= kMaxCus;
+    bool beside = ctx->overlap && groups <= kRansBesideMaxGroups && cus >= 4 * kRansBesideMaxGroups;
     if (beside) {
         const hipError_t busy = hipStreamQuery(st);
         if (busy != hipSuccess) { (void)hipGetLastError(); beside = false; }
     }
-    uint64_t* progress = nullptr;
     if (beside) {
-        if (++ctx->epoch == 0) {      // wrapped: the words of old launches would look finished
-            if (hipMemset(ctx->d_progress, 0, kProgressBytes) != hipSuccess) return PCC_E_HIP;
+        rc = ensure_tagged(ctx, (size_t)P * 3);
+        if (rc != PCC_OK) return rc;
+        if (++ctx->epoch == 0) {      // wrapped: the words of old launches would pass for new ones
+            if (hipMemset(ctx->d_tagged, 0, ctx->tagged_count * sizeof(uint64_t)) != hipSuccess) return PCC_E_HIP;
             ctx->epoch = 1;
         }
-        progress = ctx->d_progress;
     }
+    ctx->last_tagged = beside;
+    uint64_t* d_tagged = beside ? ctx->d_tagged : nullptr;
     // Workgroups go to the chip's eight dies in turn and stay there: a die must have room for its share of both
     // kernels, or a pixel workgroup waits for a compute unit until others of its die have ended and then works
     // through its share of the items alone.
     const uint32_t reserve = beside ? kXcds * ((groups + kXcds - 1) / kXcds) : 0u;
-    const uint32_t pixel_waves = encode_blocks(ctx, n, H, W, reserve) * (variant.threads / 64);
     hipStream_t tail = beside ? ctx->side : st;
 
     if (hipMemsetAsync(ctx->d_status, 0, kStWords * sizeof(int) + sizeof(uint64_t), st) != hipSuccess) return PCC_E_HIP;
@@ -1705,17 +1686,17 @@ int pcc_encode(pcc_ctx* ctx, const uint8_t* d_img, int n, int H, int W, uint8_t*
     auto launch_rans = [&]() {
         prof_begin(ctx, PCC_T_ENCODE_RANS, tail);
         if (beside)
-            hipLaunchKernelGGL(rans_rows_kernel<true>, dim3(groups), dim3(kRansThreads), 0, tail, d_sf, W, rows, d_slabs, d_rw,
-                               progress, ctx->epoch, pixel_waves, strip_cols, ctx->d_status, kRansSpinLimit);
+            hipLaunchKernelGGL(rans_rows_kernel<true>, dim3(groups), dim3(kRansThreads), 0, tail, d_sf, d_tagged, ctx->epoch, W,
+                               rows, d_slabs, d_rw, ctx->d_status, kRansSpinLimit);
         else
-            hipLaunchKernelGGL(rans_rows_kernel<false>, dim3(groups), dim3(kRansThreads), 0, tail, d_sf, W, rows, d_slabs, d_rw,
-                               progress, ctx->epoch, pixel_waves, strip_cols, ctx->d_status, kRansSpinLimit);
+            hipLaunchKernelGGL(rans_rows_kernel<false>, dim3(groups), dim3(kRansThreads), 0, tail, d_sf, d_tagged, ctx->epoch, W,
+                               rows, d_slabs, d_rw, ctx->d_status, kRansSpinLimit);
         prof_end(ctx, PCC_T_ENCODE_RANS, tail);
     };
     // beside: the row coder goes first and is in place, polling, when the pixel kernel starts
     if (beside) launch_rans();
     prof_begin(ctx, PCC_T_ENCODE_PIXELS, st);
-    rc = launch_encode_any(ctx, d_img, n, H, W, d_sf, nullptr, nullptr, progress, reserve, st);
+    rc = launch_encode_any(ctx, d_img, n, H, W, beside ? nullptr : d_sf, nullptr, nullptr, d_tagged, reserve, st);
     if (rc != PCC_OK) {
         if (beside) (void)hipStreamSynchronize(ctx->side);   // the row coder gives up once its polls run out
         return rc;
@@ -1826,6 +1807,11 @@ int pcc_copy_intervals(pcc_ctx* ctx, uint32_t* d_out, size_t count, void* hip_st
     if (!ctx->d_sf || count != ctx->sf_count) return PCC_E_ARG;
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return PCC_E_HIP;
+    if (ctx->last_tagged) {
+        const uint32_t blocks = (uint32_t)((count + 255) / 256 < 4096 ? (count + 255) / 256 : 4096);
+        hipLaunchKernelGGL(untag_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)hip_stream, ctx->d_tagged, count, d_out);
+        return hipGetLastError() == hipSuccess ? PCC_OK : PCC_E_HIP;
+    }
     if (hipMemcpyAsync(d_out, ctx->d_sf, count * sizeof(uint32_t), hipMemcpyDeviceToDevice, (hipStream_t)hip_stream) !=
         hipSuccess) return PCC_E_HIP;
     return PCC_OK;
