@@ -47,6 +47,14 @@ constexpr int kDefaultEncodeVariant = 1;
 
 // status words in device memory
 enum { kStErr = 0, kStAbort = 1, kStTicket = 2, kStWords = 4 };
+// The status block: kStWords ints that every call clears on its stream before its kernels, the 64-bit stream
+// size, and two ints that only a row coder running beside the pixel kernel writes (stood down; wait ran out).
+// That row coder runs on another stream than the clearing, so its words are cleared after they have been read,
+// at the end of the call, and are zero whenever a call begins.
+constexpr size_t kStCleared = kStWords * sizeof(int) + sizeof(uint64_t);
+constexpr int kStSide = (int)(kStCleared / sizeof(int));     // index of the first of the two side words
+enum { kSideDefer = 0, kSideErr = 1 };
+constexpr size_t kStBytes = kStCleared + 2 * sizeof(int);
 
 __host__ __device__ inline size_t slab_words(int W) { return (6 * (size_t)W + 16) / 4 + 1; }
 
@@ -278,6 +286,7 @@ constexpr int kRansThreads = 256;
 constexpr uint32_t kRansBesideMaxGroups = 48;      // row-coder workgroups that may run beside the pixel kernel
 constexpr uint32_t kXcds = 8;
 constexpr uint32_t kRansSpinLimit = 1u << 22;       // polls for one symbol before the row coder gives up (seconds)
+constexpr uint32_t kRansFirstPolls = 1024;          // ... before it has seen the pixel kernel's first symbol (a few ms)
 // Padding symbol (start 0, frequency 2^16): pushing it leaves the state unchanged
 // and never renormalises, so every chunk can be coded as a full one.
 constexpr uint32_t kRansNop = 0xFFFF0000u;
@@ -331,12 +340,14 @@ __device__ __forceinline__ void lds_barrier() {
 template <bool BESIDE>
 __global__ void __launch_bounds__(kRansThreads)
 rans_rows_kernel(const uint32_t* __restrict__ sf, const uint64_t* sf_tagged, uint32_t epoch, int W, uint32_t rows,
-                 uint32_t* __restrict__ slabs, uint32_t* __restrict__ row_words, int* status, uint32_t spin_limit) {
+                 uint32_t* __restrict__ slabs, uint32_t* __restrict__ row_words, int* status, uint32_t first_limit,
+                 uint32_t spin_limit) {
     // [buffer][row][symbol of the chunk]; the odd row strides keep the coding wave's column accesses off shared banks
     __shared__ uint32_t sym[2][kRansRows][kRansChunk + 1];
     __shared__ double rcp[2][kRansRows][kRansChunk + 1];
     // renormalisation words the coding wave produced in a chunk, in the order produced
     __shared__ uint32_t outw[2][kRansRows][kRansChunk + 1];
+    __shared__ uint32_t abandon;                // set by a loader whose wait ran out: every wave leaves after the round
     __shared__ uint32_t outmeta[2][kRansRows];  // the row's slab position (words) before the chunk << 6 | words produced in it
     const int tid = threadIdx.x, lane = tid & 63;
     const bool coder = tid < 64;
@@ -366,6 +377,7 @@ rans_rows_kernel(const uint32_t* __restrict__ sf, const uint64_t* sf_tagged, uin
     //   round k - 1  the words it produced are copied to the rows' slabs
     using Staged = std::conditional_t<BESIDE, uint64_t, uint32_t>;
     Staged staged[2][kPerLoader];
+    bool seen_symbols = false;      // this lane's first wait for the pixel kernel is over
     auto request = [&](int k, Staged (&staged)[kPerLoader]) __attribute__((always_inline)) {
 #pragma unroll
         for (int it = 0; it < kPerLoader; ++it) {
@@ -386,8 +398,12 @@ rans_rows_kernel(const uint32_t* __restrict__ sf, const uint64_t* sf_tagged, uin
             // Symbols the pixel kernel has not written yet (seldom once the pixel kernel, the faster of the two, is
             // ahead): the lane polls one of them, sleeping in between so that the polls of a coder that has
             // caught up do not load the memory system, and then loads its whole set again, all loads at once.
-            // Every wait is bounded.
+            // Every wait is bounded.  The first one is short: if nothing has appeared by then the pixel kernel
+            // is not running beside this one (something runs the process's kernels one at a time, or the chip
+            // is taken), and the row coder stands down; the host launches it again after the pixel kernel.
+            // Once symbols have been seen the pixel kernel is on the chip and the bound is only a safeguard.
             uint32_t spins = 0;
+            const uint32_t limit = seen_symbols ? spin_limit : first_limit;
             for (;;) {
                 size_t stale_at = 0;
                 bool stale = false;
@@ -404,12 +420,18 @@ rans_rows_kernel(const uint32_t* __restrict__ sf, const uint64_t* sf_tagged, uin
                 if (!stale) break;
                 bool gave_up = false;
                 while ((uint32_t)(__hip_atomic_load(&sf_tagged[stale_at], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >> 32) != epoch) {
-                    if (++spins > spin_limit) { set_error(status, PCC_E_INTERNAL); gave_up = true; break; }
+                    if (++spins > limit) { gave_up = true; break; }
                     __builtin_amdgcn_s_sleep(32);
                 }
-                if (gave_up) break;
+                if (gave_up) {
+                    __hip_atomic_store(&status[kStSide + (seen_symbols ? kSideErr : kSideDefer)], 1, __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+                    abandon = 1;
+                    break;
+                }
                 request(k, staged);
             }
+            seen_symbols = true;
         }
 #pragma unroll
         for (int it = 0; it < kPerLoader; ++it) {
@@ -439,6 +461,8 @@ rans_rows_kernel(const uint32_t* __restrict__ sf, const uint64_t* sf_tagged, uin
                 slabs[(size_t)(row0 + r) * sw + ((meta[it] >> 6) - 1u - i)] = word[it];
         }
     };
+    if (tid == 0) abandon = 0;
+    lds_barrier();
     if (coder) rans_round_toward_zero();
     // one round; P = the round's parity, which picks the loaders' register set
     auto round = [&](int k, auto parity) __attribute__((always_inline)) {
@@ -484,11 +508,14 @@ rans_rows_kernel(const uint32_t* __restrict__ sf, const uint64_t* sf_tagged, uin
             wp -= cnt;
         }
         lds_barrier();   // all that crosses threads here is in LDS; the loaders' global loads stay in flight
+        return !BESIDE || abandon == 0;
     };
     // rounds nchunks + 2 (or + 3, for an even number of rounds) down to -1, where chunk 0's words are stored
     for (int k = nchunks + 2 + (nchunks & 1); k >= 0; k -= 2) {
-        round(k, std::integral_constant<int, 0>());
-        round(k - 1, std::integral_constant<int, 1>());
+        if (!round(k, std::integral_constant<int, 0>()) || !round(k - 1, std::integral_constant<int, 1>())) {
+            if (coder && row < rows) row_words[row] = 0;    // stood down: nothing for the compaction to copy
+            return;
+        }
     }
     if (coder && row < rows) {
         uint32_t* slab = slabs + (size_t)row * sw;
@@ -542,6 +569,10 @@ compact_kernel(const uint32_t* __restrict__ slabs, const uint32_t* __restrict__ 
     const uint64_t table = (uint64_t)kStreamHeader + 8ull * (rows + 1);
     const uint64_t off = reinterpret_cast<const uint64_t*>(stream + kStreamHeader)[row];
     const uint32_t nw = row_words[row];
+    if (nw > sw) {                                // not a row coder's count: never read outside the slab
+        if (threadIdx.x == 0) set_error(status, PCC_E_INTERNAL);
+        return;
+    }
     if (table + off + 4ull * nw > cap_bytes) {
         if (threadIdx.x == 0) set_error(status, PCC_E_CAP);
         return;
@@ -594,6 +625,10 @@ compact_scan_kernel(const uint32_t* __restrict__ slabs, const uint32_t* __restri
             offsets[rows] = off + 4ull * nw;
             *total_bytes = table + off + 4ull * nw;
         }
+    }
+    if (nw > sw) {                                // not a row coder's count: never read outside the slab
+        if (threadIdx.x == 0) set_error(status, PCC_E_INTERNAL);
+        return;
     }
     if (table + off + 4ull * nw > cap_bytes) {
         if (threadIdx.x == 0) set_error(status, PCC_E_CAP);
@@ -1259,6 +1294,7 @@ struct pcc_ctx {
     int encode_variant = kDefaultEncodeVariant;
     // the row coder of a small job runs beside the pixel kernel, on a stream of its own
     bool overlap = true;
+    uint32_t first_polls = kRansFirstPolls;   // the row coder's patience before the pixel kernel's first symbol
     hipStream_t side = nullptr;
     // symbols handed from the pixel kernel to a row coder running beside it: epoch << 32 | start | (freq - 1) << 16.
     // Zero when allocated and written by nothing else, so a word carries an epoch only if that launch wrote it.
@@ -1576,8 +1612,9 @@ int pcc_create(pcc_ctx** out, const void* h_blob, size_t blob_bytes, int hip_dev
     bool ok = hipGetDeviceProperties(&prop, hip_device) == hipSuccess;
     if (ok) ctx->num_cus = prop.multiProcessorCount;
     ok = ok && hipMalloc((void**)&ctx->d_model, image.size()) == hipSuccess;
-    ok = ok && hipMalloc((void**)&ctx->d_status, kStWords * sizeof(int) + sizeof(uint64_t)) == hipSuccess;
-    ok = ok && hipHostMalloc((void**)&ctx->h_status, kStWords * sizeof(int) + sizeof(uint64_t), hipHostMallocDefault) == hipSuccess;
+    ok = ok && hipMalloc((void**)&ctx->d_status, kStBytes) == hipSuccess;
+    ok = ok && hipMemset(ctx->d_status, 0, kStBytes) == hipSuccess;
+    ok = ok && hipHostMalloc((void**)&ctx->h_status, kStBytes, hipHostMallocDefault) == hipSuccess;
     ok = ok && hipMemcpy(ctx->d_model, image.data(), image.size(), hipMemcpyHostToDevice) == hipSuccess;
     ok = ok && with_net(net, [](auto tag) { return set_kernel_attributes<decltype(tag)>(); });
     if (const char* e = getenv("PCC_ENCODE_VARIANT")) {
@@ -1585,6 +1622,7 @@ int pcc_create(pcc_ctx** out, const void* h_blob, size_t blob_bytes, int hip_dev
         if (v >= 0 && v < 4) ctx->encode_variant = v;
     }
     if (const char* e = getenv("PCC_ENCODE_OVERLAP")) ctx->overlap = atoi(e) != 0;
+    if (const char* e = getenv("PCC_RANS_FIRST_POLLS")) ctx->first_polls = (uint32_t)atoi(e);
     ok = ok && hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking) == hipSuccess;
     if (!ok) { (void)hipGetLastError(); pcc_destroy(ctx); return PCC_E_HIP; }
     ctx->d_total = reinterpret_cast<uint64_t*>(ctx->d_status + kStWords);
@@ -1679,52 +1717,69 @@ int pcc_encode(pcc_ctx* ctx, const uint8_t* d_img, int n, int H, int W, uint8_t*
     // kernels, or a pixel workgroup waits for a compute unit until others of its die have ended and then works
     // through its share of the items alone.
     const uint32_t reserve = beside ? kXcds * ((groups + kXcds - 1) / kXcds) : 0u;
-    hipStream_t tail = beside ? ctx->side : st;
 
-    if (hipMemsetAsync(ctx->d_status, 0, kStWords * sizeof(int) + sizeof(uint64_t), st) != hipSuccess) return PCC_E_HIP;
+    if (hipMemsetAsync(ctx->d_status, 0, kStCleared, st) != hipSuccess) return PCC_E_HIP;
     prof_reset(ctx);
-    auto launch_rans = [&]() {
-        prof_begin(ctx, PCC_T_ENCODE_RANS, tail);
+    const uint32_t tag = with_net(ctx->net, [](auto net) { return model_tag<decltype(net)>(); });
+    auto launch_rans = [&](hipStream_t s, uint32_t first_polls) {
+        prof_begin(ctx, PCC_T_ENCODE_RANS, s);
         if (beside)
-            hipLaunchKernelGGL(rans_rows_kernel<true>, dim3(groups), dim3(kRansThreads), 0, tail, d_sf, d_tagged, ctx->epoch, W,
-                               rows, d_slabs, d_rw, ctx->d_status, kRansSpinLimit);
+            hipLaunchKernelGGL(rans_rows_kernel<true>, dim3(groups), dim3(kRansThreads), 0, s, d_sf, d_tagged, ctx->epoch, W,
+                               rows, d_slabs, d_rw, ctx->d_status, first_polls, kRansSpinLimit);
         else
-            hipLaunchKernelGGL(rans_rows_kernel<false>, dim3(groups), dim3(kRansThreads), 0, tail, d_sf, d_tagged, ctx->epoch, W,
-                               rows, d_slabs, d_rw, ctx->d_status, kRansSpinLimit);
-        prof_end(ctx, PCC_T_ENCODE_RANS, tail);
+            hipLaunchKernelGGL(rans_rows_kernel<false>, dim3(groups), dim3(kRansThreads), 0, s, d_sf, d_tagged, ctx->epoch, W,
+                               rows, d_slabs, d_rw, ctx->d_status, first_polls, kRansSpinLimit);
+        prof_end(ctx, PCC_T_ENCODE_RANS, s);
     };
-    // beside: the row coder goes first and is in place, polling, when the pixel kernel starts
-    if (beside) launch_rans();
+    // what follows the row coder, and the wait for it
+    auto finish = [&](hipStream_t s) -> int {
+        if (rows <= kCompactScanMaxRows) {
+            prof_begin(ctx, PCC_T_ENCODE_COMPACT, s);
+            hipLaunchKernelGGL(compact_scan_kernel, dim3(rows), dim3(kCompactScanThreads), 0, s, d_slabs, d_rw, n, H, W, rows,
+                               tag, ctx->dist, d_stream, (uint64_t)cap_bytes, ctx->d_total, ctx->d_status);
+            prof_end(ctx, PCC_T_ENCODE_COMPACT, s);
+        } else {
+            prof_begin(ctx, PCC_T_ENCODE_SCAN, s);
+            hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), 0, s, d_rw, rows, n, H, W, tag, ctx->dist, d_stream, ctx->d_total);
+            prof_end(ctx, PCC_T_ENCODE_SCAN, s);
+            prof_begin(ctx, PCC_T_ENCODE_COMPACT, s);
+            hipLaunchKernelGGL(compact_kernel, dim3(rows), dim3(64), 0, s, d_slabs, d_rw, W, rows, d_stream,
+                               (uint64_t)cap_bytes, ctx->d_status);
+            prof_end(ctx, PCC_T_ENCODE_COMPACT, s);
+        }
+        if (hipGetLastError() != hipSuccess) return PCC_E_HIP;
+        if (hipMemcpyAsync(ctx->h_status, ctx->d_status, kStBytes, hipMemcpyDeviceToHost, s) != hipSuccess) return PCC_E_HIP;
+        if (beside && hipMemsetAsync(ctx->d_status + kStSide, 0, 2 * sizeof(int), s) != hipSuccess) return PCC_E_HIP;
+        if (hipStreamSynchronize(s) != hipSuccess) { (void)hipGetLastError(); return PCC_E_HIP; }
+        return PCC_OK;
+    };
+    // Beside: the row coder goes first, so that it is in place when the pixel kernel's first symbols appear (its
+    // launch would otherwise come that much later, and it is the longer of the two).
+    if (beside) launch_rans(ctx->side, ctx->first_polls);
     prof_begin(ctx, PCC_T_ENCODE_PIXELS, st);
     rc = launch_encode_any(ctx, d_img, n, H, W, beside ? nullptr : d_sf, nullptr, nullptr, d_tagged, reserve, st);
     if (rc != PCC_OK) {
-        if (beside) (void)hipStreamSynchronize(ctx->side);   // the row coder gives up once its polls run out
+        if (beside) (void)hipStreamSynchronize(ctx->side);   // the row coder stands down after its first, short wait
         return rc;
     }
     prof_end(ctx, PCC_T_ENCODE_PIXELS, st);
-    if (!beside) launch_rans();
-    const uint32_t tag = with_net(ctx->net, [](auto net) { return model_tag<decltype(net)>(); });
-    if (rows <= kCompactScanMaxRows) {
-        prof_begin(ctx, PCC_T_ENCODE_COMPACT, tail);
-        hipLaunchKernelGGL(compact_scan_kernel, dim3(rows), dim3(kCompactScanThreads), 0, tail, d_slabs, d_rw, n, H, W, rows,
-                           tag, ctx->dist, d_stream, (uint64_t)cap_bytes, ctx->d_total, ctx->d_status);
-        prof_end(ctx, PCC_T_ENCODE_COMPACT, tail);
-    } else {
-        prof_begin(ctx, PCC_T_ENCODE_SCAN, tail);
-        hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), 0, tail, d_rw, rows, n, H, W, tag, ctx->dist, d_stream, ctx->d_total);
-        prof_end(ctx, PCC_T_ENCODE_SCAN, tail);
-        prof_begin(ctx, PCC_T_ENCODE_COMPACT, tail);
-        hipLaunchKernelGGL(compact_kernel, dim3(rows), dim3(64), 0, tail, d_slabs, d_rw, W, rows, d_stream,
-                           (uint64_t)cap_bytes, ctx->d_status);
-        prof_end(ctx, PCC_T_ENCODE_COMPACT, tail);
+    if (!beside) launch_rans(st, 0);
+    rc = finish(beside ? ctx->side : st);
+    if (rc != PCC_OK) return rc;
+    if (beside) {
+        // the row coder ends after the pixel kernel's last store; the caller's stream is waited for as well, so
+        // that the pixel kernel has retired when this returns
+        if (hipStreamSynchronize(st) != hipSuccess) { (void)hipGetLastError(); return PCC_E_HIP; }
+        if (ctx->h_status[kStSide + kSideErr] != 0) return PCC_E_INTERNAL;
+        if (ctx->h_status[kStErr] == 0 && ctx->h_status[kStSide + kSideDefer] != 0) {
+            // The row coder saw nothing of the pixel kernel and stood down: the two did not run side by side.
+            // The symbols are all there now; code them on the caller's stream.
+            if (hipMemsetAsync(ctx->d_status, 0, kStCleared, st) != hipSuccess) return PCC_E_HIP;
+            launch_rans(st, kRansSpinLimit);
+            rc = finish(st);
+            if (rc != PCC_OK) return rc;
+        }
     }
-    if (hipGetLastError() != hipSuccess) return PCC_E_HIP;
-    if (hipMemcpyAsync(ctx->h_status, ctx->d_status, kStWords * sizeof(int) + sizeof(uint64_t), hipMemcpyDeviceToHost,
-                       tail) != hipSuccess) return PCC_E_HIP;
-    // the row coder ends after the pixel kernel's last store; the caller's stream is waited for as well so that
-    // the pixel kernel has retired when this returns
-    if (hipStreamSynchronize(tail) != hipSuccess) { (void)hipGetLastError(); return PCC_E_HIP; }
-    if (beside && hipStreamSynchronize(st) != hipSuccess) { (void)hipGetLastError(); return PCC_E_HIP; }
     prof_collect(ctx);
     if (ctx->h_status[kStErr] != 0) return ctx->h_status[kStErr];
     uint64_t total;
@@ -1750,7 +1805,7 @@ int pcc_decode(pcc_ctx* ctx, const uint8_t* d_stream, size_t nbytes, int n, int 
     if (rc != PCC_OK) return rc;
     ctx->d_sf = nullptr; ctx->sf_count = 0;
     uint32_t* d_mail = reinterpret_cast<uint32_t*>(ctx->d_ws);
-    if (hipMemsetAsync(ctx->d_status, 0, kStWords * sizeof(int) + sizeof(uint64_t), st) != hipSuccess) return PCC_E_HIP;
+    if (hipMemsetAsync(ctx->d_status, 0, kStCleared, st) != hipSuccess) return PCC_E_HIP;
     if (hipMemsetAsync(d_mail, 0, mail_bytes, st) != hipSuccess) return PCC_E_HIP;
     const uint32_t spin_limit = 1u << 22;
     prof_reset(ctx);

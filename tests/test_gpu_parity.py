@@ -418,8 +418,9 @@ def test_roundtrip_random_shapes(codec, codec_sharp, paper_blob, diagonal_blob):
 
 
 def test_row_coder_beside_after_and_busy_stream_agree(blob, paper_blob, monkeypatch):
-    """The row coder of a small job runs beside the pixel kernel, that of a large job or of a caller whose stream
-    has work pending runs after it: all three must write the same bytes (and bytes the oracle-coded rows give
+    """The row coder of a small job runs beside the pixel kernel; that of a large job, of a caller whose stream
+    has work pending, or one that stood down because it saw nothing of the pixel kernel, runs after it: all must
+    write the same bytes (and bytes the oracle-coded rows give
     are covered by the container tests)."""
     from paper_2212_01185_amd import binding
     rng = np.random.default_rng(23)
@@ -429,12 +430,18 @@ def test_row_coder_beside_after_and_busy_stream_agree(blob, paper_blob, monkeypa
         monkeypatch.setenv("PCC_ENCODE_OVERLAP", "0")
         after = binding.Codec(b, 0)
         monkeypatch.delenv("PCC_ENCODE_OVERLAP")
+        # no patience at all: the row coder stands down at the first symbol it does not find, and the host
+        # launches it again after the pixel kernel (what happens where kernels are run one at a time)
+        monkeypatch.setenv("PCC_RANS_FIRST_POLLS", "0")
+        impatient = binding.Codec(b, 0)
+        monkeypatch.delenv("PCC_RANS_FIRST_POLLS")
         try:
             for n, h, w in shapes:
                 _log("row coder beside/after %s %dx%dx%d" % (name, n, h, w))
                 imgs = _dev(rng.integers(0, 256, (n, h, w, 3), dtype=np.uint8))
                 want = after.pcc_encode(imgs).cpu().numpy().tobytes()
                 assert beside.pcc_encode(imgs).cpu().numpy().tobytes() == want
+                assert impatient.pcc_encode(imgs).cpu().numpy().tobytes() == want
                 # pending work on the caller's stream: the encode must order itself behind it
                 big = torch.ones(1 << 27, device="cuda")
                 for _ in range(16):
@@ -444,3 +451,4 @@ def test_row_coder_beside_after_and_busy_stream_agree(blob, paper_blob, monkeypa
         finally:
             beside.close()
             after.close()
+            impatient.close()
