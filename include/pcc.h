@@ -105,7 +105,11 @@ int pcc_encode_probs(pcc_ctx *ctx, const uint8_t *d_img, int n, int H, int W,
 /* Encoder (Sec. IV-C first paragraph): parameters for all pixels in parallel,
  * integer CDF values of the true sub-pixels, row-wise rANS, stream assembly.
  * Writes at most cap_bytes to d_stream and the byte count to *h_nbytes_out.
- * Synchronises hip_stream before returning (the size is read back). */
+ * Synchronises hip_stream before returning (the size is read back).  When
+ * hip_stream is idle at the call and the job has at most 3072 rows, the row
+ * coder and the stream assembly run on a stream the ctx owns, beside the
+ * pixel kernel; both streams have been waited for when the call returns, so
+ * the caller's view is the same.  One call at a time per ctx. */
 int pcc_encode(pcc_ctx *ctx, const uint8_t *d_img, int n, int H, int W,
                uint8_t *d_stream, size_t cap_bytes, size_t *h_nbytes_out, void *hip_stream);
 
