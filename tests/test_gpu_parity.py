@@ -425,6 +425,9 @@ def test_row_coder_beside_after_and_busy_stream_agree(blob, paper_blob, monkeypa
     from paper_2212_01185_amd import binding
     rng = np.random.default_rng(23)
     shapes = [(1, 70, 45), (3, 33, 100), (1, 130, 1), (1, 64, 11), (2, 200, 37), (1, 1, 300)]
+    # either side of the most rows the row coder takes beside the pixel kernel (48 groups of 64), and of the most
+    # rows whose sizes the compaction sums by itself (4096)
+    shapes += [(1, 3072, 5), (1, 3073, 5), (2, 2048, 3), (1, 4097, 3)]
     for name, b in (("workload", blob), ("paper", paper_blob)):
         beside = binding.Codec(b, 0)
         monkeypatch.setenv("PCC_ENCODE_OVERLAP", "0")
@@ -442,6 +445,8 @@ def test_row_coder_beside_after_and_busy_stream_agree(blob, paper_blob, monkeypa
                 want = after.pcc_encode(imgs).cpu().numpy().tobytes()
                 assert beside.pcc_encode(imgs).cpu().numpy().tobytes() == want
                 assert impatient.pcc_encode(imgs).cpu().numpy().tobytes() == want
+                got = after.pcc_decode(_dev(np.frombuffer(want, dtype=np.uint8).copy()), n, h, w)
+                assert torch.equal(got, imgs), "round trip"
                 # pending work on the caller's stream: the encode must order itself behind it
                 big = torch.ones(1 << 27, device="cuda")
                 for _ in range(16):
