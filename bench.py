@@ -142,6 +142,24 @@ def main():
     t1 = time.perf_counter()
     assert torch.equal(d_out, d_img), "round trip is not lossless"
 
+    # the third entry point of the boundary, outside the step: raw head outputs and bits of every pixel
+    # (3 B read, 4 * (head outputs + 1) B written per pixel; an HBM-side figure)
+    d_params = torch.empty((n, h, w, codec.head_outputs), dtype=torch.float32, device="cuda")
+    d_bits = torch.empty((n, h, w), dtype=torch.float32, device="cuda")
+    lib = binding.load()
+    st = torch.cuda.current_stream().cuda_stream
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    probs_reps = max(1, min(10, args.steps))
+    for i in range(probs_reps + 1):
+        if i == 1:
+            ev0.record()
+        rc = lib.pcc_encode_probs(codec._h, d_img.data_ptr(), n, h, w, d_params.data_ptr(), d_bits.data_ptr(), st)
+        assert rc == 0, rc
+    ev1.record()
+    torch.cuda.synchronize()
+    probs_ms = ev0.elapsed_time(ev1) / probs_reps
+    probs_bytes = pixels * (3 + 4 * (codec.head_outputs + 1))
+
     k = args.steps
     ms_per_step = (t1 - t0) / k * 1e3
     kern = {name: acc[name] / k for name in acc}       # ms per launch
@@ -183,6 +201,9 @@ def main():
             "achieved_TFLOP_s": FLOP_PER_PIXEL * pixels / (kern["decode"] * 1e-3) / 1e12,
             "frac_of_mfma_peak": FLOP_PER_PIXEL * pixels / (kern["decode"] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
         },
+        "encode_probs": {"ms": probs_ms, "MPix_s": pixels / (probs_ms * 1e-3) / 1e6, "bytes": probs_bytes,
+                         "GB_s": probs_bytes / (probs_ms * 1e-3) / 1e9,
+                         "frac_of_hbm_peak": probs_bytes / (probs_ms * 1e-3) / 1e9 / PEAK_HBM_GBS},
         "paper_context": "paper, 512x512 on RTX 2080 + i7-9700: wavefront encode 3.10 s, decode 26.26 s (0.0846 / 0.00998 MPix/s); "
                          "diagonal 3.08 s / 27.22 s",
     }
