@@ -48,12 +48,12 @@ constexpr int kDefaultEncodeVariant = 1;
 // status words in device memory
 enum { kStErr = 0, kStAbort = 1, kStTicket = 2, kStWords = 4 };
 // The status block: kStWords ints that every call clears on its stream before its kernels, the 64-bit stream
-// size, and two ints that only a row coder running beside the pixel kernel writes (stood down; wait ran out).
+// size, and two ints that only a row coder running beside the pixel kernel writes (stood down; spare).
 // That row coder runs on another stream than the clearing, so its words are cleared after they have been read,
 // at the end of the call, and are zero whenever a call begins.
 constexpr size_t kStCleared = kStWords * sizeof(int) + sizeof(uint64_t);
 constexpr int kStSide = (int)(kStCleared / sizeof(int));     // index of the first of the two side words
-enum { kSideDefer = 0, kSideErr = 1 };
+enum { kSideDefer = 0 };
 constexpr size_t kStBytes = kStCleared + 2 * sizeof(int);
 
 __host__ __device__ inline size_t slab_words(int W) { return (6 * (size_t)W + 16) / 4 + 1; }
@@ -153,7 +153,7 @@ template <class Net, int T, int THREADS>
 __global__ void __launch_bounds__(THREADS)
 encode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ img, int n, int H, int W,
               uint32_t* __restrict__ sf, float* __restrict__ params, float* __restrict__ bits, int* status,
-              uint64_t* sf_tagged, uint32_t epoch) {
+              uint64_t* sf_tagged, uint32_t epoch, uint32_t strip_begin, uint32_t strip_count) {
     using Lay = Layout<Net>;
     constexpr int K = Net::K, KB0 = Net::kb(0), HEAD = Net::dim(Net::kLayers);
     extern __shared__ __align__(16) uint8_t lds[];
@@ -166,10 +166,9 @@ encode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ img
     const int g = lane >> 4, nl = lane & 15;
     const uint32_t rows = (uint32_t)n * (uint32_t)H;
     const uint32_t P = rows * (uint32_t)W;
-    const uint32_t nstrips = ((uint32_t)W + 16 * T - 1) / (16 * T);
-    const uint32_t items = nstrips * rows;
+    const uint32_t items = strip_count * rows;              // this launch's strips: strip_begin .. strip_begin + strip_count - 1
     for (uint32_t item = blockIdx.x * nwaves + wave; item < items; item += gridDim.x * nwaves) {
-        const uint32_t strip = item / rows, rowg = item - strip * rows;
+        const uint32_t local = item / rows, rowg = item - local * rows, strip = strip_begin + local;
         const uint32_t im = rowg / (uint32_t)H;
         const int r = (int)(rowg - im * (uint32_t)H);
         const int c0 = W - 16 * T * (int)(strip + 1);           // negative in the leftmost strip of a ragged width
@@ -285,8 +284,11 @@ constexpr int kRansChunk = 32;
 constexpr int kRansThreads = 256;
 constexpr uint32_t kRansBesideMaxGroups = 48;      // row-coder workgroups that may run beside the pixel kernel
 constexpr uint32_t kXcds = 8;
-constexpr uint32_t kRansSpinLimit = 1u << 22;       // polls for one symbol before the row coder gives up (seconds)
-constexpr uint32_t kRansFirstPolls = 1024;          // ... before it has seen the pixel kernel's first symbol (a few ms)
+constexpr uint32_t kRansPatience = 2048;            // polls for one symbol before a row coder beside the pixel kernel stands down (a few ms)
+// Rows at which the row coder of an image takes as long as the pixel kernel with the whole chip (both times are
+// proportional to the width; measured with the 30-160-160-128-60 network, 768x512 to 4096x2160): decides how much of
+// a tall image the pixel kernel does before the row coder joins it.
+constexpr uint32_t kRansBalanceRows = 850;
 // Padding symbol (start 0, frequency 2^16): pushing it leaves the state unchanged
 // and never renormalises, so every chunk can be coded as a full one.
 constexpr uint32_t kRansNop = 0xFFFF0000u;
@@ -340,8 +342,7 @@ __device__ __forceinline__ void lds_barrier() {
 template <bool BESIDE>
 __global__ void __launch_bounds__(kRansThreads)
 rans_rows_kernel(const uint32_t* __restrict__ sf, const uint64_t* sf_tagged, uint32_t epoch, int W, uint32_t rows,
-                 uint32_t* __restrict__ slabs, uint32_t* __restrict__ row_words, int* status, uint32_t first_limit,
-                 uint32_t spin_limit) {
+                 uint32_t* __restrict__ slabs, uint32_t* __restrict__ row_words, int* status, uint32_t patience) {
     // [buffer][row][symbol of the chunk]; the odd row strides keep the coding wave's column accesses off shared banks
     __shared__ uint32_t sym[2][kRansRows][kRansChunk + 1];
     __shared__ double rcp[2][kRansRows][kRansChunk + 1];
@@ -377,7 +378,6 @@ rans_rows_kernel(const uint32_t* __restrict__ sf, const uint64_t* sf_tagged, uin
     //   round k - 1  the words it produced are copied to the rows' slabs
     using Staged = std::conditional_t<BESIDE, uint64_t, uint32_t>;
     Staged staged[2][kPerLoader];
-    bool seen_symbols = false;      // this lane's first wait for the pixel kernel is over
     auto request = [&](int k, Staged (&staged)[kPerLoader]) __attribute__((always_inline)) {
 #pragma unroll
         for (int it = 0; it < kPerLoader; ++it) {
@@ -398,12 +398,11 @@ rans_rows_kernel(const uint32_t* __restrict__ sf, const uint64_t* sf_tagged, uin
             // Symbols the pixel kernel has not written yet (seldom once the pixel kernel, the faster of the two, is
             // ahead): the lane polls one of them, sleeping in between so that the polls of a coder that has
             // caught up do not load the memory system, and then loads its whole set again, all loads at once.
-            // Every wait is bounded.  The first one is short: if nothing has appeared by then the pixel kernel
-            // is not running beside this one (something runs the process's kernels one at a time, or the chip
-            // is taken), and the row coder stands down; the host launches it again after the pixel kernel.
-            // Once symbols have been seen the pixel kernel is on the chip and the bound is only a safeguard.
+            // A running pixel kernel delivers a row's next strip within tens of microseconds.  A wait of
+            // `patience` polls (milliseconds) therefore means that it is not running beside this kernel
+            // (something runs the process's kernels one at a time, or the chip is taken): the row coder stands
+            // down, and the host launches it again after the pixel kernel.
             uint32_t spins = 0;
-            const uint32_t limit = seen_symbols ? spin_limit : first_limit;
             for (;;) {
                 size_t stale_at = 0;
                 bool stale = false;
@@ -420,18 +419,16 @@ rans_rows_kernel(const uint32_t* __restrict__ sf, const uint64_t* sf_tagged, uin
                 if (!stale) break;
                 bool gave_up = false;
                 while ((uint32_t)(__hip_atomic_load(&sf_tagged[stale_at], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >> 32) != epoch) {
-                    if (++spins > limit) { gave_up = true; break; }
+                    if (++spins > patience) { gave_up = true; break; }
                     __builtin_amdgcn_s_sleep(32);
                 }
                 if (gave_up) {
-                    __hip_atomic_store(&status[kStSide + (seen_symbols ? kSideErr : kSideDefer)], 1, __ATOMIC_RELAXED,
-                                       __HIP_MEMORY_SCOPE_AGENT);
+                    __hip_atomic_store(&status[kStSide + kSideDefer], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     abandon = 1;
                     break;
                 }
                 request(k, staged);
             }
-            seen_symbols = true;
         }
 #pragma unroll
         for (int it = 0; it < kPerLoader; ++it) {
@@ -1294,8 +1291,9 @@ struct pcc_ctx {
     int encode_variant = kDefaultEncodeVariant;
     // the row coder of a small job runs beside the pixel kernel, on a stream of its own
     bool overlap = true;
-    uint32_t first_polls = kRansFirstPolls;   // the row coder's patience before the pixel kernel's first symbol
+    uint32_t patience = kRansPatience;        // polls before a row coder beside the pixel kernel stands down
     hipStream_t side = nullptr;
+    hipEvent_t ev_joined = nullptr;           // the pixel kernel's first part is done: the row coder may join
     // symbols handed from the pixel kernel to a row coder running beside it: epoch << 32 | start | (freq - 1) << 16.
     // Zero when allocated and written by nothing else, so a word carries an epoch only if that launch wrote it.
     uint64_t* d_tagged = nullptr;
@@ -1493,10 +1491,14 @@ bool set_kernel_attributes() {
 }
 
 // Workgroups of the pixel kernel.  reserve_cus: compute units left free for a kernel that runs beside it.
-uint32_t encode_blocks(const pcc_ctx* ctx, int n, int H, int W, uint32_t reserve_cus) {
+uint32_t encode_strips(const pcc_ctx* ctx, int W) {
+    const uint32_t cols = 16u * (uint32_t)kEncodeVariants[ctx->encode_variant].tiles;
+    return ((uint32_t)W + cols - 1) / cols;
+}
+
+uint32_t encode_blocks(const pcc_ctx* ctx, int n, int H, uint32_t strips, uint32_t reserve_cus) {
     const EncodeVariant ev = kEncodeVariants[ctx->encode_variant];
-    const uint64_t strips = ((uint64_t)W + 16u * ev.tiles - 1) / (16u * ev.tiles);
-    const uint64_t items = strips * (uint64_t)n * H;          // dims_ok: below 2^31
+    const uint64_t items = (uint64_t)strips * (uint64_t)n * H;          // dims_ok: below 2^31
     const uint32_t per_block = ev.threads / 64;
     const uint64_t blocks = (items + per_block - 1) / per_block;
     const uint32_t cus = (ctx->num_cus > 0 ? (uint32_t)ctx->num_cus : 256u) - reserve_cus;
@@ -1506,34 +1508,35 @@ uint32_t encode_blocks(const pcc_ctx* ctx, int n, int H, int W, uint32_t reserve
 // sf_tagged: see encode_kernel
 template <class Net>
 int launch_encode(pcc_ctx* ctx, const uint8_t* d_img, int n, int H, int W, uint32_t* sf, float* params, float* bits,
-                  uint64_t* sf_tagged, uint32_t reserve_cus, hipStream_t st) {
+                  uint64_t* sf_tagged, uint32_t reserve_cus, uint32_t strip_begin, uint32_t strip_count, hipStream_t st) {
     constexpr int kLds = Layout<Net>::kModelBytes;
-    const uint32_t blocks = encode_blocks(ctx, n, H, W, reserve_cus);
+    const uint32_t blocks = encode_blocks(ctx, n, H, strip_count, reserve_cus);
     switch (ctx->encode_variant) {
         case 0:
             hipLaunchKernelGGL((encode_kernel<Net, 1, 512>), dim3(blocks), dim3(512), kLds, st, ctx->d_model, d_img, n, H, W,
-                               sf, params, bits, ctx->d_status, sf_tagged, ctx->epoch);
+                               sf, params, bits, ctx->d_status, sf_tagged, ctx->epoch, strip_begin, strip_count);
             break;
         case 1:
             hipLaunchKernelGGL((encode_kernel<Net, 2, 512>), dim3(blocks), dim3(512), kLds, st, ctx->d_model, d_img, n, H, W,
-                               sf, params, bits, ctx->d_status, sf_tagged, ctx->epoch);
+                               sf, params, bits, ctx->d_status, sf_tagged, ctx->epoch, strip_begin, strip_count);
             break;
         case 2:
             hipLaunchKernelGGL((encode_kernel<Net, 1, 1024>), dim3(blocks), dim3(1024), kLds, st, ctx->d_model, d_img, n, H, W,
-                               sf, params, bits, ctx->d_status, sf_tagged, ctx->epoch);
+                               sf, params, bits, ctx->d_status, sf_tagged, ctx->epoch, strip_begin, strip_count);
             break;
         default:
             hipLaunchKernelGGL((encode_kernel<Net, 4, 256>), dim3(blocks), dim3(256), kLds, st, ctx->d_model, d_img, n, H, W,
-                               sf, params, bits, ctx->d_status, sf_tagged, ctx->epoch);
+                               sf, params, bits, ctx->d_status, sf_tagged, ctx->epoch, strip_begin, strip_count);
             break;
     }
     return hipGetLastError() == hipSuccess ? PCC_OK : PCC_E_HIP;
 }
 
 int launch_encode_any(pcc_ctx* ctx, const uint8_t* d_img, int n, int H, int W, uint32_t* sf, float* params, float* bits,
-                      uint64_t* sf_tagged, uint32_t reserve_cus, hipStream_t st) {
+                      uint64_t* sf_tagged, uint32_t reserve_cus, uint32_t strip_begin, uint32_t strip_count, hipStream_t st) {
     return with_net(ctx->net, [&](auto net) {
-        return launch_encode<decltype(net)>(ctx, d_img, n, H, W, sf, params, bits, sf_tagged, reserve_cus, st);
+        return launch_encode<decltype(net)>(ctx, d_img, n, H, W, sf, params, bits, sf_tagged, reserve_cus, strip_begin,
+                                            strip_count, st);
     });
 }
 
@@ -1622,8 +1625,9 @@ int pcc_create(pcc_ctx** out, const void* h_blob, size_t blob_bytes, int hip_dev
         if (v >= 0 && v < 4) ctx->encode_variant = v;
     }
     if (const char* e = getenv("PCC_ENCODE_OVERLAP")) ctx->overlap = atoi(e) != 0;
-    if (const char* e = getenv("PCC_RANS_FIRST_POLLS")) ctx->first_polls = (uint32_t)atoi(e);
+    if (const char* e = getenv("PCC_RANS_PATIENCE")) ctx->patience = (uint32_t)atoi(e);
     ok = ok && hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&ctx->ev_joined, hipEventDisableTiming) == hipSuccess;
     if (!ok) { (void)hipGetLastError(); pcc_destroy(ctx); return PCC_E_HIP; }
     ctx->d_total = reinterpret_cast<uint64_t*>(ctx->d_status + kStWords);
     *out = ctx;
@@ -1639,6 +1643,7 @@ void pcc_destroy(pcc_ctx* ctx) {
     if (ctx->h_status) (void)hipHostFree(ctx->h_status);
     for (hipEvent_t e : ctx->ev) if (e) (void)hipEventDestroy(e);
     if (ctx->d_tagged) (void)hipFree(ctx->d_tagged);
+    if (ctx->ev_joined) (void)hipEventDestroy(ctx->ev_joined);
     if (ctx->side) (void)hipStreamDestroy(ctx->side);
     delete ctx;
 }
@@ -1663,7 +1668,8 @@ int pcc_encode_probs(pcc_ctx* ctx, const uint8_t* d_img, int n, int H, int W, fl
     if (!ctx || !d_img || !d_params || !dims_ok(n, H, W)) return PCC_E_ARG;
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return PCC_E_HIP;
-    return launch_encode_any(ctx, d_img, n, H, W, nullptr, d_params, d_bits, nullptr, 0, (hipStream_t)hip_stream);
+    return launch_encode_any(ctx, d_img, n, H, W, nullptr, d_params, d_bits, nullptr, 0, 0, encode_strips(ctx, W),
+                             (hipStream_t)hip_stream);
 }
 
 int pcc_encode(pcc_ctx* ctx, const uint8_t* d_img, int n, int H, int W, uint8_t* d_stream, size_t cap_bytes,
@@ -1721,14 +1727,14 @@ int pcc_encode(pcc_ctx* ctx, const uint8_t* d_img, int n, int H, int W, uint8_t*
     if (hipMemsetAsync(ctx->d_status, 0, kStCleared, st) != hipSuccess) return PCC_E_HIP;
     prof_reset(ctx);
     const uint32_t tag = with_net(ctx->net, [](auto net) { return model_tag<decltype(net)>(); });
-    auto launch_rans = [&](hipStream_t s, uint32_t first_polls) {
+    auto launch_rans = [&](hipStream_t s) {
         prof_begin(ctx, PCC_T_ENCODE_RANS, s);
         if (beside)
             hipLaunchKernelGGL(rans_rows_kernel<true>, dim3(groups), dim3(kRansThreads), 0, s, d_sf, d_tagged, ctx->epoch, W,
-                               rows, d_slabs, d_rw, ctx->d_status, first_polls, kRansSpinLimit);
+                               rows, d_slabs, d_rw, ctx->d_status, ctx->patience);
         else
             hipLaunchKernelGGL(rans_rows_kernel<false>, dim3(groups), dim3(kRansThreads), 0, s, d_sf, d_tagged, ctx->epoch, W,
-                               rows, d_slabs, d_rw, ctx->d_status, first_polls, kRansSpinLimit);
+                               rows, d_slabs, d_rw, ctx->d_status, 0u);
         prof_end(ctx, PCC_T_ENCODE_RANS, s);
     };
     // what follows the row coder, and the wait for it
@@ -1753,31 +1759,54 @@ int pcc_encode(pcc_ctx* ctx, const uint8_t* d_img, int n, int H, int W, uint8_t*
         if (hipStreamSynchronize(s) != hipSuccess) { (void)hipGetLastError(); return PCC_E_HIP; }
         return PCC_OK;
     };
-    // Beside: the row coder goes first, so that it is in place when the pixel kernel's first symbols appear (its
-    // launch would otherwise come that much later, and it is the longer of the two).
-    if (beside) launch_rans(ctx->side, ctx->first_polls);
-    prof_begin(ctx, PCC_T_ENCODE_PIXELS, st);
-    rc = launch_encode_any(ctx, d_img, n, H, W, beside ? nullptr : d_sf, nullptr, nullptr, d_tagged, reserve, st);
-    if (rc != PCC_OK) {
-        if (beside) (void)hipStreamSynchronize(ctx->side);   // the row coder stands down after its first, short wait
-        return rc;
-    }
-    prof_end(ctx, PCC_T_ENCODE_PIXELS, st);
-    if (!beside) launch_rans(st, 0);
-    rc = finish(beside ? ctx->side : st);
-    if (rc != PCC_OK) return rc;
-    if (beside) {
+    const uint32_t strips = encode_strips(ctx, W);
+    if (!beside) {
+        prof_begin(ctx, PCC_T_ENCODE_PIXELS, st);
+        rc = launch_encode_any(ctx, d_img, n, H, W, d_sf, nullptr, nullptr, nullptr, 0, 0, strips, st);
+        if (rc != PCC_OK) return rc;
+        prof_end(ctx, PCC_T_ENCODE_PIXELS, st);
+        launch_rans(st);
+        rc = finish(st);
+        if (rc != PCC_OK) return rc;
+    } else {
+        // An image of few rows: the row coder is the longer of the two, goes first and is in place when the pixel
+        // kernel's first symbols appear.  A tall image: the pixel kernel is the longer one; it does the first
+        // strips with the whole chip, and the row coder joins it (an event; the launch gap does not matter at
+        // this size) for a last part sized so that both end together.  The row coder takes about as long as the
+        // pixel kernel at kRansBalanceRows rows, both in proportion to the width.
+        const double share = 1.1 * kRansBalanceRows / rows * (double)(cus - reserve) / cus;   // of the strips, beside
+        const uint32_t strips_alone = share >= 1.0 ? 0u : (uint32_t)((1.0 - share) * strips);
+        if (strips_alone == 0) {
+            launch_rans(ctx->side);
+            prof_begin(ctx, PCC_T_ENCODE_PIXELS, st);
+        } else {
+            prof_begin(ctx, PCC_T_ENCODE_PIXELS, st);
+            rc = launch_encode_any(ctx, d_img, n, H, W, nullptr, nullptr, nullptr, d_tagged, 0, 0, strips_alone, st);
+            if (rc != PCC_OK) return rc;
+            if (hipEventRecord(ctx->ev_joined, st) != hipSuccess) return PCC_E_HIP;
+            if (hipStreamWaitEvent(ctx->side, ctx->ev_joined, 0) != hipSuccess) return PCC_E_HIP;
+            launch_rans(ctx->side);
+        }
+        rc = launch_encode_any(ctx, d_img, n, H, W, nullptr, nullptr, nullptr, d_tagged, reserve, strips_alone,
+                               strips - strips_alone, st);
+        if (rc != PCC_OK) {
+            (void)hipStreamSynchronize(ctx->side);   // the row coder stands down when its patience is over
+            return rc;
+        }
+        prof_end(ctx, PCC_T_ENCODE_PIXELS, st);
+        rc = finish(ctx->side);
+        if (rc != PCC_OK) return rc;
         // the row coder ends after the pixel kernel's last store; the caller's stream is waited for as well, so
         // that the pixel kernel has retired when this returns
         if (hipStreamSynchronize(st) != hipSuccess) { (void)hipGetLastError(); return PCC_E_HIP; }
-        if (ctx->h_status[kStSide + kSideErr] != 0) return PCC_E_INTERNAL;
         if (ctx->h_status[kStErr] == 0 && ctx->h_status[kStSide + kSideDefer] != 0) {
-            // The row coder saw nothing of the pixel kernel and stood down: the two did not run side by side.
-            // The symbols are all there now; code them on the caller's stream.
+            // The row coder saw nothing of the pixel kernel for a long time and stood down: the two did not run side
+            // by side.  The symbols are all there now; code them on the caller's stream.
             if (hipMemsetAsync(ctx->d_status, 0, kStCleared, st) != hipSuccess) return PCC_E_HIP;
-            launch_rans(st, kRansSpinLimit);
+            launch_rans(st);
             rc = finish(st);
             if (rc != PCC_OK) return rc;
+            if (ctx->h_status[kStSide + kSideDefer] != 0) return PCC_E_INTERNAL;   // a symbol was never written
         }
     }
     prof_collect(ctx);

@@ -428,6 +428,8 @@ def test_row_coder_beside_after_and_busy_stream_agree(blob, paper_blob, monkeypa
     # either side of the most rows the row coder takes beside the pixel kernel (48 groups of 64), and of the most
     # rows whose sizes the compaction sums by itself (4096)
     shapes += [(1, 3072, 5), (1, 3073, 5), (2, 2048, 3), (1, 4097, 3)]
+    # tall enough for the pixel kernel to run in two parts, the row coder joining for the second
+    shapes += [(1, 1200, 100), (1, 2000, 70)]
     for name, b in (("workload", blob), ("paper", paper_blob)):
         beside = binding.Codec(b, 0)
         monkeypatch.setenv("PCC_ENCODE_OVERLAP", "0")
@@ -435,9 +437,9 @@ def test_row_coder_beside_after_and_busy_stream_agree(blob, paper_blob, monkeypa
         monkeypatch.delenv("PCC_ENCODE_OVERLAP")
         # no patience at all: the row coder stands down at the first symbol it does not find, and the host
         # launches it again after the pixel kernel (what happens where kernels are run one at a time)
-        monkeypatch.setenv("PCC_RANS_FIRST_POLLS", "0")
+        monkeypatch.setenv("PCC_RANS_PATIENCE", "0")
         impatient = binding.Codec(b, 0)
-        monkeypatch.delenv("PCC_RANS_FIRST_POLLS")
+        monkeypatch.delenv("PCC_RANS_PATIENCE")
         try:
             for n, h, w in shapes:
                 _log("row coder beside/after %s %dx%dx%d" % (name, n, h, w))
