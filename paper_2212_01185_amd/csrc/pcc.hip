@@ -42,6 +42,11 @@ constexpr uint32_t model_tag() { return (uint32_t)Net::K | ((uint32_t)Net::kNbhd
 // Encode kernel variants: tiles of 16 pixels per wave per iteration x threads per workgroup.
 // More tiles per wave reuse each LDS weight read more often but need more registers.
 struct EncodeVariant { int tiles, threads; };
+// pcc_encode_probs: pixels of a tile whose head outputs a wave stages in LDS at a time, and the bytes that takes for
+// the workgroup (beyond the model image; 16 waves at most)
+constexpr int kParamsStagePixels = 4;
+template <class Net>
+constexpr int params_stage_bytes(int threads) { return (threads / 64) * kParamsStagePixels * Net::dim(Net::kLayers) * 4; }
 constexpr EncodeVariant kEncodeVariants[4] = {{1, 512}, {2, 512}, {1, 1024}, {4, 256}};
 constexpr int kDefaultEncodeVariant = 1;
 
@@ -234,7 +239,38 @@ encode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ img
             const int c = c0 + 16 * t + nl;
             const bool live = c >= 0;
             const uint32_t p = rowg * (uint32_t)W + (uint32_t)c;
-            if (params != nullptr && live) {
+            if (params != nullptr && ((uintptr_t)params & 15u) == 0) {
+                // The tile's head outputs are HEAD consecutive floats per pixel, 16 consecutive pixels: they go
+                // through a staging area of this wave in LDS, kParamsStagePixels pixels at a time, and leave as
+                // 16-byte stores of consecutive lanes (stored straight from the registers, a lane's values lie
+                // 4 bytes here and 4 bytes there, 240 bytes apart from its neighbour's).  LDS takes a wave's
+                // instructions in order, so the reads see the writes of the same pass.
+                constexpr int PX = kParamsStagePixels;
+                float* stage = reinterpret_cast<float*>(lds + Lay::kModelBytes) + wave * (PX * HEAD);
+#pragma unroll
+                for (int pass = 0; pass < 16 / PX; ++pass) {
+                    if (nl / PX == pass) {
+#pragma unroll
+                        for (int ob = 0; ob < Lay::kHeadOB; ++ob) {
+                            const float vv[4] = {out[t][ob].x, out[t][ob].y, out[t][ob].z, out[t][ob].w};
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) {
+                                const int idx = Net::head_index(g, 4 * ob + i);
+                                if (idx >= 0) stage[(nl % PX) * HEAD + idx] = vv[i];
+                            }
+                        }
+                    }
+                    __builtin_amdgcn_wave_barrier();
+                    for (int j = lane; j < PX * HEAD / 4; j += 64) {
+                        const int cc = c0 + 16 * t + pass * PX + (4 * j) / HEAD;      // the chunk's pixel
+                        if (cc >= 0) {
+                            const f32x4_t v = *reinterpret_cast<const f32x4_t*>(stage + 4 * j);
+                            *reinterpret_cast<f32x4_t*>(params + ((size_t)rowg * W + cc) * HEAD + (4 * j) % HEAD) = v;
+                        }
+                    }
+                    __builtin_amdgcn_wave_barrier();
+                }
+            } else if (params != nullptr && live) {
 #pragma unroll
                 for (int ob = 0; ob < Lay::kHeadOB; ++ob) {
                     const float vv[4] = {out[t][ob].x, out[t][ob].y, out[t][ob].z, out[t][ob].w};
@@ -1473,7 +1509,7 @@ int pack_model(const uint8_t* p, size_t blob_bytes, uint32_t dist, std::vector<u
 
 template <class Net>
 bool set_kernel_attributes() {
-    const int enc = Layout<Net>::kModelBytes, dec = DecLds<Net>::kBytes;
+    const int enc = Layout<Net>::kModelBytes + params_stage_bytes<Net>(1024), dec = DecLds<Net>::kBytes;
     bool ok = true;
     ok = ok && hipFuncSetAttribute(reinterpret_cast<const void*>(&encode_kernel<Net, 1, 512>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, enc) == hipSuccess;
@@ -1509,7 +1545,7 @@ uint32_t encode_blocks(const pcc_ctx* ctx, int n, int H, uint32_t strips, uint32
 template <class Net>
 int launch_encode(pcc_ctx* ctx, const uint8_t* d_img, int n, int H, int W, uint32_t* sf, float* params, float* bits,
                   uint64_t* sf_tagged, uint32_t reserve_cus, uint32_t strip_begin, uint32_t strip_count, hipStream_t st) {
-    constexpr int kLds = Layout<Net>::kModelBytes;
+    const int kLds = Layout<Net>::kModelBytes + (params != nullptr ? params_stage_bytes<Net>(kEncodeVariants[ctx->encode_variant].threads) : 0);
     const uint32_t blocks = encode_blocks(ctx, n, H, strip_count, reserve_cus);
     switch (ctx->encode_variant) {
         case 0:

@@ -459,3 +459,30 @@ def test_row_coder_beside_after_and_busy_stream_agree(blob, paper_blob, monkeypa
             beside.close()
             after.close()
             impatient.close()
+
+
+def test_encode_probs_output_alignment_and_ragged_shapes(codec, paper_blob):
+    """pcc_encode_probs writes through 16-byte stores when its output is 16-byte aligned and value by value
+    when it is not: both must give the same numbers, also where strips and tiles are ragged, and every value of
+    the output (and nothing outside it) must be written."""
+    import ctypes as C
+    from paper_2212_01185_amd import binding
+    rng = np.random.default_rng(29)
+    paper = binding.Codec(paper_blob, 0)
+    try:
+        for c in (codec, paper):
+            for n, h, w in [(1, 5, 37), (2, 3, 16), (1, 7, 1), (1, 2, 70)]:
+                imgs = _dev(rng.integers(0, 256, (n, h, w, 3), dtype=np.uint8))
+                count = n * h * w * c.head_outputs
+                want, _ = c.pcc_encode_probs(imgs)
+                for shift in (0, 1, 3):          # floats: 0 is aligned, 1 and 3 are not
+                    buf = torch.full((count + 8,), float("nan"), dtype=torch.float32, device="cuda")
+                    out = buf[shift:shift + count]
+                    rc = binding.load().pcc_encode_probs(c._h, imgs.data_ptr(), n, h, w, out.data_ptr(), None,
+                                                         torch.cuda.current_stream().cuda_stream)
+                    assert rc == 0
+                    torch.cuda.synchronize()
+                    assert torch.equal(out, want.reshape(-1)), (n, h, w, shift)
+                    assert torch.isnan(buf[:shift]).all() and torch.isnan(buf[shift + count:]).all()
+    finally:
+        paper.close()
