@@ -310,9 +310,10 @@ encode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ img
 
 // ---------------------------------------------------------------------------
 // rANS encode, one lane per row.  A workgroup owns 64 rows: the lanes of wave 0
-// each run one row's serial chain, and waves 1-3 feed it -- they fetch the rows'
-// (start, freq) words chunk by chunk (coalesced), compute the fp64 reciprocal of
-// every frequency, and stage both in LDS one chunk ahead.  The coding wave's
+// each run one row's serial chain; waves 2 and 3 fetch the rows' (start, freq)
+// words chunk by chunk (coalesced, two chunks ahead), compute the fp64
+// reciprocal of every frequency and stage both in LDS; wave 1 copies the words
+// the coding wave produced from LDS to the rows' slabs.  The coding wave's
 // instruction stream, which bounds the kernel, then holds only the chain itself.
 // ---------------------------------------------------------------------------
 constexpr int kRansRows = 64;
