@@ -160,6 +160,19 @@ def main():
     probs_ms = ev0.elapsed_time(ev1) / probs_reps
     probs_bytes = pixels * (3 + 4 * (codec.head_outputs + 1))
 
+    # The pixel kernel of a small job leaves compute units to the row coder that runs beside it.  For reference:
+    # the same kernel with the whole chip, the row coder after it (a second context, not part of the step).
+    os.environ["PCC_ENCODE_OVERLAP"] = "0"
+    plain = binding.Codec(blob, 0)
+    del os.environ["PCC_ENCODE_OVERLAP"]
+    plain.pcc_set_profiling(True)
+    plain_reps, plain_pix_ms = max(1, min(10, args.steps)), 0.0
+    for i in range(plain_reps + 2):
+        plain.pcc_encode(d_img, out=d_stream)
+        if i >= 2:
+            plain_pix_ms += plain.pcc_last_timings()["encode_pixels"] / plain_reps
+    plain.close()
+
     k = args.steps
     ms_per_step = (t1 - t0) / k * 1e3
     kern = {name: acc[name] / k for name in acc}       # ms per launch
@@ -195,6 +208,9 @@ def main():
             "traffic": (ENCODE_KERNEL_TRAFFIC_768x512["fetch_bytes"] + ENCODE_KERNEL_TRAFFIC_768x512["write_bytes"])
                        if headline else None,
             "traffic_detail": ENCODE_KERNEL_TRAFFIC_768x512 if headline else None,
+            # the same kernel when the row coder runs after it and it has every compute unit
+            "whole_chip": {"kernel_ms": plain_pix_ms,
+                           "frac": FLOP_PER_PIXEL * pixels / (plain_pix_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS},
         },
         "roofline_decode": {
             "kernel": "decode_kernel (persistent wavefront)", "bound": "dependency chain",
