@@ -1308,7 +1308,7 @@ cdf_tables_kernel(const uint8_t* __restrict__ model, const float* __restrict__ p
 // ===========================================================================
 using namespace pcc;
 
-enum { kNetWorkload = 0, kNetPaper = 1, kNetDiagonal = 2 };
+enum { kNetWorkload = 0, kNetPaper = 1, kNetDiagonal = 2, kNetFewerLayers = 3, kNetFewerFilters = 4, kNetMoreMixtures = 5 };
 
 struct pcc_ctx {
     int device = 0;
@@ -1422,6 +1422,9 @@ auto with_net(int net, F&& f) {
     switch (net) {
         case kNetPaper: return f(NetPaper{});
         case kNetDiagonal: return f(NetDiagonal{});
+        case kNetFewerLayers: return f(NetFewerLayers{});
+        case kNetFewerFilters: return f(NetFewerFilters{});
+        case kNetMoreMixtures: return f(NetMoreMixtures{});
         default: return f(NetWorkload{});
     }
 }
@@ -1510,7 +1513,8 @@ int pack_model(const uint8_t* p, size_t blob_bytes, uint32_t dist, std::vector<u
 
 template <class Net>
 bool set_kernel_attributes() {
-    const int enc = Layout<Net>::kModelBytes + params_stage_bytes<Net>(1024), dec = DecLds<Net>::kBytes;
+    constexpr int enc = Layout<Net>::kModelBytes + params_stage_bytes<Net>(1024), dec = DecLds<Net>::kBytes;
+    static_assert(enc <= 160 * 1024 && dec <= 160 * 1024, "the network does not fit a compute unit's LDS");
     bool ok = true;
     ok = ok && hipFuncSetAttribute(reinterpret_cast<const void*>(&encode_kernel<Net, 1, 512>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, enc) == hipSuccess;
@@ -1635,6 +1639,9 @@ int pcc_create(pcc_ctx** out, const void* h_blob, size_t blob_bytes, int hip_dev
     if (header_matches<NetWorkload>(p)) net = kNetWorkload;
     else if (header_matches<NetPaper>(p)) net = kNetPaper;
     else if (header_matches<NetDiagonal>(p)) net = kNetDiagonal;
+    else if (header_matches<NetFewerLayers>(p)) net = kNetFewerLayers;
+    else if (header_matches<NetFewerFilters>(p)) net = kNetFewerFilters;
+    else if (header_matches<NetMoreMixtures>(p)) net = kNetMoreMixtures;
     else return PCC_E_BLOB;
 
     std::vector<uint8_t> image;

@@ -135,6 +135,26 @@ struct NetDiagonal : NetPaper {
     }
 };
 
+// The paper's network with another number of mixture components, filters or layers (the ablations of
+// Sec. IV-E; wavefront order): 36 -> C -> ... -> C -> 12 K, LAYERS weight layers, LeakyReLU.  K is 3 or 5
+// (the head layouts above), C a multiple of 32; the packed model must fit the encoder's LDS beside the
+// staging area (checked where the kernels are set up), which six layers of 128 filters do not.
+template <int MIXTURES, int C, int LAYERS>
+struct NetAblation : NetPaper {
+    static_assert((MIXTURES == 3 || MIXTURES == 5) && C % 32 == 0 && C <= 128 && LAYERS >= 3 && LAYERS <= 7, "unsupported shape");
+    static constexpr int kLayers = LAYERS;
+    static constexpr int K = MIXTURES;
+    __host__ __device__ static constexpr int dim(int l) { return l == 0 ? 36 : l == LAYERS ? 12 * MIXTURES : C; }
+    __host__ __device__ static constexpr int ob(int l) { return (dim(l + 1) + 15) / 16; }
+    __host__ __device__ static constexpr int kb(int l) { return (dim(l) + 31) / 32; }
+    __host__ __device__ static constexpr int head_index(int g, int s) {
+        return MIXTURES == 3 ? NetPaper::head_index(g, s) : NetWorkload::head_index(g, s);
+    }
+};
+using NetFewerLayers = NetAblation<3, 128, 4>;
+using NetFewerFilters = NetAblation<3, 64, 5>;
+using NetMoreMixtures = NetAblation<5, 128, 5>;
+
 // Every canonical first-layer input sits in exactly one k-slot.
 template <class Net>
 constexpr bool inputs_placed_once() {
@@ -147,7 +167,9 @@ constexpr bool inputs_placed_once() {
     }
     return true;
 }
-static_assert(inputs_placed_once<NetWorkload>() && inputs_placed_once<NetPaper>() && inputs_placed_once<NetDiagonal>(),
+static_assert(inputs_placed_once<NetWorkload>() && inputs_placed_once<NetPaper>() && inputs_placed_once<NetDiagonal>() &&
+                  inputs_placed_once<NetFewerLayers>() &&
+                  inputs_placed_once<NetFewerFilters>() && inputs_placed_once<NetMoreMixtures>(),
               "first-layer slot map");
 
 constexpr int kBlockBytes = 64 * 16;  // one (out-block, k-block) A operand: 64 lanes x 8 bf16

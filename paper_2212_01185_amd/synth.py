@@ -255,6 +255,23 @@ def make_diagonal_blob(seed: int = 0, sharp: bool = False, dist: int = DIST_GAUS
                      act=ACT_LEAKY, dist=dist)
 
 
+# The shapes of the paper's ablation study (Sec. IV-E: one hyper-parameter of (K, C, L) = (3, 128, 5) changed at a
+# time) that the GPU library also takes: name -> (mixtures K, filters C, layers L).
+ABLATION_SHAPES = {"fewer_layers": (3, 128, 4), "fewer_filters": (3, 64, 5), "more_mixtures": (5, 128, 5)}
+
+
+def ablation_dims(k: int, c: int, n_layers: int):
+    """Layer widths of the paper's network with K mixtures, C filters and L layers: 36, C x (L-1), 12 K."""
+    return (PAPER_DIMS[0],) + (c,) * (n_layers - 1) + (12 * k,)
+
+
+def make_ablation_blob(k: int, c: int, n_layers: int, seed: int = 0, sharp: bool = False,
+                       dist: int = DIST_GAUSSIAN) -> bytes:
+    """A weight blob of one of the ablation shapes (He-initialised), wavefront order."""
+    return pack_blob(make_weights(seed, ablation_dims(k, c, n_layers), sharp=sharp), k=k, nbhd=PAPER_NBHD,
+                     delay=PAPER_DELAY, act=ACT_LEAKY, dist=dist)
+
+
 def param_count(dims) -> int:
     """Weights + biases of a fully connected stack with these layer widths."""
     return sum(i * o + o for i, o in zip(dims[:-1], dims[1:]))

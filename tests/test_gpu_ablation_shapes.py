@@ -1,0 +1,146 @@
+"""The network shapes of the paper's ablation study (Sec. IV-E: number of mixtures, of filters, of layers, one changed
+at a time from K = 3, C = 128, L = 5) on the HIP path against the CPU oracle.  Needs an MI355X.
+
+Of the paper's six variants the library takes K = 5, C = 64 and L = 4; K = 7 (84 head outputs), C = 192 and L = 6
+are refused at pcc_create like any other unknown shape (a CPU test covers that)."""
+import struct
+
+import numpy as np
+import pytest
+
+from oracle import pcc_oracle as po
+from paper_2212_01185_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+PARAM_ATOL = 2e-3         # raw head outputs against the exact fp64 network
+PARAM_ATOL_SPLIT = 2e-4   # against the oracle rounding activations to hi + lo bf16 the same way
+BITS_RTOL = 1e-3          # bits/pixel within 0.1 %
+CQ_ATOL = 2               # integer CDF counts
+
+SHAPES = sorted(synth.ABLATION_SHAPES)
+
+
+def _log(msg):
+    print(msg, flush=True)
+
+
+def _dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+@pytest.fixture(scope="module", params=SHAPES)
+def variant(request):
+    """(name, K, head size, layers, codec, codec with narrow mixtures, oracle) of one shape."""
+    from paper_2212_01185_amd import binding
+    if not torch.cuda.is_available():
+        pytest.fail("no GPU visible")
+    k, c, nl = synth.ABLATION_SHAPES[request.param]
+    blob = synth.make_ablation_blob(k, c, nl)
+    sharp = synth.make_ablation_blob(k, c, nl, sharp=True)
+    _log("ablation shape %s: K=%d C=%d L=%d" % (request.param, k, c, nl))
+    codec, codec_sharp = binding.Codec(blob, 0), binding.Codec(sharp, 0)
+    yield request.param, k, 12 * k, nl, codec, codec_sharp, po.Oracle(blob)
+    codec.close()
+    codec_sharp.close()
+
+
+def test_model_info_and_params_match_oracle(variant):
+    name, k, head, nl, codec, _, orc = variant
+    assert codec.pcc_model_info() == (head, k, 12, 3, 0, nl)
+    rng = np.random.default_rng(61)
+    for what, img in (("64x64 workload image", synth.make_batch(0)[0]),
+                      ("19x37 random", rng.integers(0, 256, (19, 37, 3), dtype=np.uint8))):
+        _log("%s: encode_probs %s" % (name, what))
+        h, w, _ = img.shape
+        params, bits = codec.pcc_encode_probs(_dev(img[None]))
+        torch.cuda.synchronize()
+        assert tuple(params.shape) == (1, h, w, head)
+        got = params.cpu().numpy().astype(np.float64)[0]
+        err = np.abs(got - orc.params_rows(img, range(h), po.MODE_EXACT)).max()
+        _log("max |params - oracle(exact)| = %.3g" % err)
+        assert err <= PARAM_ATOL
+        err = np.abs(got - orc.params_rows(img, range(h), po.MODE_SPLIT)).max()
+        _log("max |params - oracle(split activations)| = %.3g" % err)
+        assert err <= PARAM_ATOL_SPLIT
+        _, wbits = orc.encode(img[None], po.MODE_EXACT)
+        gbits = bits.cpu().numpy().astype(np.float64)
+        _log("bits/pixel gpu %.5f oracle %.5f" % (gbits.mean(), wbits.mean()))
+        assert abs(gbits.sum() / wbits.sum() - 1) <= BITS_RTOL
+        assert np.abs(gbits - wbits).mean() < 0.01
+
+
+def test_cdf_tables_against_oracle(variant):
+    name, k, head, _, codec, _, orc = variant
+    rng = np.random.default_rng(62)
+    heads = [rng.normal(0, s, head) for s in (0.1, 0.5, 1.0, 3.0) for _ in range(25)]
+    for mu in (0.0, 0.5, 100.5 / 256, 255 / 256, -3.0, 4.0):
+        for ls in (-20.0, -8.0, -4.0, 0.0, 4.0, 20.0):
+            o = np.zeros(head)
+            for ch in range(3):
+                o[3 * k * ch + k: 3 * k * ch + 2 * k] = mu
+                o[3 * k * ch + 2 * k: 3 * k * ch + 3 * k] = ls
+            heads.append(o)
+    heads = np.asarray(heads, dtype=np.float32)
+    rg = rng.integers(0, 256, (len(heads), 2), dtype=np.uint8)
+    cq = codec.pcc_cdf_tables(_dev(heads), _dev(rg))
+    torch.cuda.synchronize()
+    cq = cq.cpu().numpy().astype(np.int64)
+    assert (cq[:, :, 0] == 0).all() and (cq[:, :, 256] == 65536).all()
+    assert (np.diff(cq, axis=2) >= 1).all()
+    worst = 0
+    for i, o in enumerate(heads.astype(np.float64)):
+        for ch in range(3):
+            want = orc.cdf_table(o, ch, int(rg[i, 0]), int(rg[i, 1])).astype(np.int64)
+            worst = max(worst, int(np.abs(cq[i, ch] - want).max()))
+    _log("%s: max |Cq_gpu - Cq_oracle| = %d counts" % (name, worst))
+    assert worst <= CQ_ATOL
+
+
+def test_coder_and_container_bit_exact(variant):
+    name, k, _, _, codec, codec_sharp, _ = variant
+    tag = k | (12 << 8) | (3 << 16) | (16 << 24)
+    rng = np.random.default_rng(63)
+    n, h, w = 2, 17, 33
+    imgs = rng.integers(0, 256, (n, h, w, 3), dtype=np.uint8)
+    for c in (codec, codec_sharp):
+        stream = c.pcc_encode(_dev(imgs))
+        iv = c.pcc_copy_intervals(n, h, w)
+        torch.cuda.synchronize()
+        iv = iv.cpu().numpy().view(np.uint32)
+        freq = (iv >> 16) + 1
+        assert freq.min() >= 1 and ((iv & 0xFFFF) + freq).max() <= 65536
+        sf = iv.reshape(n * h, 3 * w)
+        payloads = [po.rans_encode(row & 0xFFFF, (row >> 16) + 1) for row in sf]
+        offs = np.concatenate([[0], np.cumsum([len(p) for p in payloads])]).astype("<u8")
+        want = struct.pack("<8I", 0x31434350, 1, n, h, w, tag, 0, 0) + offs.tobytes() + b"".join(payloads)
+        assert stream.cpu().numpy().tobytes() == want
+
+
+def _images():
+    rng = np.random.default_rng(64)
+    yield "1x1", rng.integers(0, 256, (1, 1, 1, 3), dtype=np.uint8)
+    yield "1x9", rng.integers(0, 256, (1, 1, 9, 3), dtype=np.uint8)
+    yield "9x1", rng.integers(0, 256, (1, 9, 1, 3), dtype=np.uint8)
+    yield "3x3", rng.integers(0, 256, (1, 3, 3, 3), dtype=np.uint8)
+    yield "17x33x3", rng.integers(0, 256, (3, 17, 33, 3), dtype=np.uint8)     # ragged band, ragged tile
+    yield "40x7", rng.integers(0, 256, (1, 40, 7, 3), dtype=np.uint8)         # taller than wide
+    yield "33x2", rng.integers(0, 256, (1, 33, 2, 3), dtype=np.uint8)         # narrower than the neighbourhood
+    yield "ones", np.full((1, 33, 20, 3), 255, dtype=np.uint8)
+    yield "blobs", synth.make_image(3, synth.ImageSpec(100, 50, 5, 3.0, 12.0))[None]
+    yield "256x256", synth.make_image(8, synth.ImageSpec(256, 256, 24, 8.0, 64.0))[None]
+
+
+def test_roundtrip(variant):
+    name, _, _, _, codec, codec_sharp, _ = variant
+    for what, imgs in _images():
+        for which, c in (("default", codec), ("sharp", codec_sharp)):
+            _log("%s roundtrip %s %s" % (name, what, which))
+            n, h, w, _ = imgs.shape
+            stream = c.pcc_encode(_dev(imgs))
+            out = c.pcc_decode(stream, n, h, w)
+            torch.cuda.synchronize()
+            np.testing.assert_array_equal(out.cpu().numpy(), imgs, err_msg="%s %s %s" % (name, what, which))
+

@@ -44,6 +44,8 @@ def test_paper_parameter_counts():
     for k, c, nl, printed in (map(int, r) for r in rows):
         dims = [36] + [c] * (nl - 1) + [12 * k]
         assert synth.param_count(dims) + 1 == printed
+        assert tuple(dims) == synth.ablation_dims(k, c, nl)
+    assert synth.ablation_dims(3, 128, 5) == synth.PAPER_DIMS
     assert 58917 + (75 - 36) * 128 == 63909      # Table I's "63.9 K"
 
 
