@@ -28,7 +28,7 @@
  * per row, activation id, distribution id}, then per layer W[out][in] and
  * b[out] as fp32.  Weights must be exactly representable in bf16 (biases are
  * fp32); components are Gaussian (distribution id 0, Eq. (1)) or logistic
- * (id 1, Eq. (8)).  This library accepts three models:
+ * (id 1, Eq. (8)).  This library accepts these models:
  *   - 30 -> 160 -> 160 -> 128 -> 60, ReLU (activation id 0), K = 5, the
  *     10-pixel neighbourhood {rows r-2, r-1 at columns c-2..c+1; row r at
  *     c-2, c-1}, delay 2 (the measured workloads);
@@ -39,7 +39,10 @@
  *   - the same shape with delay 1: the diagonal decoding order of Sec. III-C,
  *     Eq. (7).  A pass decodes the anti-diagonal r + c = t; the inputs of the
  *     three neighbours not yet decoded then, (r-2,c+2), (r-1,c+1), (r-1,c+2),
- *     carry copies of pixel (r-1,c) (zero in the first row), at the encoder too.
+ *     carry copies of pixel (r-1,c) (zero in the first row), at the encoder too;
+ *   - three shapes of the ablations of Sec. IV-E, each the second model with
+ *     one hyper-parameter changed: K = 5 (36 -> 128 x 4 -> 60), 64 filters
+ *     (36 -> 64 x 4 -> 36), four layers (36 -> 128 x 3 -> 36).
  * Head layout o[12 K]: for each of R,G,B: K mixture logits, K means, K
  * log-sigmas (units of 1/256 of the grey range); then K alphas, K betas,
  * K gammas of Eq. (3)-(4).
