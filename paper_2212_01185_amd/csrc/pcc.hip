@@ -21,6 +21,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <algorithm>
 #include <new>
 #include <type_traits>
 #include <vector>
@@ -689,6 +690,9 @@ compact_scan_kernel(const uint32_t* __restrict__ slabs, const uint32_t* __restri
 //             in global memory that the band below polls
 // ---------------------------------------------------------------------------
 constexpr int kDecThreads = 256;
+// Time of a decode step when two workgroups share a CU, in percent of the time when one has it alone (measured
+// with batches of 9 to 48 images of 768x512: 40 images take the same time either way, 48 are 8 % faster shared).
+constexpr unsigned kDecodeSharedStepPercent = 195;
 
 // decode LDS: the CDF table, two activation buffers, head outputs, mixtures, ring
 template <class Net>
@@ -971,10 +975,9 @@ __device__ __forceinline__ void lds_read_floats(const float* __restrict__ src, f
     }
 }
 
-// MINBLOCKS = 1: all registers to one workgroup per CU (lowest latency per step; used when
-// every band gets a CU of its own).  MINBLOCKS = 2: two workgroups share a CU (a few
-// spills, ~15 % slower per step, but the second band fills the first one's stalls; used
-// when there are more bands than CUs).
+// MINBLOCKS = 1: all registers to one workgroup per CU (lowest latency per step).  MINBLOCKS = 2: two
+// workgroups share a CU (some spills; a step takes about twice as long, so this only pays for jobs of
+// so many bands that the work per CU, not an image's chain of steps, sets the time: launch_decode).
 template <class Net, int MINBLOCKS>
 __global__ void __launch_bounds__(kDecThreads, MINBLOCKS)
 decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ stream, uint64_t nbytes, int n, int H,
@@ -1002,27 +1005,52 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
     // search role: pixel q of the band, lane j of its group
     const int q = 4 * wave + (lane >> 4), j = lane & 15;
 
-    // Bands take tickets in start order: a band only ever waits for the band above it
-    // (same image), which holds a smaller ticket and is therefore already running.
-    if (tid == 0) { misc[0] = atomicAdd(&status[kStTicket], 1); misc[1] = 0; }
     {
         const float2* src = reinterpret_cast<const float2*>(model + Lay::kLutOff);
         for (int i = tid; i < kLutEntries + 1; i += kDecThreads) lut[i] = src[i];
     }
-    for (int i = tid; i < 18 * D::kRingRowElems; i += kDecThreads) ring[i] = 0;
-
-    // this wave's weights stay in registers
+    // this wave's weights stay in registers, for every band the workgroup decodes
     WaveNet<Net, 0> net;
     net.load(model, lane, wave);
-    __syncthreads();
-
-    // Tickets are handed out band-major (band 0 of every image, then band 1 of every image, ...):
-    // the order in which bands become runnable.  A workgroup slot is then held by a band that can
-    // run rather than by one that waits for hundreds of steps, and all images advance together.
-    const int ticket = misc[0];
-    const int band = ticket / n, im = ticket - band * n;
-    if (band >= nbands) return;
     const float lut_scale = *reinterpret_cast<const float*>(model + Lay::kLutScaleOff);
+    const int total_bands = n * nbands;
+
+    // network role: this lane's first-layer inputs are runs of four consecutive ring values
+    // (ring row, offset within the row's window that starts at column c-2); a run the
+    // network does not use reads as zero
+    const uint16_t* run_ptr[KB0][2];
+    bool run_used[KB0][2];
+#pragma unroll
+    for (int kbi = 0; kbi < KB0; ++kbi) {
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            int dr = 0, off = 0;
+            run_used[kbi][half] = Net::run_desc(kbi, g, half, dr, off);
+            run_ptr[kbi][half] = ring + (nl + 2 + dr) * D::kRingRowElems + off;
+        }
+    }
+
+    // The grid has at most as many workgroups as the chip holds at once, and a workgroup decodes band after band:
+    // it takes a ticket, decodes that band, takes the next.  Tickets go out in the order they are asked for, so a
+    // band only ever waits for the band above it (same image), whose smaller ticket some workgroup holds or has
+    // finished.  (Leaving the bands beyond the resident ones to the hardware's dispatcher costs up to a third:
+    // it deals workgroups to dies and shader engines in strict rotation, and waits for a place in the engine
+    // whose turn it is while others are free.)
+    // Tickets are numbered band-major (band 0 of every image, then band 1 of every image, ...): the order in
+    // which bands become runnable, so a workgroup holds a band that can run rather than one that waits for
+    // hundreds of steps, and all images advance together.
+    for (;;) {
+    __syncthreads();                                   // the previous band's last reads of the ring and of misc
+    if (tid == 0) {
+        const bool stop = __hip_atomic_load(&status[kStAbort], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0;
+        misc[0] = stop ? total_bands : atomicAdd(&status[kStTicket], 1);
+        misc[1] = 0;
+    }
+    for (int i = tid; i < 18 * D::kRingRowElems; i += kDecThreads) ring[i] = 0;
+    __syncthreads();
+    const int ticket = misc[0];
+    if (ticket >= total_bands) break;
+    const int band = ticket / n, im = ticket - band * n;
 
     const int r0 = band * kBandRows;
     const uint64_t rows_total = (uint64_t)n * H;
@@ -1112,21 +1140,6 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
         if (!ok) give_up();
     }
     lds_barrier();
-
-    // network role: this lane's first-layer inputs are runs of four consecutive ring values
-    // (ring row, offset within the row's window that starts at column c-2); a run the
-    // network does not use reads as zero
-    const uint16_t* run_ptr[KB0][2];
-    bool run_used[KB0][2];
-#pragma unroll
-    for (int kbi = 0; kbi < KB0; ++kbi) {
-#pragma unroll
-        for (int half = 0; half < 2; ++half) {
-            int dr = 0, off = 0;
-            run_used[kbi][half] = Net::run_desc(kbi, g, half, dr, off);
-            run_ptr[kbi][half] = ring + (nl + 2 + dr) * D::kRingRowElems + off;
-        }
-    }
 
     for (int t = t_begin; t <= t_end; ++t) {
         if ((t & 7) == 0 && misc[1] != 0) break;  // uniform: written before the last barrier; a late exit only decodes garbage
@@ -1268,6 +1281,8 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
         }
         lds_barrier();
     }
+    if (misc[1] != 0) break;    // uniform: written before the last barrier.  The call has failed; no further bands.
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -1326,6 +1341,8 @@ struct pcc_ctx {
     int num_cus = 0;
     uint32_t dist = 0;             // written to / checked against stream header word 6
     int encode_variant = kDefaultEncodeVariant;
+    uint32_t spin_limit = 1u << 22;      // polls of a band for one pixel of the band above (seconds) before the call fails (PCC_DECODE_SPIN_LIMIT, for tests)
+    int decode_variant = 0;              // 0: chosen per job; 1: one workgroup per CU; 2: two (PCC_DECODE_VARIANT, for measurements)
     // the row coder of a small job runs beside the pixel kernel, on a stream of its own
     bool overlap = true;
     uint32_t patience = kRansPatience;        // polls before a row coder beside the pixel kernel stands down
@@ -1585,9 +1602,19 @@ template <class Net>
 void launch_decode(pcc_ctx* ctx, const uint8_t* d_stream, size_t nbytes, int n, int H, int W, int nbands,
                    uint8_t* d_img_out, uint32_t* d_mail, uint32_t spin_limit, hipStream_t st) {
     constexpr int kLds = DecLds<Net>::kBytes;
-    const uint32_t grid = (uint32_t)(n * nbands);
-    const uint32_t cus = ctx->num_cus > 0 ? (uint32_t)ctx->num_cus : 256u;
-    if (grid <= cus)
+    const uint64_t bands = (uint64_t)n * nbands;                      // dims_ok: below 2^31
+    const uint64_t cus = ctx->num_cus > 0 ? (uint64_t)ctx->num_cus : 256u;
+    // One workgroup per CU decodes a step in the shortest time; two per CU take kDecodeSharedStepPercent / 100
+    // as long per step but decode twice as many bands at once.  An image is a chain of `chain` steps whatever the
+    // machine does; the job is `work` band-steps.  Two per CU pay when the work per place, not the chain, sets the time.
+    const int band_rows = H < kBandRows ? H : kBandRows;
+    const uint64_t chain = (uint64_t)W + (uint64_t)Net::kDelay * (H - 1);
+    const uint64_t work = bands * ((uint64_t)W + (uint64_t)Net::kDelay * (band_rows - 1));
+    const uint64_t alone = std::max(chain, (work + cus - 1) / cus) * 100u;
+    const uint64_t shared = std::max(chain, (work + 2 * cus - 1) / (2 * cus)) * kDecodeSharedStepPercent;
+    const bool two = ctx->decode_variant == 2 || (ctx->decode_variant == 0 && bands > cus && shared < alone);
+    const uint32_t grid = (uint32_t)std::min(bands, two ? 2 * cus : cus);
+    if (!two)
         hipLaunchKernelGGL((decode_kernel<Net, 1>), dim3(grid), dim3(kDecThreads), kLds, st, ctx->d_model, d_stream,
                            (uint64_t)nbytes, n, H, W, nbands, ctx->dist, d_img_out, d_mail, ctx->d_status, spin_limit);
     else
@@ -1667,6 +1694,11 @@ int pcc_create(pcc_ctx** out, const void* h_blob, size_t blob_bytes, int hip_dev
     if (const char* e = getenv("PCC_ENCODE_VARIANT")) {
         const int v = atoi(e);
         if (v >= 0 && v < 4) ctx->encode_variant = v;
+    }
+    if (const char* e = getenv("PCC_DECODE_SPIN_LIMIT")) ctx->spin_limit = (uint32_t)atoi(e);
+    if (const char* e = getenv("PCC_DECODE_VARIANT")) {
+        const int v = atoi(e);
+        if (v >= 0 && v <= 2) ctx->decode_variant = v;
     }
     if (const char* e = getenv("PCC_ENCODE_OVERLAP")) ctx->overlap = atoi(e) != 0;
     if (const char* e = getenv("PCC_RANS_PATIENCE")) ctx->patience = (uint32_t)atoi(e);
@@ -1880,7 +1912,7 @@ int pcc_decode(pcc_ctx* ctx, const uint8_t* d_stream, size_t nbytes, int n, int 
     uint32_t* d_mail = reinterpret_cast<uint32_t*>(ctx->d_ws);
     if (hipMemsetAsync(ctx->d_status, 0, kStCleared, st) != hipSuccess) return PCC_E_HIP;
     if (hipMemsetAsync(d_mail, 0, mail_bytes, st) != hipSuccess) return PCC_E_HIP;
-    const uint32_t spin_limit = 1u << 22;
+    const uint32_t spin_limit = ctx->spin_limit;
     prof_reset(ctx);
     prof_begin(ctx, PCC_T_DECODE, st);
     with_net(ctx->net, [&](auto net) {

@@ -417,6 +417,58 @@ def test_roundtrip_random_shapes(codec, codec_sharp, paper_blob, diagonal_blob):
             c.close()
 
 
+def test_more_bands_than_resident_workgroups(blob, paper_blob, monkeypatch):
+    """540 bands of 16 rows: more than the chip holds workgroups, with one and with two per compute unit, so every
+    workgroup decodes several bands one after the other.  All three launch choices return the images."""
+    from paper_2212_01185_amd import binding
+    rng = np.random.default_rng(77)
+    imgs = np.stack([synth.make_image(100 + s, synth.ImageSpec(24, 40, 4, 2.0, 8.0)) for s in range(20)])
+    imgs = np.concatenate([imgs, rng.integers(0, 256, (160, 40, 24, 3), dtype=np.uint8)])
+    n, h, w, _ = imgs.shape
+    for which in (blob, paper_blob):
+        streams = []
+        for variant in ("0", "1", "2"):
+            monkeypatch.setenv("PCC_DECODE_VARIANT", variant)
+            c = binding.Codec(which, 0)
+            try:
+                _log("decode variant %s: %d images of %dx%d" % (variant, n, w, h))
+                stream = c.pcc_encode(_dev(imgs))
+                out = c.pcc_decode(stream, n, h, w)
+                torch.cuda.synchronize()
+                np.testing.assert_array_equal(out.cpu().numpy(), imgs)
+                streams.append(stream.cpu().numpy().tobytes())
+            finally:
+                c.close()
+        assert streams[0] == streams[1] == streams[2]
+
+
+def test_a_band_that_gives_up_ends_the_call(blob, monkeypatch):
+    """With no patience at all (the limit of a band's polls for the band above set to zero from the host) the
+    bands below the first give up at once: the call returns an error, every workgroup leaves, also those that
+    would have gone on to further bands, and the next call on another context works."""
+    from paper_2212_01185_amd import binding
+    rng = np.random.default_rng(78)
+    imgs = rng.integers(0, 256, (120, 40, 24, 3), dtype=np.uint8)       # 360 bands
+    good = binding.Codec(blob, 0)
+    monkeypatch.setenv("PCC_DECODE_SPIN_LIMIT", "0")
+    hasty = binding.Codec(blob, 0)
+    try:
+        stream = good.pcc_encode(_dev(imgs))
+        for variant_imgs in (imgs, imgs[:1]):
+            n = variant_imgs.shape[0]
+            s = good.pcc_encode(_dev(variant_imgs))
+            _log("decode without patience: %d images" % n)
+            with pytest.raises(binding.PccError) as e:
+                hasty.pcc_decode(s, n, 40, 24)
+            assert e.value.code == binding.PCC_E_INTERNAL
+        out = good.pcc_decode(stream, 120, 40, 24)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(out.cpu().numpy(), imgs)
+    finally:
+        good.close()
+        hasty.close()
+
+
 def test_row_coder_beside_after_and_busy_stream_agree(blob, paper_blob, monkeypatch):
     """The row coder of a small job runs beside the pixel kernel; that of a large job, of a caller whose stream
     has work pending, or one that stood down because it saw nothing of the pixel kernel, runs after it: all must
