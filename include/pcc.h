@@ -79,7 +79,15 @@ extern "C" {
 typedef struct pcc_ctx pcc_ctx;
 
 /* Parse and pack the weight blob (host pointer) for device `hip_device`.
- * On success *out owns device memory until pcc_destroy. */
+ * On success *out owns device memory until pcc_destroy.
+ * Reads these environment variables, which exist for tests and measurements and
+ * never change a result: PCC_ENCODE_VARIANT (0..3: tiles per work item and
+ * workgroup size of the pixel kernel), PCC_ENCODE_OVERLAP (0: the row coder
+ * always runs after the pixel kernel), PCC_RANS_PATIENCE (polls before a row
+ * coder running beside the pixel kernel stands down), PCC_DECODE_VARIANT (1, 2:
+ * decoder workgroups per compute unit; 0: chosen per job), PCC_DECODE_SPIN_LIMIT
+ * (polls of a band for the band above before pcc_decode fails with
+ * PCC_E_INTERNAL). */
 int pcc_create(pcc_ctx **out, const void *h_blob, size_t blob_bytes, int hip_device);
 void pcc_destroy(pcc_ctx *ctx);
 
