@@ -43,11 +43,17 @@ constexpr uint32_t model_tag() { return (uint32_t)Net::K | ((uint32_t)Net::kNbhd
 // Encode kernel variants: tiles of 16 pixels per wave per iteration x threads per workgroup.
 // More tiles per wave reuse each LDS weight read more often but need more registers.
 struct EncodeVariant { int tiles, threads; };
-// pcc_encode_probs: pixels of a tile whose head outputs a wave stages in LDS at a time, and the bytes that takes for
-// the workgroup (beyond the model image; 16 waves at most)
-constexpr int kParamsStagePixels = 4;
+// pcc_encode_probs: pixels of a tile whose head outputs a wave stages in LDS at a time (four, or as many as fit
+// beside the model image: two or one for the largest networks), and the bytes that takes for the workgroup.
+constexpr int kLdsBytes = 160 * 1024;
 template <class Net>
-constexpr int params_stage_bytes(int threads) { return (threads / 64) * kParamsStagePixels * Net::dim(Net::kLayers) * 4; }
+constexpr int params_stage_pixels(int threads) {
+    for (int px = 4; px >= 1; px /= 2)
+        if (Layout<Net>::kModelBytes + (threads / 64) * px * Net::dim(Net::kLayers) * 4 <= kLdsBytes) return px;
+    return 0;
+}
+template <class Net>
+constexpr int params_stage_bytes(int threads) { return (threads / 64) * params_stage_pixels<Net>(threads) * Net::dim(Net::kLayers) * 4; }
 constexpr EncodeVariant kEncodeVariants[4] = {{1, 512}, {2, 512}, {1, 1024}, {4, 256}};
 constexpr int kDefaultEncodeVariant = 1;
 
@@ -242,11 +248,11 @@ encode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ img
             const uint32_t p = rowg * (uint32_t)W + (uint32_t)c;
             if (params != nullptr && ((uintptr_t)params & 15u) == 0) {
                 // The tile's head outputs are HEAD consecutive floats per pixel, 16 consecutive pixels: they go
-                // through a staging area of this wave in LDS, kParamsStagePixels pixels at a time, and leave as
+                // through a staging area of this wave in LDS, PX pixels at a time, and leave as
                 // 16-byte stores of consecutive lanes (stored straight from the registers, a lane's values lie
                 // 4 bytes here and 4 bytes there, 240 bytes apart from its neighbour's).  LDS takes a wave's
                 // instructions in order, so the reads see the writes of the same pass.
-                constexpr int PX = kParamsStagePixels;
+                constexpr int PX = params_stage_pixels<Net>(THREADS);
                 float* stage = reinterpret_cast<float*>(lds + Lay::kModelBytes) + wave * (PX * HEAD);
 #pragma unroll
                 for (int pass = 0; pass < 16 / PX; ++pass) {
@@ -710,7 +716,7 @@ struct DecLds {
     // Strides in floats, padded by one 16-byte vector: consecutive pixels (and channels) then start
     // four LDS banks apart instead of on the same bank.
     static constexpr int kHeadStride = 4 * kHS + 4;                    // head outputs of one pixel: [4 groups][kHS]
-    static constexpr int kCpStride = 20;                               // mixture of one (pixel, channel): pi[K], mu[K], a[K]
+    static constexpr int kCpStride = 3 * Net::K <= 16 ? 20 : 24;       // mixture of one (pixel, channel): pi[K], mu[K], a[K]
     static constexpr int kHeadOff = kAct1Off + kActBytes;              // [16 pixels][kHeadStride] fp32, (group, register) layout
     static constexpr int kCpOff = kHeadOff + 16 * kHeadStride * 4;     // [16 pixels][3 channels][kCpStride] fp32
     // Ring of recently decoded pixels as first-layer inputs: [18 rows][2 * kRingCols columns][3] bf16.
@@ -907,17 +913,20 @@ struct WaveNet {
                                         uint8_t* __restrict__ act1, float* __restrict__ headout,
                                         uint8_t* __restrict__ dump) const {
         if constexpr (kHead) {
-            static_assert(SLOTS == 1, "the head has at most four out-blocks, one per wave");
-            f32x4_t acc = wl.bias[0];
-#pragma unroll
-            for (int kb = 0; kb < NKB; ++kb) {
-                acc = mfma16(wl.a[0][kb], in[kb][0], acc);
-                acc = mfma16(wl.a[0][kb], in[kb][1], acc);
-            }
-            // registers s = 4 wave + i of group g, kept in (group, register) order
+            // registers s = 4 ob + i of group g, kept in (group, register) order; out-blocks ob = wave + 4 slot
             constexpr int HS = Layout<Net>::kHeadSlots;
-            if (wave < NOB)
-                *reinterpret_cast<f32x4_t*>(headout + (lane & 15) * DecLds<Net>::kHeadStride + (lane >> 4) * HS + 4 * wave) = acc;
+#pragma unroll
+            for (int slot = 0; slot < SLOTS; ++slot) {
+                f32x4_t acc = wl.bias[slot];
+#pragma unroll
+                for (int kb = 0; kb < NKB; ++kb) {
+                    acc = mfma16(wl.a[slot][kb], in[kb][0], acc);
+                    acc = mfma16(wl.a[slot][kb], in[kb][1], acc);
+                }
+                const int ob = wave + 4 * slot;
+                if (ob < NOB)
+                    *reinterpret_cast<f32x4_t*>(headout + (lane & 15) * DecLds<Net>::kHeadStride + (lane >> 4) * HS + 4 * ob) = acc;
+            }
             lds_barrier();
         } else {
             uint8_t* out = (L & 1) ? act1 : act0;
@@ -1180,8 +1189,8 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
         net.template run<(MINBLOCKS > 1)>(in1, lane, wave, act0, act1, headout, dump);
 
         // ---- mixtures: lane j < 3K of pixel q prepares component j % K of channel j / K
-        if (j < 3 * K) {
-            const int ch = j / K, k = j - K * ch;
+        for (int jj = j; jj < 3 * K; jj += 16) {      // one pass unless K > 5
+            const int ch = jj / K, k = jj - K * ch;
             const float* hc = headout + q * D::kHeadStride + ch * HS;
             float pk, mk, ak;
             if constexpr (K >= 5) {
@@ -1323,7 +1332,7 @@ cdf_tables_kernel(const uint8_t* __restrict__ model, const float* __restrict__ p
 // ===========================================================================
 using namespace pcc;
 
-enum { kNetWorkload = 0, kNetPaper = 1, kNetDiagonal = 2, kNetFewerLayers = 3, kNetFewerFilters = 4, kNetMoreMixtures = 5 };
+enum { kNetWorkload = 0, kNetPaper = 1, kNetDiagonal = 2, kNetFewerLayers = 3, kNetFewerFilters = 4, kNetMoreMixtures = 5, kNetMostMixtures = 6 };
 
 struct pcc_ctx {
     int device = 0;
@@ -1442,6 +1451,7 @@ auto with_net(int net, F&& f) {
         case kNetFewerLayers: return f(NetFewerLayers{});
         case kNetFewerFilters: return f(NetFewerFilters{});
         case kNetMoreMixtures: return f(NetMoreMixtures{});
+        case kNetMostMixtures: return f(NetMostMixtures{});
         default: return f(NetWorkload{});
     }
 }
@@ -1531,7 +1541,8 @@ int pack_model(const uint8_t* p, size_t blob_bytes, uint32_t dist, std::vector<u
 template <class Net>
 bool set_kernel_attributes() {
     constexpr int enc = Layout<Net>::kModelBytes + params_stage_bytes<Net>(1024), dec = DecLds<Net>::kBytes;
-    static_assert(enc <= 160 * 1024 && dec <= 160 * 1024, "the network does not fit a compute unit's LDS");
+    static_assert(params_stage_pixels<Net>(1024) >= 1 && enc <= kLdsBytes && dec <= kLdsBytes,
+                  "the network does not fit a compute unit's LDS");
     bool ok = true;
     ok = ok && hipFuncSetAttribute(reinterpret_cast<const void*>(&encode_kernel<Net, 1, 512>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, enc) == hipSuccess;
@@ -1669,6 +1680,7 @@ int pcc_create(pcc_ctx** out, const void* h_blob, size_t blob_bytes, int hip_dev
     else if (header_matches<NetFewerLayers>(p)) net = kNetFewerLayers;
     else if (header_matches<NetFewerFilters>(p)) net = kNetFewerFilters;
     else if (header_matches<NetMoreMixtures>(p)) net = kNetMoreMixtures;
+    else if (header_matches<NetMostMixtures>(p)) net = kNetMostMixtures;
     else return PCC_E_BLOB;
 
     std::vector<uint8_t> image;

@@ -136,24 +136,30 @@ struct NetDiagonal : NetPaper {
 };
 
 // The paper's network with another number of mixture components, filters or layers (the ablations of
-// Sec. IV-E; wavefront order): 36 -> C -> ... -> C -> 12 K, LAYERS weight layers, LeakyReLU.  K is 3 or 5
-// (the head layouts above), C a multiple of 32; the packed model must fit the encoder's LDS beside the
+// Sec. IV-E; wavefront order): 36 -> C -> ... -> C -> 12 K, LAYERS weight layers, LeakyReLU.  K is 3, 5
+// (the head layouts above) or 7, C a multiple of 32; the packed model must fit the encoder's LDS beside the
 // staging area (checked where the kernels are set up), which six layers of 128 filters do not.
+// K = 7 (six out-blocks, 24 registers): groups 0..2 hold their channel's 21 parameters, group 3 the
+// 21 coupling coefficients.
 template <int MIXTURES, int C, int LAYERS>
 struct NetAblation : NetPaper {
-    static_assert((MIXTURES == 3 || MIXTURES == 5) && C % 32 == 0 && C <= 128 && LAYERS >= 3 && LAYERS <= 7, "unsupported shape");
+    static_assert((MIXTURES == 3 || MIXTURES == 5 || MIXTURES == 7) && C % 32 == 0 && C <= 128 && LAYERS >= 3 && LAYERS <= 7,
+                  "unsupported shape");
     static constexpr int kLayers = LAYERS;
     static constexpr int K = MIXTURES;
     __host__ __device__ static constexpr int dim(int l) { return l == 0 ? 36 : l == LAYERS ? 12 * MIXTURES : C; }
     __host__ __device__ static constexpr int ob(int l) { return (dim(l + 1) + 15) / 16; }
     __host__ __device__ static constexpr int kb(int l) { return (dim(l) + 31) / 32; }
     __host__ __device__ static constexpr int head_index(int g, int s) {
-        return MIXTURES == 3 ? NetPaper::head_index(g, s) : NetWorkload::head_index(g, s);
+        return MIXTURES == 3 ? NetPaper::head_index(g, s)
+             : MIXTURES == 5 ? NetWorkload::head_index(g, s)
+                             : (s < 21 ? 21 * g + s : -1);
     }
 };
 using NetFewerLayers = NetAblation<3, 128, 4>;
 using NetFewerFilters = NetAblation<3, 64, 5>;
 using NetMoreMixtures = NetAblation<5, 128, 5>;
+using NetMostMixtures = NetAblation<7, 128, 5>;
 
 // Every canonical first-layer input sits in exactly one k-slot.
 template <class Net>
@@ -169,7 +175,8 @@ constexpr bool inputs_placed_once() {
 }
 static_assert(inputs_placed_once<NetWorkload>() && inputs_placed_once<NetPaper>() && inputs_placed_once<NetDiagonal>() &&
                   inputs_placed_once<NetFewerLayers>() &&
-                  inputs_placed_once<NetFewerFilters>() && inputs_placed_once<NetMoreMixtures>(),
+                  inputs_placed_once<NetFewerFilters>() && inputs_placed_once<NetMoreMixtures>() &&
+                  inputs_placed_once<NetMostMixtures>(),
               "first-layer slot map");
 
 constexpr int kBlockBytes = 64 * 16;  // one (out-block, k-block) A operand: 64 lanes x 8 bf16
@@ -458,7 +465,7 @@ __device__ __forceinline__ void couple_blue(ChanParams<K>& cp, const float (&bet
 // increasing in e and every symbol has frequency >= 1.
 template <int K>
 __device__ __forceinline__ uint32_t cq_eval(const ChanParams<K>& cp, int e, const float2* __restrict__ lut) {
-    static_assert(K == 3 || K == 5, "the scheduling barrier below lists the table reads explicitly");
+    static_assert(K == 3 || K == 5 || K == 7, "the scheduling barrier below lists the table reads explicitly");
     const float edge = (float)(2 * e - 1) * (1.0f / 512.0f);
     float t[K];
     float2 td[K];
@@ -469,7 +476,11 @@ __device__ __forceinline__ uint32_t cq_eval(const ChanParams<K>& cp, int e, cons
     }
     // Scheduling only: all table reads are in flight before the first is used
     // (one LDS latency per evaluation instead of K).
-    if constexpr (K == 5) {
+    if constexpr (K == 7) {
+        asm volatile("" : "+v"(td[0].x), "+v"(td[0].y), "+v"(td[1].x), "+v"(td[1].y), "+v"(td[2].x), "+v"(td[2].y),
+                          "+v"(td[3].x), "+v"(td[3].y), "+v"(td[4].x), "+v"(td[4].y), "+v"(td[5].x), "+v"(td[5].y),
+                          "+v"(td[6].x), "+v"(td[6].y));
+    } else if constexpr (K == 5) {
         asm volatile("" : "+v"(td[0].x), "+v"(td[0].y), "+v"(td[1].x), "+v"(td[1].y), "+v"(td[2].x), "+v"(td[2].y),
                           "+v"(td[3].x), "+v"(td[3].y), "+v"(td[4].x), "+v"(td[4].y));
     } else {
