@@ -1189,7 +1189,7 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
         net.template run<(MINBLOCKS > 1)>(in1, lane, wave, act0, act1, headout, dump);
 
         // ---- mixtures: lane j < 3K of pixel q prepares component j % K of channel j / K
-        for (int jj = j; jj < 3 * K; jj += 16) {      // one pass unless K > 5
+        auto prepare = [&](int jj) __attribute__((always_inline)) {
             const int ch = jj / K, k = jj - K * ch;
             const float* hc = headout + q * D::kHeadStride + ch * HS;
             float pk, mk, ak;
@@ -1210,6 +1210,11 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
             }
             float* dst = cpbuf + (q * 3 + ch) * D::kCpStride + k;
             dst[0] = pk; dst[K] = mk; dst[2 * K] = ak;
+        };
+        if constexpr (3 * K <= 16) {
+            if (j < 3 * K) prepare(j);
+        } else {
+            for (int jj = j; jj < 3 * K; jj += 16) prepare(jj);      // two passes for the first lanes
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
         __builtin_amdgcn_wave_barrier();
