@@ -696,9 +696,6 @@ compact_scan_kernel(const uint32_t* __restrict__ slabs, const uint32_t* __restri
 //             in global memory that the band below polls
 // ---------------------------------------------------------------------------
 constexpr int kDecThreads = 256;
-// Time of a decode step when two workgroups share a CU, in percent of the time when one has it alone (measured
-// with batches of 9 to 48 images of 768x512: 40 images take the same time either way, 48 are 8 % faster shared).
-constexpr unsigned kDecodeSharedStepPercent = 195;
 
 // decode LDS: the CDF table, two activation buffers, head outputs, mixtures, ring
 template <class Net>
@@ -728,6 +725,23 @@ struct DecLds {
     static constexpr int kMiscOff = kRingOff + 18 * kRingRowElems * 2; // ticket, abort flag
     static constexpr int kDumpOff = (kMiscOff + 64 + 15) / 16 * 16;    // 2 KB nobody reads: stores of out-blocks a wave does not own
     static constexpr int kBytes = kDumpOff + 2 * 64 * 16;
+    // Two workgroups per CU have 256 registers per lane each, too few for the whole of a wave's weight slices: there
+    // the biases, and the weights of the first layer and of the head where two workgroups' LDS then still fits a CU,
+    // are kept in LDS behind the above and read when used.
+    static constexpr int kBiasBytes = Layout<Net>::kLutOff - Layout<Net>::kWeightBytes;
+    static constexpr int kFirstBytes = Net::ob(0) * Net::kb(0) * kBlockBytes;
+    static constexpr int kHeadBytes = Net::ob(Net::kLayers - 1) * Net::kb(Net::kLayers - 1) * kBlockBytes;
+    static constexpr bool kBiasInLds = (Net::kSharedCuLds & 1) != 0;
+    static constexpr int kBiasLds = kBiasInLds ? kBiasBytes : 0;
+    static constexpr bool kFirstInLds = (Net::kSharedCuLds & 2) != 0 && 2 * (kBytes + kBiasLds + kFirstBytes) <= kLdsBytes;
+    static constexpr int kFirstLds = kFirstInLds ? kFirstBytes : 0;
+    static constexpr bool kHeadInLds = (Net::kSharedCuLds & 4) != 0 && 2 * (kBytes + kBiasLds + kFirstLds + kHeadBytes) <= kLdsBytes;
+    static constexpr int kBiasOff = kBytes;
+    static constexpr int kFirstOff = kBiasOff + kBiasLds;
+    static constexpr int kHeadWOff = kFirstOff + kFirstLds;
+    static constexpr int kBytesShared = kHeadWOff + (kHeadInLds ? kHeadBytes : 0);
+    static constexpr bool kTwoFit = 2 * kBytesShared <= kLdsBytes;      // else a CU holds one workgroup whatever the launch asks
+    static_assert(kBytes % 16 == 0 && kBiasBytes % 16 == 0, "vector alignment");
     static_assert(kAct0Off % 16 == 0 && kHeadOff % 16 == 0 && kCpOff % 16 == 0, "vector alignment");
     static_assert((16 * kHS) % 16 == 0 && (kRingRowElems * 2) % 4 == 0, "vector alignment");
     // A ring row is read by the two rows below it, which trail by delay and 2 * delay columns and
@@ -828,19 +842,34 @@ __device__ __forceinline__ void reader_refill(RowReader& rd, int j) {
 // This wave's weight slices of one layer: out-blocks ob = wave + 4 s.  Where the
 // wave has no such block (ob >= NOB) it holds a copy of the layer's last block
 // and its results are discarded.
-template <int NOB, int NKB, int SLOTS>
+// W_LDS / B_LDS: the weights / biases stay where w / b point (a copy in LDS) and are read when used.
+template <int NOB, int NKB, int SLOTS, bool W_LDS, bool B_LDS>
 struct WaveLayer {
-    u32x4_t a[SLOTS][NKB];
-    f32x4_t bias[SLOTS];
+    u32x4_t a[W_LDS ? 1 : SLOTS][W_LDS ? 1 : NKB];
+    f32x4_t bias[B_LDS ? 1 : SLOTS];
+    const uint8_t* w_at;     // + this lane's 16 bytes
+    const float* b_at;       // + this lane group's four floats
     __device__ __forceinline__ void load(const uint8_t* __restrict__ w, const float* __restrict__ b, int lane, int wave) {
+        w_at = w + lane * 16;
+        b_at = b + 4 * (lane >> 4);
 #pragma unroll
         for (int s = 0; s < SLOTS; ++s) {
             const int ob = min(wave + 4 * s, NOB - 1);
-            bias[s] = *reinterpret_cast<const f32x4_t*>(b + 16 * ob + 4 * (lane >> 4));
+            if constexpr (!B_LDS) bias[s] = *reinterpret_cast<const f32x4_t*>(b_at + 16 * ob);
+            if constexpr (!W_LDS) {
 #pragma unroll
-            for (int kb = 0; kb < NKB; ++kb)
-                a[s][kb] = *reinterpret_cast<const u32x4_t*>(w + ((ob * NKB + kb) * 64 + lane) * 16);
+                for (int kb = 0; kb < NKB; ++kb)
+                    a[s][kb] = *reinterpret_cast<const u32x4_t*>(w_at + (ob * NKB + kb) * (64 * 16));
+            }
         }
+    }
+    __device__ __forceinline__ u32x4_t A(int s, int kb, int wave) const {
+        if constexpr (W_LDS) return *reinterpret_cast<const u32x4_t*>(w_at + (min(wave + 4 * s, NOB - 1) * NKB + kb) * (64 * 16));
+        else return a[s][kb];
+    }
+    __device__ __forceinline__ f32x4_t B(int s, int wave) const {
+        if constexpr (B_LDS) return *reinterpret_cast<const f32x4_t*>(b_at + 16 * min(wave + 4 * s, NOB - 1));
+        else return bias[s];
     }
 };
 
@@ -851,8 +880,8 @@ struct WaveLayer {
 // the activation and split of one block run in the shadow of the next block's MFMAs.
 // A block this wave does not own (ob >= NOB) is computed on a copy of the layer's
 // last block (or not at all, SKIP_UNOWNED) and stored to `dump`.
-template <int NOB, int NKB, int SLOTS, bool SPLIT_IN, bool LEAKY, bool SKIP_UNOWNED>
-__device__ __forceinline__ void dec_hidden_layer(const WaveLayer<NOB, NKB, SLOTS>& wl, int lane, int wave,
+template <int NOB, int NKB, int SLOTS, bool W_LDS, bool B_LDS, bool SPLIT_IN, bool LEAKY, bool SKIP_UNOWNED>
+__device__ __forceinline__ void dec_hidden_layer(const WaveLayer<NOB, NKB, SLOTS, W_LDS, B_LDS>& wl, int lane, int wave,
                                                  const u32x4_t (&in)[NKB][2], uint8_t* __restrict__ act_out,
                                                  uint8_t* __restrict__ dump) {
     auto finish = [&](int s, const f32x4_t& acc) {
@@ -868,20 +897,29 @@ __device__ __forceinline__ void dec_hidden_layer(const WaveLayer<NOB, NKB, SLOTS
     f32x4_t acc[SLOTS];
 #pragma unroll
     for (int s = 0; s < SLOTS; ++s) {
-        acc[s] = wl.bias[s];
+        acc[s] = wl.B(s, wave);
         // Two workgroups per CU share the matrix cores: there a wave without this block skips its MFMAs
         // (`wave` is a scalar, the dump store below still runs).  With one workgroup per CU the pipe is
         // idle anyway, and a branch here would keep the previous block's split from running under them.
         if (!SKIP_UNOWNED || 4 * s + 3 < NOB || wave + 4 * s < NOB) {
 #pragma unroll
             for (int kb = 0; kb < NKB; ++kb) {
-                acc[s] = mfma16(wl.a[s][kb], in[kb][0], acc[s]);
-                if (SPLIT_IN) acc[s] = mfma16(wl.a[s][kb], in[kb][1], acc[s]);
+                const u32x4_t a = wl.A(s, kb, wave);
+                acc[s] = mfma16(a, in[kb][0], acc[s]);
+                if (SPLIT_IN) acc[s] = mfma16(a, in[kb][1], acc[s]);
             }
         }
-        if (s > 0) finish(s - 1, acc[s - 1]);
+        // Where that branch exists, a block is finished before the next block's branch, never behind it: the wait
+        // states between an MFMA and the first read of its result are counted along the instruction stream as laid
+        // out, and a taken branch straight after the MFMA would skip them (seen as wrong activations now and then).
+        if constexpr (SKIP_UNOWNED) {
+            finish(s, acc[s]);
+            __builtin_amdgcn_sched_barrier(0);      // the next block's instructions stay behind this one's
+        } else {
+            if (s > 0) finish(s - 1, acc[s - 1]);
+        }
     }
-    finish(SLOTS - 1, acc[SLOTS - 1]);
+    if constexpr (!SKIP_UNOWNED) finish(SLOTS - 1, acc[SLOTS - 1]);
 }
 
 template <int NKB>
@@ -897,16 +935,23 @@ __device__ __forceinline__ void dec_load_act(const uint8_t* __restrict__ act, in
 // the per-step evaluation that hands activations from layer to layer through LDS
 // (hidden layer l writes activation buffer l & 1).  Ends behind a barrier with the
 // raw head outputs in `headout`.
-template <class Net, int L, bool END = (L == Net::kLayers)>
+// SHARED: the workgroup shares its CU with another (see DecLds): `lds` then holds the pieces kept there.
+template <class Net, bool SHARED, int L, bool END = (L == Net::kLayers)>
 struct WaveNet {
     static constexpr int NOB = Net::ob(L), NKB = Net::kb(L), SLOTS = (NOB + 3) / 4;
     static constexpr bool kHead = L == Net::kLayers - 1;
-    WaveLayer<NOB, NKB, SLOTS> wl;
-    WaveNet<Net, L + 1> rest;
+    static constexpr bool kWLds = SHARED && ((L == 0 && DecLds<Net>::kFirstInLds) || (kHead && DecLds<Net>::kHeadInLds));
+    static constexpr bool kBLds = SHARED && DecLds<Net>::kBiasInLds;
+    WaveLayer<NOB, NKB, SLOTS, kWLds, kBLds> wl;
+    WaveNet<Net, SHARED, L + 1> rest;
 
-    __device__ __forceinline__ void load(const uint8_t* __restrict__ model, int lane, int wave) {
-        wl.load(model + Layout<Net>::w_off(L), reinterpret_cast<const float*>(model + Layout<Net>::b_off(L)), lane, wave);
-        rest.load(model, lane, wave);
+    __device__ __forceinline__ void load(const uint8_t* __restrict__ model, const uint8_t* __restrict__ lds, int lane, int wave) {
+        using Lay = Layout<Net>;
+        using D = DecLds<Net>;
+        const uint8_t* w = kWLds ? lds + (L == 0 ? D::kFirstOff : D::kHeadWOff) : model + Lay::w_off(L);
+        const uint8_t* b = kBLds ? lds + D::kBiasOff + (Lay::b_off(L) - Lay::kWeightBytes) : model + Lay::b_off(L);
+        wl.load(w, reinterpret_cast<const float*>(b), lane, wave);
+        rest.load(model, lds, lane, wave);
     }
     template <bool SKIP_UNOWNED>
     __device__ __forceinline__ void run(const u32x4_t (&in)[NKB][2], int lane, int wave, uint8_t* __restrict__ act0,
@@ -917,11 +962,12 @@ struct WaveNet {
             constexpr int HS = Layout<Net>::kHeadSlots;
 #pragma unroll
             for (int slot = 0; slot < SLOTS; ++slot) {
-                f32x4_t acc = wl.bias[slot];
+                f32x4_t acc = wl.B(slot, wave);
 #pragma unroll
                 for (int kb = 0; kb < NKB; ++kb) {
-                    acc = mfma16(wl.a[slot][kb], in[kb][0], acc);
-                    acc = mfma16(wl.a[slot][kb], in[kb][1], acc);
+                    const u32x4_t a = wl.A(slot, kb, wave);
+                    acc = mfma16(a, in[kb][0], acc);
+                    acc = mfma16(a, in[kb][1], acc);
                 }
                 const int ob = wave + 4 * slot;
                 if (ob < NOB)
@@ -930,7 +976,7 @@ struct WaveNet {
             lds_barrier();
         } else {
             uint8_t* out = (L & 1) ? act1 : act0;
-            dec_hidden_layer<NOB, NKB, SLOTS, (L > 0), Net::kLeaky, SKIP_UNOWNED>(wl, lane, wave, in, out, dump);
+            dec_hidden_layer<NOB, NKB, SLOTS, kWLds, kBLds, (L > 0), Net::kLeaky, SKIP_UNOWNED>(wl, lane, wave, in, out, dump);
             lds_barrier();
             u32x4_t nxt[Net::kb(L + 1)][2];
             dec_load_act<Net::kb(L + 1)>(out, lane, nxt);
@@ -941,9 +987,9 @@ struct WaveNet {
         }
     }
 };
-template <class Net, int L>
-struct WaveNet<Net, L, true> {
-    __device__ __forceinline__ void load(const uint8_t* __restrict__, int, int) {}
+template <class Net, bool SHARED, int L>
+struct WaveNet<Net, SHARED, L, true> {
+    __device__ __forceinline__ void load(const uint8_t* __restrict__, const uint8_t* __restrict__, int, int) {}
 };
 
 // Symbol search by the 16 lanes (j = 0..15) of one pixel: two rounds of 16
@@ -1018,9 +1064,18 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
         const float2* src = reinterpret_cast<const float2*>(model + Lay::kLutOff);
         for (int i = tid; i < kLutEntries + 1; i += kDecThreads) lut[i] = src[i];
     }
-    // this wave's weights stay in registers, for every band the workgroup decodes
-    WaveNet<Net, 0> net;
-    net.load(model, lane, wave);
+    if constexpr (MINBLOCKS > 1) {
+        auto stage = [&](int dst_off, int src_off, int bytes) {
+            for (int i = tid * 16; i < bytes; i += kDecThreads * 16)
+                *reinterpret_cast<u32x4_t*>(lds + dst_off + i) = *reinterpret_cast<const u32x4_t*>(model + src_off + i);
+        };
+        if constexpr (D::kBiasInLds) stage(D::kBiasOff, Lay::kWeightBytes, D::kBiasBytes);
+        if constexpr (D::kFirstInLds) stage(D::kFirstOff, Lay::w_off(0), D::kFirstBytes);
+        if constexpr (D::kHeadInLds) stage(D::kHeadWOff, Lay::w_off(Net::kLayers - 1), D::kHeadBytes);
+    }
+    // this wave's weights stay in registers (all that is not staged above), for every band the workgroup decodes
+    WaveNet<Net, (MINBLOCKS > 1), 0> net;
+    net.load(model, lds, lane, wave);
     const float lut_scale = *reinterpret_cast<const float*>(model + Lay::kLutScaleOff);
     const int total_bands = n * nbands;
 
@@ -1546,7 +1601,7 @@ int pack_model(const uint8_t* p, size_t blob_bytes, uint32_t dist, std::vector<u
 template <class Net>
 bool set_kernel_attributes() {
     constexpr int enc = Layout<Net>::kModelBytes + params_stage_bytes<Net>(1024), dec = DecLds<Net>::kBytes;
-    static_assert(params_stage_pixels<Net>(1024) >= 1 && enc <= kLdsBytes && dec <= kLdsBytes,
+    static_assert(params_stage_pixels<Net>(1024) >= 1 && enc <= kLdsBytes && dec <= kLdsBytes && DecLds<Net>::kBytesShared <= kLdsBytes,
                   "the network does not fit a compute unit's LDS");
     bool ok = true;
     ok = ok && hipFuncSetAttribute(reinterpret_cast<const void*>(&encode_kernel<Net, 1, 512>),
@@ -1560,7 +1615,7 @@ bool set_kernel_attributes() {
     ok = ok && hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_kernel<Net, 1>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, dec) == hipSuccess;
     ok = ok && hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_kernel<Net, 2>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, dec) == hipSuccess;
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, DecLds<Net>::kBytesShared) == hipSuccess;
     return ok;
 }
 
@@ -1620,21 +1675,25 @@ void launch_decode(pcc_ctx* ctx, const uint8_t* d_stream, size_t nbytes, int n, 
     constexpr int kLds = DecLds<Net>::kBytes;
     const uint64_t bands = (uint64_t)n * nbands;                      // dims_ok: below 2^31
     const uint64_t cus = ctx->num_cus > 0 ? (uint64_t)ctx->num_cus : 256u;
-    // One workgroup per CU decodes a step in the shortest time; two per CU take kDecodeSharedStepPercent / 100
-    // as long per step but decode twice as many bands at once.  An image is a chain of `chain` steps whatever the
-    // machine does; the job is `work` band-steps.  Two per CU pay when the work per place, not the chain, sets the time.
+    // One workgroup per CU decodes a step in the shortest time; two per CU take Net::kSharedStepPercent / 100 as
+    // long per step when both are busy (a fifth less when most CUs hold one busy workgroup) but decode twice as
+    // many bands at once.  An image is a chain of `chain` steps whatever the machine does; the job is `work`
+    // band-steps, which one workgroup per CU gets through about 12 % slower than evenly once there are more bands
+    // than CUs.  Two per CU pay when the work per place, not the chain, sets the time (measured, batches of 12 to 48
+    // images of 768x512: from 20 images on).
     const int band_rows = H < kBandRows ? H : kBandRows;
     const uint64_t chain = (uint64_t)W + (uint64_t)Net::kDelay * (H - 1);
     const uint64_t work = bands * ((uint64_t)W + (uint64_t)Net::kDelay * (band_rows - 1));
-    const uint64_t alone = std::max(chain, (work + cus - 1) / cus) * 100u;
-    const uint64_t shared = std::max(chain, (work + 2 * cus - 1) / (2 * cus)) * kDecodeSharedStepPercent;
-    const bool two = ctx->decode_variant == 2 || (ctx->decode_variant == 0 && bands > cus && shared < alone);
+    const uint64_t per_cu = (work + cus - 1) / cus, per_half_cu = (work + 2 * cus - 1) / (2 * cus);
+    const uint64_t alone = std::max(chain, per_cu) * (per_cu > chain ? 112u : 100u);
+    const uint64_t shared = std::max(chain * (Net::kSharedStepPercent - 20u), per_half_cu * Net::kSharedStepPercent);
+    const bool two = ctx->decode_variant == 2 || (ctx->decode_variant == 0 && DecLds<Net>::kTwoFit && bands > cus && shared < alone);
     const uint32_t grid = (uint32_t)std::min(bands, two ? 2 * cus : cus);
     if (!two)
         hipLaunchKernelGGL((decode_kernel<Net, 1>), dim3(grid), dim3(kDecThreads), kLds, st, ctx->d_model, d_stream,
                            (uint64_t)nbytes, n, H, W, nbands, ctx->dist, d_img_out, d_mail, ctx->d_status, spin_limit);
     else
-        hipLaunchKernelGGL((decode_kernel<Net, 2>), dim3(grid), dim3(kDecThreads), kLds, st, ctx->d_model, d_stream,
+        hipLaunchKernelGGL((decode_kernel<Net, 2>), dim3(grid), dim3(kDecThreads), DecLds<Net>::kBytesShared, st, ctx->d_model, d_stream,
                            (uint64_t)nbytes, n, H, W, nbands, ctx->dist, d_img_out, d_mail, ctx->d_status, spin_limit);
 }
 

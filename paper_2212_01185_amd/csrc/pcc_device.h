@@ -51,6 +51,14 @@ struct NetWorkload {
     static constexpr int kRingCols = 8;       // decoder ring columns (power of two)
     static constexpr int kRingPad = 2;        // extra 16-bit elements per ring row
     static constexpr bool kLeaky = false;
+    // Decoder with two workgroups per CU (256 registers per lane each): what of a wave's weight slices is then read
+    // from a copy in LDS instead of held in registers, chosen by measurement (batches of 48 images of 768x512): LDS
+    // copies cost time too, so a few spilled registers can be the better deal.  1: the biases, 2: the first layer's
+    // weights, 4: the head's.
+    static constexpr int kSharedCuLds = 6;
+    // Time of a decode step when both workgroups of a CU are busy, in percent of a step of a workgroup that has its
+    // CU alone (measured the same way; the host chooses between the two launches with it).
+    static constexpr unsigned kSharedStepPercent = 158;
     __host__ __device__ static constexpr int dim(int l) { return l == 0 ? 30 : l == 1 ? 160 : l == 2 ? 160 : l == 3 ? 128 : 60; }
     __host__ __device__ static constexpr int ob(int l) { return l == 0 ? 10 : l == 1 ? 10 : l == 2 ? 8 : 4; }
     __host__ __device__ static constexpr int kb(int l) { return l == 0 ? 1 : l == 1 ? 5 : l == 2 ? 5 : 4; }
@@ -85,6 +93,8 @@ struct NetPaper {
     static constexpr int kRingCols = 16;
     static constexpr int kRingPad = 4;
     static constexpr bool kLeaky = true;
+    static constexpr int kSharedCuLds = 0;      // a few registers spill instead: faster than any LDS copy here
+    static constexpr unsigned kSharedStepPercent = 145;
     __host__ __device__ static constexpr int dim(int l) { return l == 0 ? 36 : l == 5 ? 36 : 128; }
     __host__ __device__ static constexpr int ob(int l) { return l == 4 ? 3 : 8; }
     __host__ __device__ static constexpr int kb(int l) { return l == 0 ? 2 : 4; }
@@ -111,6 +121,7 @@ struct NetDiagonal : NetPaper {
     static constexpr int kReach1 = 0, kReach2 = 1;   // row r-1 is read up to column c, row r-2 up to c+1
     static constexpr int kRingCols = 8;
     static constexpr int kRingPad = 4;
+    static constexpr unsigned kSharedStepPercent = 138;
     __host__ __device__ static constexpr bool run_desc(int kbi, int g, int half, int& dr, int& off) {
         if (kbi == 0) {
             if (g == 0) { dr = -2; off = 4 * half; }                          // row r-2, bytes 0..7
@@ -147,6 +158,8 @@ struct NetAblation : NetPaper {
                   "unsupported shape");
     static constexpr int kLayers = LAYERS;
     static constexpr int K = MIXTURES;
+    static constexpr int kSharedCuLds = MIXTURES >= 7 ? 7 : MIXTURES >= 5 ? 6 : NetPaper::kSharedCuLds;
+    static constexpr unsigned kSharedStepPercent = MIXTURES >= 7 ? 186 : MIXTURES >= 5 ? 153 : 147;
     __host__ __device__ static constexpr int dim(int l) { return l == 0 ? 36 : l == LAYERS ? 12 * MIXTURES : C; }
     __host__ __device__ static constexpr int ob(int l) { return (dim(l + 1) + 15) / 16; }
     __host__ __device__ static constexpr int kb(int l) { return (dim(l) + 31) / 32; }
