@@ -689,7 +689,7 @@ compact_scan_kernel(const uint32_t* __restrict__ slabs, const uint32_t* __restri
 //   network   the 16 pixels form one MFMA tile; each wave computes a quarter
 //             of every layer's out-blocks with its weight slices held in
 //             registers for the whole kernel, and the layers meet in LDS
-//   search    16 lanes per pixel find the symbol with two 16-way rounds of
+//   search    16 lanes per pixel find the symbol with two 16-way sweeps of
 //             Cq evaluations per channel (R, then G given R, then B given R,G)
 //   publish   the pixel goes to the LDS ring (next steps' neighbourhoods), to
 //             the output image and, for the band's last two rows, to a mailbox
@@ -992,13 +992,13 @@ struct WaveNet<Net, SHARED, L, true> {
     __device__ __forceinline__ void load(const uint8_t* __restrict__, const uint8_t* __restrict__, int, int) {}
 };
 
-// Symbol search by the 16 lanes (j = 0..15) of one pixel: two rounds of 16
+// Symbol search by the 16 lanes (j = 0..15) of one pixel: two sweeps of 16
 // evaluations.  All lanes of the group return the same x, start, freq.
 template <int K>
 __device__ __forceinline__ int group_search(const ChanParams<K>& cp, uint32_t slot, const float2* __restrict__ lut, int lane,
                                             uint32_t& start, uint32_t& freq) {
     const int j = lane & 15, shift = lane & 48;
-    // round 1: Cq(16 j); lanes 0..b satisfy Cq <= slot (Cq is increasing and Cq(0) = 0).
+    // first sweep: Cq(16 j); lanes 0..b satisfy Cq <= slot (Cq is increasing and Cq(0) = 0).
     // Lane 0 evaluates too and discards the value: no branch.
     const uint32_t e1 = cq_eval<K>(cp, 16 * j, lut);
     const uint32_t c1 = j == 0 ? 0u : e1;
@@ -1006,7 +1006,7 @@ __device__ __forceinline__ int group_search(const ChanParams<K>& cp, uint32_t sl
     const int b = __popcll((__ballot(p1) >> shift) & 0xFFFFull) - 1;
     const uint32_t lo1 = row_allmax(p1 ? c1 : 0u);           // Cq(16 b)
     const uint32_t hi1 = row_allmin(p1 ? 65536u : c1);       // Cq(16 b + 16)
-    // round 2: Cq(16 b + j)
+    // second sweep: Cq(16 b + j)
     const uint32_t e2 = cq_eval<K>(cp, 16 * b + j, lut);
     const uint32_t c2 = j == 0 ? lo1 : e2;
     const bool p2 = c2 <= slot;
