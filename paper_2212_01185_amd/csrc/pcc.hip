@@ -240,6 +240,15 @@ encode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ img
         }
         f32x4_t out[T][Lay::kHeadOB];
         mlp_from<Net, T, (T == 1 && THREADS <= 512), 0>(lds + opaque_zero(), lane, in, out);
+        // The head's results are first read behind branches (which outputs are wanted, border tiles).  The wait
+        // states an MFMA's result needs are counted along the instruction stream as laid out, not along a taken
+        // branch, so the accumulators are made to settle here, in straight-line code.
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+#pragma unroll
+            for (int ob = 0; ob < Lay::kHeadOB; ++ob) asm volatile("" : "+v"(out[t][ob]));
+        }
+        asm volatile("s_nop 7" ::: "memory");
 
 #pragma unroll
         for (int t = 0; t < T; ++t) {
