@@ -46,10 +46,17 @@ struct EncodeVariant { int tiles, threads; };
 // pcc_encode_probs: pixels of a tile whose head outputs a wave stages in LDS at a time (four, or as many as fit
 // beside the model image: two or one for the largest networks), and the bytes that takes for the workgroup.
 constexpr int kLdsBytes = 160 * 1024;
+// What the pixel kernel keeps in LDS: the whole model image, or, where that does not fit, the image without the CDF
+// table (the last thing in it), which the epilogue then reads from global memory.
+template <class Net>
+constexpr bool encode_table_in_lds() { return Layout<Net>::kModelBytes <= kLdsBytes; }
+template <class Net>
+constexpr int encode_model_lds_bytes() { return encode_table_in_lds<Net>() ? Layout<Net>::kModelBytes : Layout<Net>::kLutOff; }
+// 0: no room for a staging area; the head outputs are then stored value by value.
 template <class Net>
 constexpr int params_stage_pixels(int threads) {
     for (int px = 4; px >= 1; px /= 2)
-        if (Layout<Net>::kModelBytes + (threads / 64) * px * Net::dim(Net::kLayers) * 4 <= kLdsBytes) return px;
+        if (encode_model_lds_bytes<Net>() + (threads / 64) * px * Net::dim(Net::kLayers) * 4 <= kLdsBytes) return px;
     return 0;
 }
 template <class Net>
@@ -169,10 +176,11 @@ encode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ img
     using Lay = Layout<Net>;
     constexpr int K = Net::K, KB0 = Net::kb(0), HEAD = Net::dim(Net::kLayers);
     extern __shared__ __align__(16) uint8_t lds[];
-    copy_to_lds(lds, model, Lay::kModelBytes);
+    copy_to_lds(lds, model, encode_model_lds_bytes<Net>());
     __syncthreads();
-    const float2* lut = reinterpret_cast<const float2*>(lds + Lay::kLutOff);
-    const float lut_scale = *reinterpret_cast<const float*>(lds + Lay::kLutScaleOff);
+    const uint8_t* table_at = encode_table_in_lds<Net>() ? lds : model;
+    const float2* lut = reinterpret_cast<const float2*>(table_at + Lay::kLutOff);
+    const float lut_scale = *reinterpret_cast<const float*>(table_at + Lay::kLutScaleOff);
     const int lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // a scalar: the item's row and strip are scalars too
     const int g = lane >> 4, nl = lane & 15;
@@ -255,14 +263,15 @@ encode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ img
             const int c = c0 + 16 * t + nl;
             const bool live = c >= 0;
             const uint32_t p = rowg * (uint32_t)W + (uint32_t)c;
-            if (params != nullptr && ((uintptr_t)params & 15u) == 0) {
+            constexpr int kStagePixels = params_stage_pixels<Net>(THREADS);
+            constexpr int PX = kStagePixels > 0 ? kStagePixels : 1;       // (the block below is dead code when there is no room)
+            if (kStagePixels > 0 && params != nullptr && ((uintptr_t)params & 15u) == 0) {
                 // The tile's head outputs are HEAD consecutive floats per pixel, 16 consecutive pixels: they go
                 // through a staging area of this wave in LDS, PX pixels at a time, and leave as
                 // 16-byte stores of consecutive lanes (stored straight from the registers, a lane's values lie
                 // 4 bytes here and 4 bytes there, 240 bytes apart from its neighbour's).  LDS takes a wave's
                 // instructions in order, so the reads see the writes of the same pass.
-                constexpr int PX = params_stage_pixels<Net>(THREADS);
-                float* stage = reinterpret_cast<float*>(lds + Lay::kModelBytes) + wave * (PX * HEAD);
+                float* stage = reinterpret_cast<float*>(lds + encode_model_lds_bytes<Net>()) + wave * (PX * HEAD);
 #pragma unroll
                 for (int pass = 0; pass < 16 / PX; ++pass) {
                     if (nl / PX == pass) {
@@ -1401,7 +1410,7 @@ cdf_tables_kernel(const uint8_t* __restrict__ model, const float* __restrict__ p
 // ===========================================================================
 using namespace pcc;
 
-enum { kNetWorkload = 0, kNetPaper = 1, kNetDiagonal = 2, kNetFewerLayers = 3, kNetFewerFilters = 4, kNetMoreMixtures = 5, kNetMostMixtures = 6 };
+enum { kNetWorkload = 0, kNetPaper = 1, kNetDiagonal = 2, kNetFewerLayers = 3, kNetFewerFilters = 4, kNetMoreMixtures = 5, kNetMostMixtures = 6, kNetMoreLayers = 7 };
 
 struct pcc_ctx {
     int device = 0;
@@ -1521,6 +1530,7 @@ auto with_net(int net, F&& f) {
         case kNetFewerFilters: return f(NetFewerFilters{});
         case kNetMoreMixtures: return f(NetMoreMixtures{});
         case kNetMostMixtures: return f(NetMostMixtures{});
+        case kNetMoreLayers: return f(NetMoreLayers{});
         default: return f(NetWorkload{});
     }
 }
@@ -1609,8 +1619,9 @@ int pack_model(const uint8_t* p, size_t blob_bytes, uint32_t dist, std::vector<u
 
 template <class Net>
 bool set_kernel_attributes() {
-    constexpr int enc = Layout<Net>::kModelBytes + params_stage_bytes<Net>(1024), dec = DecLds<Net>::kBytes;
-    static_assert(params_stage_pixels<Net>(1024) >= 1 && enc <= kLdsBytes && dec <= kLdsBytes && DecLds<Net>::kBytesShared <= kLdsBytes,
+    constexpr int stage = std::max(params_stage_bytes<Net>(256), std::max(params_stage_bytes<Net>(512), params_stage_bytes<Net>(1024)));
+    constexpr int enc = encode_model_lds_bytes<Net>() + stage, dec = DecLds<Net>::kBytes;
+    static_assert(enc <= kLdsBytes && dec <= kLdsBytes && DecLds<Net>::kBytesShared <= kLdsBytes,
                   "the network does not fit a compute unit's LDS");
     bool ok = true;
     ok = ok && hipFuncSetAttribute(reinterpret_cast<const void*>(&encode_kernel<Net, 1, 512>),
@@ -1647,7 +1658,7 @@ uint32_t encode_blocks(const pcc_ctx* ctx, int n, int H, uint32_t strips, uint32
 template <class Net>
 int launch_encode(pcc_ctx* ctx, const uint8_t* d_img, int n, int H, int W, uint32_t* sf, float* params, float* bits,
                   uint64_t* sf_tagged, uint32_t reserve_cus, uint32_t strip_begin, uint32_t strip_count, hipStream_t st) {
-    const int kLds = Layout<Net>::kModelBytes + (params != nullptr ? params_stage_bytes<Net>(kEncodeVariants[ctx->encode_variant].threads) : 0);
+    const int kLds = encode_model_lds_bytes<Net>() + (params != nullptr ? params_stage_bytes<Net>(kEncodeVariants[ctx->encode_variant].threads) : 0);
     const uint32_t blocks = encode_blocks(ctx, n, H, strip_count, reserve_cus);
     switch (ctx->encode_variant) {
         case 0:
@@ -1754,6 +1765,7 @@ int pcc_create(pcc_ctx** out, const void* h_blob, size_t blob_bytes, int hip_dev
     else if (header_matches<NetFewerFilters>(p)) net = kNetFewerFilters;
     else if (header_matches<NetMoreMixtures>(p)) net = kNetMoreMixtures;
     else if (header_matches<NetMostMixtures>(p)) net = kNetMostMixtures;
+    else if (header_matches<NetMoreLayers>(p)) net = kNetMoreLayers;
     else return PCC_E_BLOB;
 
     std::vector<uint8_t> image;

@@ -148,8 +148,9 @@ struct NetDiagonal : NetPaper {
 
 // The paper's network with another number of mixture components, filters or layers (the ablations of
 // Sec. IV-E; wavefront order): 36 -> C -> ... -> C -> 12 K, LAYERS weight layers, LeakyReLU.  K is 3, 5
-// (the head layouts above) or 7, C a multiple of 32; the packed model must fit the encoder's LDS beside the
-// staging area (checked where the kernels are set up), which six layers of 128 filters do not.
+// (the head layouts above) or 7, C a multiple of 32; the packed weights and biases must fit the encoder's LDS
+// (checked where the kernels are set up).  Six layers of 128 filters fit without the CDF table, which that
+// shape's encoder reads from global memory.
 // K = 7 (six out-blocks, 24 registers): groups 0..2 hold their channel's 21 parameters, group 3 the
 // 21 coupling coefficients.
 template <int MIXTURES, int C, int LAYERS>
@@ -158,7 +159,7 @@ struct NetAblation : NetPaper {
                   "unsupported shape");
     static constexpr int kLayers = LAYERS;
     static constexpr int K = MIXTURES;
-    static constexpr int kSharedCuLds = MIXTURES >= 7 ? 7 : MIXTURES >= 5 ? 6 : NetPaper::kSharedCuLds;
+    static constexpr int kSharedCuLds = MIXTURES >= 7 ? 7 : (MIXTURES >= 5 || LAYERS >= 6) ? 6 : NetPaper::kSharedCuLds;
     static constexpr unsigned kSharedStepPercent = MIXTURES >= 7 ? 186 : MIXTURES >= 5 ? 153 : 147;
     __host__ __device__ static constexpr int dim(int l) { return l == 0 ? 36 : l == LAYERS ? 12 * MIXTURES : C; }
     __host__ __device__ static constexpr int ob(int l) { return (dim(l + 1) + 15) / 16; }
@@ -173,6 +174,7 @@ using NetFewerLayers = NetAblation<3, 128, 4>;
 using NetFewerFilters = NetAblation<3, 64, 5>;
 using NetMoreMixtures = NetAblation<5, 128, 5>;
 using NetMostMixtures = NetAblation<7, 128, 5>;
+using NetMoreLayers = NetAblation<3, 128, 6>;
 
 // Every canonical first-layer input sits in exactly one k-slot.
 template <class Net>
@@ -189,7 +191,7 @@ constexpr bool inputs_placed_once() {
 static_assert(inputs_placed_once<NetWorkload>() && inputs_placed_once<NetPaper>() && inputs_placed_once<NetDiagonal>() &&
                   inputs_placed_once<NetFewerLayers>() &&
                   inputs_placed_once<NetFewerFilters>() && inputs_placed_once<NetMoreMixtures>() &&
-                  inputs_placed_once<NetMostMixtures>(),
+                  inputs_placed_once<NetMostMixtures>() && inputs_placed_once<NetMoreLayers>(),
               "first-layer slot map");
 
 constexpr int kBlockBytes = 64 * 16;  // one (out-block, k-block) A operand: 64 lanes x 8 bf16
