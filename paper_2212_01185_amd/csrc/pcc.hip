@@ -868,16 +868,16 @@ struct WaveLayer {
     const uint8_t* w_at;     // + this lane's 16 bytes
     const float* b_at;       // + this lane group's four floats
     __device__ __forceinline__ void load(const uint8_t* __restrict__ w, const float* __restrict__ b, int lane, int wave) {
-        w_at = w + lane * 16;
-        b_at = b + 4 * (lane >> 4);
+        if constexpr (W_LDS) w_at = w + lane * 16;
+        if constexpr (B_LDS) b_at = b + 4 * (lane >> 4);
 #pragma unroll
         for (int s = 0; s < SLOTS; ++s) {
             const int ob = min(wave + 4 * s, NOB - 1);
-            if constexpr (!B_LDS) bias[s] = *reinterpret_cast<const f32x4_t*>(b_at + 16 * ob);
+            if constexpr (!B_LDS) bias[s] = *reinterpret_cast<const f32x4_t*>(b + 16 * ob + 4 * (lane >> 4));
             if constexpr (!W_LDS) {
 #pragma unroll
                 for (int kb = 0; kb < NKB; ++kb)
-                    a[s][kb] = *reinterpret_cast<const u32x4_t*>(w_at + (ob * NKB + kb) * (64 * 16));
+                    a[s][kb] = *reinterpret_cast<const u32x4_t*>(w + ((ob * NKB + kb) * 64 + lane) * 16);
             }
         }
     }
