@@ -40,10 +40,11 @@
  *     Eq. (7).  A pass decodes the anti-diagonal r + c = t; the inputs of the
  *     three neighbours not yet decoded then, (r-2,c+2), (r-1,c+1), (r-1,c+2),
  *     carry copies of pixel (r-1,c) (zero in the first row), at the encoder too;
- *   - five shapes of the ablations of Sec. IV-E, each the second model with
+ *   - the six shapes of the ablations of Sec. IV-E, each the second model with
  *     one hyper-parameter changed: K = 5 (36 -> 128 x 4 -> 60), K = 7
- *     (36 -> 128 x 4 -> 84), 64 filters (36 -> 64 x 4 -> 36), four layers
- *     (36 -> 128 x 3 -> 36), six layers (36 -> 128 x 5 -> 36).
+ *     (36 -> 128 x 4 -> 84), 64 filters (36 -> 64 x 4 -> 36), 192 filters
+ *     (36 -> 192 x 4 -> 36), four layers (36 -> 128 x 3 -> 36), six layers
+ *     (36 -> 128 x 5 -> 36).
  * Head layout o[12 K]: for each of R,G,B: K mixture logits, K means, K
  * log-sigmas (units of 1/256 of the grey range); then K alphas, K betas,
  * K gammas of Eq. (3)-(4).

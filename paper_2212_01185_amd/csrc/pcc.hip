@@ -46,12 +46,25 @@ struct EncodeVariant { int tiles, threads; };
 // pcc_encode_probs: pixels of a tile whose head outputs a wave stages in LDS at a time (four, or as many as fit
 // beside the model image: two or one for the largest networks), and the bytes that takes for the workgroup.
 constexpr int kLdsBytes = 160 * 1024;
-// What the pixel kernel keeps in LDS: the whole model image, or, where that does not fit, the image without the CDF
-// table (the last thing in it), which the epilogue then reads from global memory.
+// What the pixel kernel keeps in LDS: the weight tiles of as many leading layers as fit together with all biases,
+// the biases behind them, and behind those the CDF table if there is room left (the whole model image when
+// everything fits).  The other layers' tiles, and the table when it is not there, are read from global memory.
 template <class Net>
-constexpr bool encode_table_in_lds() { return Layout<Net>::kModelBytes <= kLdsBytes; }
+constexpr int encode_resident_layers() {
+    int r = Net::kLayers;
+    while (r > 0 && Layout<Net>::w_off(r) + (Layout<Net>::kLutOff - Layout<Net>::kWeightBytes) > kLdsBytes) --r;
+    return r;
+}
 template <class Net>
-constexpr int encode_model_lds_bytes() { return encode_table_in_lds<Net>() ? Layout<Net>::kModelBytes : Layout<Net>::kLutOff; }
+constexpr int encode_table_lds_off() {      // = Layout::kLutOff when all layers are resident
+    return Layout<Net>::w_off(encode_resident_layers<Net>()) + (Layout<Net>::kLutOff - Layout<Net>::kWeightBytes);
+}
+template <class Net>
+constexpr bool encode_table_in_lds() { return encode_table_lds_off<Net>() + (Layout<Net>::kModelBytes - Layout<Net>::kLutOff) <= kLdsBytes; }
+template <class Net>
+constexpr int encode_model_lds_bytes() {
+    return encode_table_lds_off<Net>() + (encode_table_in_lds<Net>() ? Layout<Net>::kModelBytes - Layout<Net>::kLutOff : 0);
+}
 // 0: no room for a staging area; the head outputs are then stored value by value.
 template <class Net>
 constexpr int params_stage_pixels(int threads) {
@@ -62,7 +75,6 @@ constexpr int params_stage_pixels(int threads) {
 template <class Net>
 constexpr int params_stage_bytes(int threads) { return (threads / 64) * params_stage_pixels<Net>(threads) * Net::dim(Net::kLayers) * 4; }
 constexpr EncodeVariant kEncodeVariants[4] = {{1, 512}, {2, 512}, {1, 1024}, {4, 256}};
-constexpr int kDefaultEncodeVariant = 1;
 
 // status words in device memory
 enum { kStErr = 0, kStAbort = 1, kStTicket = 2, kStWords = 4 };
@@ -176,9 +188,15 @@ encode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ img
     using Lay = Layout<Net>;
     constexpr int K = Net::K, KB0 = Net::kb(0), HEAD = Net::dim(Net::kLayers);
     extern __shared__ __align__(16) uint8_t lds[];
-    copy_to_lds(lds, model, encode_model_lds_bytes<Net>());
+    constexpr int RESIDENT = encode_resident_layers<Net>();
+    if constexpr (RESIDENT == Net::kLayers) {
+        copy_to_lds(lds, model, encode_model_lds_bytes<Net>());
+    } else {
+        copy_to_lds(lds, model, Lay::w_off(RESIDENT));
+        copy_to_lds(lds + Lay::w_off(RESIDENT), model + Lay::kWeightBytes, encode_model_lds_bytes<Net>() - Lay::w_off(RESIDENT));
+    }
     __syncthreads();
-    const uint8_t* table_at = encode_table_in_lds<Net>() ? lds : model;
+    const uint8_t* table_at = encode_table_in_lds<Net>() ? lds + (encode_table_lds_off<Net>() - Lay::kLutOff) : model;
     const float2* lut = reinterpret_cast<const float2*>(table_at + Lay::kLutOff);
     const float lut_scale = *reinterpret_cast<const float*>(table_at + Lay::kLutScaleOff);
     const int lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
@@ -247,7 +265,7 @@ encode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ img
             }
         }
         f32x4_t out[T][Lay::kHeadOB];
-        mlp_from<Net, T, (T == 1 && THREADS <= 512), 0>(lds + opaque_zero(), lane, in, out);
+        mlp_from<Net, T, (T == 1 && THREADS <= 512), 0, RESIDENT>(lds + opaque_zero(), model, lane, in, out);
         // The head's results are first read behind branches (which outputs are wanted, border tiles).  The wait
         // states an MFMA's result needs are counted along the instruction stream as laid out, not along a taken
         // branch, so the accumulators are made to settle here, in straight-line code.
@@ -1410,7 +1428,7 @@ cdf_tables_kernel(const uint8_t* __restrict__ model, const float* __restrict__ p
 // ===========================================================================
 using namespace pcc;
 
-enum { kNetWorkload = 0, kNetPaper = 1, kNetDiagonal = 2, kNetFewerLayers = 3, kNetFewerFilters = 4, kNetMoreMixtures = 5, kNetMostMixtures = 6, kNetMoreLayers = 7 };
+enum { kNetWorkload = 0, kNetPaper = 1, kNetDiagonal = 2, kNetFewerLayers = 3, kNetFewerFilters = 4, kNetMoreMixtures = 5, kNetMostMixtures = 6, kNetMoreLayers = 7, kNetMoreFilters = 8 };
 
 struct pcc_ctx {
     int device = 0;
@@ -1427,7 +1445,7 @@ struct pcc_ctx {
     size_t sf_count = 0;
     int num_cus = 0;
     uint32_t dist = 0;             // written to / checked against stream header word 6
-    int encode_variant = kDefaultEncodeVariant;
+    int encode_variant = 1;
     uint32_t spin_limit = 1u << 22;      // polls of a band for one pixel of the band above (seconds) before the call fails (PCC_DECODE_SPIN_LIMIT, for tests)
     int decode_variant = 0;              // 0: chosen per job; 1: one workgroup per CU; 2: two (PCC_DECODE_VARIANT, for measurements)
     // the row coder of a small job runs beside the pixel kernel, on a stream of its own
@@ -1531,6 +1549,7 @@ auto with_net(int net, F&& f) {
         case kNetMoreMixtures: return f(NetMoreMixtures{});
         case kNetMostMixtures: return f(NetMostMixtures{});
         case kNetMoreLayers: return f(NetMoreLayers{});
+        case kNetMoreFilters: return f(NetMoreFilters{});
         default: return f(NetWorkload{});
     }
 }
@@ -1766,6 +1785,7 @@ int pcc_create(pcc_ctx** out, const void* h_blob, size_t blob_bytes, int hip_dev
     else if (header_matches<NetMoreMixtures>(p)) net = kNetMoreMixtures;
     else if (header_matches<NetMostMixtures>(p)) net = kNetMostMixtures;
     else if (header_matches<NetMoreLayers>(p)) net = kNetMoreLayers;
+    else if (header_matches<NetMoreFilters>(p)) net = kNetMoreFilters;
     else return PCC_E_BLOB;
 
     std::vector<uint8_t> image;
@@ -1788,6 +1808,7 @@ int pcc_create(pcc_ctx** out, const void* h_blob, size_t blob_bytes, int hip_dev
     ok = ok && hipHostMalloc((void**)&ctx->h_status, kStBytes, hipHostMallocDefault) == hipSuccess;
     ok = ok && hipMemcpy(ctx->d_model, image.data(), image.size(), hipMemcpyHostToDevice) == hipSuccess;
     ok = ok && with_net(net, [](auto tag) { return set_kernel_attributes<decltype(tag)>(); });
+    ctx->encode_variant = with_net(net, [](auto tag) { return decltype(tag)::kEncodeVariant; });
     if (const char* e = getenv("PCC_ENCODE_VARIANT")) {
         const int v = atoi(e);
         if (v >= 0 && v < 4) ctx->encode_variant = v;

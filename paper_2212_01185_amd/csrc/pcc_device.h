@@ -55,6 +55,7 @@ struct NetWorkload {
     // from a copy in LDS instead of held in registers, chosen by measurement (batches of 48 images of 768x512): LDS
     // copies cost time too, so a few spilled registers can be the better deal.  1: the biases, 2: the first layer's
     // weights, 4: the head's.
+    static constexpr int kEncodeVariant = 1;      // pixel kernel: two tiles per work item, 512 threads (index into the host's table)
     static constexpr int kSharedCuLds = 6;
     // Time of a decode step when both workgroups of a CU are busy, in percent of a step of a workgroup that has its
     // CU alone (measured the same way; the host chooses between the two launches with it).
@@ -93,6 +94,7 @@ struct NetPaper {
     static constexpr int kRingCols = 16;
     static constexpr int kRingPad = 4;
     static constexpr bool kLeaky = true;
+    static constexpr int kEncodeVariant = 1;
     static constexpr int kSharedCuLds = 0;      // a few registers spill instead: faster than any LDS copy here
     static constexpr unsigned kSharedStepPercent = 145;
     __host__ __device__ static constexpr int dim(int l) { return l == 0 ? 36 : l == 5 ? 36 : 128; }
@@ -148,19 +150,21 @@ struct NetDiagonal : NetPaper {
 
 // The paper's network with another number of mixture components, filters or layers (the ablations of
 // Sec. IV-E; wavefront order): 36 -> C -> ... -> C -> 12 K, LAYERS weight layers, LeakyReLU.  K is 3, 5
-// (the head layouts above) or 7, C a multiple of 32; the packed weights and biases must fit the encoder's LDS
-// (checked where the kernels are set up).  Six layers of 128 filters fit without the CDF table, which that
-// shape's encoder reads from global memory.
+// (the head layouts above) or 7, C a multiple of 32.  The encoder keeps in LDS what fits of the packed model: six
+// layers of 128 filters fit without the CDF table, of 192 filters the first two layers (the other layers' weight
+// tiles and, there, the table are read from global memory).
 // K = 7 (six out-blocks, 24 registers): groups 0..2 hold their channel's 21 parameters, group 3 the
 // 21 coupling coefficients.
 template <int MIXTURES, int C, int LAYERS>
 struct NetAblation : NetPaper {
-    static_assert((MIXTURES == 3 || MIXTURES == 5 || MIXTURES == 7) && C % 32 == 0 && C <= 128 && LAYERS >= 3 && LAYERS <= 7,
+    static_assert((MIXTURES == 3 || MIXTURES == 5 || MIXTURES == 7) && C % 32 == 0 && C <= 192 && LAYERS >= 3 && LAYERS <= 7,
                   "unsupported shape");
     static constexpr int kLayers = LAYERS;
     static constexpr int K = MIXTURES;
+    static constexpr int kEncodeVariant = C > 128 ? 0 : 1;      // 192 filters: one tile per work item spills least (measured)
     static constexpr int kSharedCuLds = MIXTURES >= 7 ? 7 : (MIXTURES >= 5 || LAYERS >= 6) ? 6 : NetPaper::kSharedCuLds;
-    static constexpr unsigned kSharedStepPercent = MIXTURES >= 7 ? 186 : MIXTURES >= 5 ? 153 : 147;
+    // (C = 192: a wave's weight slices alone are 264 registers; two workgroups per CU are never the better launch)
+    static constexpr unsigned kSharedStepPercent = C > 128 ? 1000 : MIXTURES >= 7 ? 186 : MIXTURES >= 5 ? 153 : 147;
     __host__ __device__ static constexpr int dim(int l) { return l == 0 ? 36 : l == LAYERS ? 12 * MIXTURES : C; }
     __host__ __device__ static constexpr int ob(int l) { return (dim(l + 1) + 15) / 16; }
     __host__ __device__ static constexpr int kb(int l) { return (dim(l) + 31) / 32; }
@@ -175,6 +179,7 @@ using NetFewerFilters = NetAblation<3, 64, 5>;
 using NetMoreMixtures = NetAblation<5, 128, 5>;
 using NetMostMixtures = NetAblation<7, 128, 5>;
 using NetMoreLayers = NetAblation<3, 128, 6>;
+using NetMoreFilters = NetAblation<3, 192, 5>;
 
 // Every canonical first-layer input sits in exactly one k-slot.
 template <class Net>
@@ -191,7 +196,8 @@ constexpr bool inputs_placed_once() {
 static_assert(inputs_placed_once<NetWorkload>() && inputs_placed_once<NetPaper>() && inputs_placed_once<NetDiagonal>() &&
                   inputs_placed_once<NetFewerLayers>() &&
                   inputs_placed_once<NetFewerFilters>() && inputs_placed_once<NetMoreMixtures>() &&
-                  inputs_placed_once<NetMostMixtures>() && inputs_placed_once<NetMoreLayers>(),
+                  inputs_placed_once<NetMostMixtures>() && inputs_placed_once<NetMoreLayers>() &&
+                  inputs_placed_once<NetMoreFilters>(),
               "first-layer slot map");
 
 constexpr int kBlockBytes = 64 * 16;  // one (out-block, k-block) A operand: 64 lanes x 8 bf16
@@ -385,20 +391,22 @@ __device__ __forceinline__ void head_layer(const uint8_t* __restrict__ w, const 
 
 // Layers L .. last.  WIDE selects how many out-blocks are accumulated concurrently:
 // the whole layer (one tile per wave: many independent MFMA chains are needed) or two.
-template <class Net, int T, bool WIDE, int L>
-__device__ __forceinline__ void mlp_from(const uint8_t* __restrict__ model, int lane,
+// `model` holds the weight tiles of the first RESIDENT layers and, straight behind them, all biases (the packed
+// image itself when RESIDENT is the number of layers); the other layers' tiles are read from the image at `rest`.
+template <class Net, int T, bool WIDE, int L, int RESIDENT = Net::kLayers>
+__device__ __forceinline__ void mlp_from(const uint8_t* __restrict__ model, const uint8_t* __restrict__ rest, int lane,
                                          const u32x4_t (&in)[T][Net::kb(L)][2],
                                          f32x4_t (&out)[T][Layout<Net>::kHeadOB]) {
     using Lay = Layout<Net>;
-    const uint8_t* w = model + Lay::w_off(L);
-    const float* b = reinterpret_cast<const float*>(model + Lay::b_off(L));
+    const uint8_t* w = (L < RESIDENT ? model : rest) + Lay::w_off(L);
+    const float* b = reinterpret_cast<const float*>(model + Lay::w_off(RESIDENT) + (Lay::b_off(L) - Lay::kWeightBytes));
     if constexpr (L == Net::kLayers - 1) {
         head_layer<T, Net::ob(L), Net::kb(L)>(w, b, lane, in, out);
     } else {
         static_assert(Net::ob(L) == 2 * Net::kb(L + 1), "two out-blocks form one k-block of the next layer");
         u32x4_t h[T][Net::kb(L + 1)][2];
         hidden_layer<T, Net::ob(L), Net::kb(L), (WIDE ? Net::ob(L) : 2), (L > 0), Net::kLeaky>(w, b, lane, in, h);
-        mlp_from<Net, T, WIDE, L + 1>(model, lane, h, out);
+        mlp_from<Net, T, WIDE, L + 1, RESIDENT>(model, rest, lane, h, out);
     }
 }
 

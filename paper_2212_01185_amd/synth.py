@@ -256,9 +256,10 @@ def make_diagonal_blob(seed: int = 0, sharp: bool = False, dist: int = DIST_GAUS
 
 
 # The shapes of the paper's ablation study (Sec. IV-E: one hyper-parameter of (K, C, L) = (3, 128, 5) changed at a
-# time) that the GPU library also takes: name -> (mixtures K, filters C, layers L).
+# time), all of which the GPU library takes: name -> (mixtures K, filters C, layers L).
 ABLATION_SHAPES = {"fewer_layers": (3, 128, 4), "fewer_filters": (3, 64, 5), "more_mixtures": (5, 128, 5),
-                   "most_mixtures": (7, 128, 5), "more_layers": (3, 128, 6)}
+                   "most_mixtures": (7, 128, 5), "more_layers": (3, 128, 6),
+                   "more_filters": (3, 192, 5)}
 
 
 def ablation_dims(k: int, c: int, n_layers: int):

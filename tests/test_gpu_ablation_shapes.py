@@ -1,8 +1,8 @@
 """The network shapes of the paper's ablation study (Sec. IV-E: number of mixtures, of filters, of layers, one changed
 at a time from K = 3, C = 128, L = 5) on the HIP path against the CPU oracle.  Needs an MI355X.
 
-Of the paper's six variants the library takes K = 5, K = 7, C = 64, L = 4 and L = 6; C = 192 is refused at
-pcc_create like any other unknown shape (a CPU test covers that)."""
+The library takes all six variants: K = 5, K = 7, C = 64, C = 192, L = 4 and L = 6 (other shapes are refused at
+pcc_create; a CPU test covers that)."""
 import struct
 
 import numpy as np

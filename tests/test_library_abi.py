@@ -47,11 +47,12 @@ def test_create_rejects_bad_blobs_before_touching_the_gpu(blob, paper_blob):
     for bad in (blob[:-4], b"\0" * len(blob), blob[:64], paper_blob[:-4], relu_paper, k5_paper):
         buf = ctypes.create_string_buffer(bad, len(bad))
         assert lib.pcc_create(ctypes.byref(h), buf, len(bad), 0) == binding.PCC_E_BLOB
-    # the shape of the paper's ablation tables (Sec. IV-E) that the kernels are not built for, C = 192; and
-    # supported ones (L = 4, L = 6, K = 7) cut short
+    # shapes beyond the paper's ablation tables (Sec. IV-E) that the kernels are not built for (256 filters, seven
+    # layers, two ablations at once), and supported ones (L = 4, L = 6, K = 7, C = 192) cut short
     from paper_2212_01185_amd import synth
-    for bad in (synth.make_ablation_blob(3, 192, 5), synth.make_ablation_blob(3, 128, 6)[:-4],
-                synth.make_ablation_blob(3, 128, 4)[:-4], synth.make_ablation_blob(7, 128, 5)[:-4]):
+    for bad in (synth.make_ablation_blob(3, 256, 5), synth.make_ablation_blob(3, 128, 7), synth.make_ablation_blob(5, 64, 5),
+                synth.make_ablation_blob(3, 128, 6)[:-4], synth.make_ablation_blob(3, 128, 4)[:-4],
+                synth.make_ablation_blob(7, 128, 5)[:-4], synth.make_ablation_blob(3, 192, 5)[:-4]):
         buf = ctypes.create_string_buffer(bad, len(bad))
         assert lib.pcc_create(ctypes.byref(h), buf, len(bad), 0) == binding.PCC_E_BLOB
     # a weight that is not a bf16 value
