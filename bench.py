@@ -6,12 +6,14 @@ pixels through gather, network, mixture CDF, row-rANS, stream assembly, then the
 wavefront decoder), inputs and outputs resident in HBM.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1] [--no-cpu-baseline]
-                  [--network workload|paper|diagonal] [--image WxH]
+                  [--network workload|paper|diagonal|<ablation shape>] [--image WxH]
 
 --network paper runs the paper's own network shape (12-pixel neighbourhood, 36-128x4-36, LeakyReLU, K=3,
 delay 3) instead of the measured workloads' one, --network diagonal the same shape in the diagonal decoding
-order (passes r + c, three inputs copied); --image 512x512 gives the image size of the paper's run-time
-table.  Neither is the headline: the driver's default run is config 1 with the workload network.
+order (passes r + c, three inputs copied), --network fewer_layers | more_layers | fewer_filters | more_filters |
+more_mixtures | most_mixtures one of the shapes of the paper's ablation study (Sec. IV-E); --image 512x512 gives
+the image size of the paper's run-time table.  None of these is the headline: the driver's default run is
+config 1 with the workload network.
 """
 from __future__ import annotations
 
@@ -31,6 +33,13 @@ NET_NAME = {"workload": "He-init 30-160-160-128-60 network, ReLU, K=5, 10-pixel 
             "paper": "He-init 36-128-128-128-128-36 network, LeakyReLU, K=3, 12-pixel neighbourhood",
             "diagonal": "He-init 36-128-128-128-128-36 network, LeakyReLU, K=3, 12-pixel neighbourhood with the three "
                         "undecoded inputs copied, diagonal order"}
+# the shapes of the paper's ablation study (Sec. IV-E): name -> (K, C, L), as paper_2212_01185_amd.synth lists them
+ABLATION_SHAPES = {"fewer_layers": (3, 128, 4), "fewer_filters": (3, 64, 5), "more_mixtures": (5, 128, 5),
+                   "most_mixtures": (7, 128, 5), "more_layers": (3, 128, 6), "more_filters": (3, 192, 5)}
+for _name, (_k, _c, _l) in ABLATION_SHAPES.items():
+    _dims = (36,) + (_c,) * (_l - 1) + (12 * _k,)
+    FLOP_PER_PIXEL_BY_NET[_name] = 2 * sum(a * b for a, b in zip(_dims[:-1], _dims[1:]))
+    NET_NAME[_name] = "He-init %s network, LeakyReLU, K=%d, 12-pixel neighbourhood" % ("-".join(str(d) for d in _dims), _k)
 # paper, Table II: 512x512, diagonal order: encode 3.08 s, decode 27.22 s
 PAPER_512_DIAGONAL_STEP_SECONDS = 3.08 + 27.22
 # paper, Table II: 512x512, wavefront, RTX 2080 + i7-9700: encode 3.10 s, decode 26.26 s
@@ -74,7 +83,7 @@ def main():
     ap.add_argument("--config", type=int, default=1, help="workload id 0..4 (1 = 768x512, the headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=256, help="rows of image 0 the oracle baseline codes (about 13 s)")
-    ap.add_argument("--network", choices=("workload", "paper", "diagonal"), default="workload")
+    ap.add_argument("--network", choices=("workload", "paper", "diagonal") + tuple(ABLATION_SHAPES), default="workload")
     ap.add_argument("--image", default=None, help="WxH of one synthetic image instead of a numbered config")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs: three encodes + decodes and one plain "
@@ -89,7 +98,10 @@ def main():
     from paper_2212_01185_amd import binding, synth
 
     FLOP_PER_PIXEL = FLOP_PER_PIXEL_BY_NET[args.network]
-    blob = {"workload": synth.make_blob, "paper": synth.make_paper_blob, "diagonal": synth.make_diagonal_blob}[args.network](0)
+    if args.network in ABLATION_SHAPES:
+        blob = synth.make_ablation_blob(*ABLATION_SHAPES[args.network])
+    else:
+        blob = {"workload": synth.make_blob, "paper": synth.make_paper_blob, "diagonal": synth.make_diagonal_blob}[args.network](0)
     if args.image:
         iw, ih = (int(v) for v in args.image.lower().split("x"))
         imgs = synth.make_image(0, synth.ImageSpec(iw, ih, 32, 8.0, 64.0))[None]

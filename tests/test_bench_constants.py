@@ -33,6 +33,15 @@ def test_flop_per_pixel_is_twice_the_macs_of_the_layers():
     assert bench.FLOP_PER_PIXEL_BY_NET["paper"] == bench.FLOP_PER_PIXEL_BY_NET["diagonal"] == 2 * _macs(paper) == 116736
 
 
+def test_ablation_shapes_in_bench_are_those_of_the_input_generators():
+    bench = _bench()
+    assert bench.ABLATION_SHAPES == synth.ABLATION_SHAPES
+    for name, (k, c, nl) in synth.ABLATION_SHAPES.items():
+        dims = _dims(synth.make_ablation_blob(k, c, nl))
+        assert dims == list(synth.ablation_dims(k, c, nl))
+        assert bench.FLOP_PER_PIXEL_BY_NET[name] == 2 * _macs(dims)
+
+
 def test_macs_of_the_papers_network_against_its_table_iii():
     # Table III: 16.9 GMac for a 512x512 image, encoding as well as decoding.  The conv form of the network has a
     # full 5x5x3 first kernel (75 taps, the masked-out ones counted by a MAC-counting tool as by Table I's parameter
