@@ -161,7 +161,7 @@ struct NetAblation : NetPaper {
                   "unsupported shape");
     static constexpr int kLayers = LAYERS;
     static constexpr int K = MIXTURES;
-    static constexpr int kEncodeVariant = C > 128 ? 0 : 1;      // 192 filters: one tile per work item spills least (measured)
+    static constexpr int kEncodeVariant = 1;
     static constexpr int kSharedCuLds = MIXTURES >= 7 ? 7 : (MIXTURES >= 5 || LAYERS >= 6) ? 6 : NetPaper::kSharedCuLds;
     // (C = 192: a wave's weight slices alone are 264 registers; two workgroups per CU are never the better launch)
     static constexpr unsigned kSharedStepPercent = C > 128 ? 1000 : MIXTURES >= 7 ? 186 : MIXTURES >= 5 ? 153 : 147;
@@ -295,7 +295,9 @@ __device__ __forceinline__ f32x4_t mfma16(u32x4_t a, u32x4_t b, f32x4_t c) {
 // Accumulation order per output element: bias, then k-blocks 0,1,2,..., each hi then lo.
 // Activations of one layer for T tiles: [tile][k-block][0 = hi, 1 = lo].
 // ---------------------------------------------------------------------------
-template <int T, int NOB, int NKB, int OBG, bool SPLIT_IN, bool LEAKY>
+// FAR: the weight tiles come from global memory; the reads of a k-block's tiles then stay behind the MFMAs of the
+// k-block before the previous one (left to itself the compiler issues a whole layer's reads at once and spills).
+template <int T, int NOB, int NKB, int OBG, bool SPLIT_IN, bool LEAKY, bool FAR = false>
 __device__ __forceinline__ void hidden_layer(const uint8_t* __restrict__ w, const float* __restrict__ bias,
                                              int lane, const u32x4_t (&in)[T][NKB][2],
                                              u32x4_t (&out)[T][NOB / 2][2]) {
@@ -335,6 +337,7 @@ __device__ __forceinline__ void hidden_layer(const uint8_t* __restrict__ w, cons
 #pragma unroll
                 for (int j = 0; j < OBG; ++j) a_cur[j] = a_nxt[j];
             }
+            if constexpr (FAR) __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
         for (int j = 0; j < OBG; j += 2) {
@@ -354,7 +357,7 @@ __device__ __forceinline__ void hidden_layer(const uint8_t* __restrict__ w, cons
     }
 }
 
-template <int T, int NOB, int NKB>
+template <int T, int NOB, int NKB, bool FAR = false>
 __device__ __forceinline__ void head_layer(const uint8_t* __restrict__ w, const float* __restrict__ bias, int lane,
                                            const u32x4_t (&in)[T][NKB][2], f32x4_t (&out)[T][NOB]) {
     const int g = lane >> 4;
@@ -386,6 +389,7 @@ __device__ __forceinline__ void head_layer(const uint8_t* __restrict__ w, const 
 #pragma unroll
             for (int ob = 0; ob < NOB; ++ob) a_cur[ob] = a_nxt[ob];
         }
+        if constexpr (FAR) __builtin_amdgcn_sched_barrier(0);
     }
 }
 
@@ -401,11 +405,11 @@ __device__ __forceinline__ void mlp_from(const uint8_t* __restrict__ model, cons
     const uint8_t* w = (L < RESIDENT ? model : rest) + Lay::w_off(L);
     const float* b = reinterpret_cast<const float*>(model + Lay::w_off(RESIDENT) + (Lay::b_off(L) - Lay::kWeightBytes));
     if constexpr (L == Net::kLayers - 1) {
-        head_layer<T, Net::ob(L), Net::kb(L)>(w, b, lane, in, out);
+        head_layer<T, Net::ob(L), Net::kb(L), (L >= RESIDENT)>(w, b, lane, in, out);
     } else {
         static_assert(Net::ob(L) == 2 * Net::kb(L + 1), "two out-blocks form one k-block of the next layer");
         u32x4_t h[T][Net::kb(L + 1)][2];
-        hidden_layer<T, Net::ob(L), Net::kb(L), (WIDE ? Net::ob(L) : 2), (L > 0), Net::kLeaky>(w, b, lane, in, h);
+        hidden_layer<T, Net::ob(L), Net::kb(L), (WIDE ? Net::ob(L) : 2), (L > 0), Net::kLeaky, (L >= RESIDENT)>(w, b, lane, in, h);
         mlp_from<Net, T, WIDE, L + 1, RESIDENT>(model, rest, lane, h, out);
     }
 }
