@@ -425,7 +425,9 @@ def test_more_bands_than_resident_workgroups(blob, paper_blob, monkeypatch):
     imgs = np.stack([synth.make_image(100 + s, synth.ImageSpec(24, 40, 4, 2.0, 8.0)) for s in range(20)])
     imgs = np.concatenate([imgs, rng.integers(0, 256, (160, 40, 24, 3), dtype=np.uint8)])
     n, h, w, _ = imgs.shape
-    for which in (blob, paper_blob):
+    # the workload network keeps two layers' weights in LDS when two workgroups share a CU, the paper's nothing, the
+    # seven-mixture shape those and the biases
+    for which in (blob, paper_blob, synth.make_ablation_blob(7, 128, 5)):
         streams = []
         for variant in ("0", "1", "2"):
             monkeypatch.setenv("PCC_DECODE_VARIANT", variant)
