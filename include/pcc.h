@@ -122,7 +122,15 @@ int pcc_encode_probs(pcc_ctx *ctx, const uint8_t *d_img, int n, int H, int W,
  * hip_stream is idle at the call and the job has at most 3072 rows, the row
  * coder and the stream assembly run on a stream the ctx owns, beside the
  * pixel kernel; both streams have been waited for when the call returns, so
- * the caller's view is the same.  One call at a time per ctx. */
+ * the caller's view is the same.  That mode needs the two kernels to run at
+ * the same time.  Where something runs a process's kernels one after the other
+ * (a profiler collecting counters does; so does a chip another job fills), the
+ * row coder finds no symbols, gives up after PCC_RANS_PATIENCE polls (a few
+ * milliseconds with the default) and is launched again behind the pixel kernel:
+ * the result is the same, but such a call pays that wait first, i.e. ten times
+ * a 768 x 512 encode.  PCC_ENCODE_OVERLAP=0 avoids the mode altogether.
+ * One call at a time per ctx.  On an error return no kernel of the call is
+ * still running on either stream. */
 int pcc_encode(pcc_ctx *ctx, const uint8_t *d_img, int n, int H, int W,
                uint8_t *d_stream, size_t cap_bytes, size_t *h_nbytes_out, void *hip_stream);
 

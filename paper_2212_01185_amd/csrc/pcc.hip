@@ -28,6 +28,7 @@
 
 #include "pcc.h"
 #include "pcc_device.h"
+#include "rans_arith.h"
 
 namespace pcc {
 
@@ -373,37 +374,11 @@ constexpr uint32_t kRansBalanceRows = 850;
 // and never renormalises, so every chunk can be coded as a full one.
 constexpr uint32_t kRansNop = 0xFFFF0000u;
 
-// A value just below 1/f in fp64 for 1 <= f < 2^17: hardware estimate plus two
-// Newton steps (relative error about 2^-52 either way), then pulled down by
-// 2^-50.  Independent of the coder state.
-__device__ __forceinline__ double rans_recip_below(uint32_t f32) {
-    const double fd = (double)f32;
-    double rf = __builtin_amdgcn_rcp(fd);
-    rf = __builtin_fma(__builtin_fma(-fd, rf, 1.0), rf, rf);
-    rf = __builtin_fma(__builtin_fma(-fd, rf, 1.0), rf, rf);
-    return rf * (1.0 - 0x1p-50);
-}
-
 // The coding wave rounds its fp64 arithmetic toward zero (MODE.FP_ROUND bits 3:2 = 3).  Written as
 // assembly: the compiler would put the default mode back in front of the wave's fp64 instructions.
+// rans_push (rans_arith.h) relies on it.
 __device__ __forceinline__ void rans_round_toward_zero() {
     asm volatile("s_setreg_imm32_b32 hwreg(HW_REG_MODE, 2, 2), 3" ::: "memory");
-}
-
-// x <- C(x, (start, f)) with an exact x / f for x = xh 2^32 + xl < 2^47 * f.  Needs
-// rans_round_toward_zero(): the state converted to fp64 (at most x), times a value
-// below 1/f, plus 2^52, each rounded toward zero, leaves an estimate of the quotient
-// in the mantissa that is the quotient or one less (all the errors together are
-// below 2^47 * 2^-49), so the remainder x - q f lies in [0, 2f) and its low 32 bits
-// decide the one correction.  Branch-free.
-__device__ __forceinline__ void rans_push(uint32_t& xl, uint32_t& xh, uint32_t f, uint32_t start, double rf_below) {
-    const double xd = __builtin_fma((double)xh, 4294967296.0, (double)xl);
-    const uint64_t qb = (uint64_t)__double_as_longlong(__builtin_fma(xd, rf_below, 4503599627370496.0));
-    const uint32_t rem = xl - (uint32_t)qb * f;
-    const uint32_t z = rem + start + (rem >= f ? 65536u - f : 0u);   // a quotient one short: carry 2^16 - f
-    const uint64_t x = (qb << 16) + z;                               // the exponent bits of qb leave at the top
-    xl = (uint32_t)x;
-    xh = (uint32_t)(x >> 32);
 }
 
 // Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for
@@ -1813,13 +1788,15 @@ int pcc_create(pcc_ctx** out, const void* h_blob, size_t blob_bytes, int hip_dev
         const int v = atoi(e);
         if (v >= 0 && v < 4) ctx->encode_variant = v;
     }
-    if (const char* e = getenv("PCC_DECODE_SPIN_LIMIT")) ctx->spin_limit = (uint32_t)atoi(e);
+    // limits from the environment: negative values are taken as zero (no patience), never as huge unsigned ones
+    auto env_limit = [](const char* e) { const long v = atol(e); return (uint32_t)std::min<long>(std::max<long>(v, 0), 0x7FFFFFFFl); };
+    if (const char* e = getenv("PCC_DECODE_SPIN_LIMIT")) ctx->spin_limit = env_limit(e);
     if (const char* e = getenv("PCC_DECODE_VARIANT")) {
         const int v = atoi(e);
         if (v >= 0 && v <= 2) ctx->decode_variant = v;
     }
     if (const char* e = getenv("PCC_ENCODE_OVERLAP")) ctx->overlap = atoi(e) != 0;
-    if (const char* e = getenv("PCC_RANS_PATIENCE")) ctx->patience = (uint32_t)atoi(e);
+    if (const char* e = getenv("PCC_RANS_PATIENCE")) ctx->patience = env_limit(e);
     ok = ok && hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking) == hipSuccess;
     ok = ok && hipEventCreateWithFlags(&ctx->ev_joined, hipEventDisableTiming) == hipSuccess;
     if (!ok) { (void)hipGetLastError(); pcc_destroy(ctx); return PCC_E_HIP; }
@@ -1968,6 +1945,19 @@ int pcc_encode(pcc_ctx* ctx, const uint8_t* d_img, int n, int H, int W, uint8_t*
         // strips with the whole chip, and the row coder joins it (an event; the launch gap does not matter at
         // this size) for a last part sized so that both end together.  The row coder takes about as long as the
         // pixel kernel at kRansBalanceRows rows, both in proportion to the width.
+        //
+        // Two streams carry work from here on.  Whatever fails, the branch leaves through `drain`: both streams
+        // are waited for (a row coder without its pixel kernel stands down when its patience is over), so nothing
+        // still writes the caller's stream buffer or the workspace after the return, and the side status words
+        // are zero again for the next call.
+        auto drain = [&](int code) -> int {
+            (void)hipStreamSynchronize(ctx->side);
+            (void)hipStreamSynchronize(st);
+            (void)hipMemsetAsync(ctx->d_status + kStSide, 0, 2 * sizeof(int), st);
+            (void)hipStreamSynchronize(st);
+            (void)hipGetLastError();
+            return code;
+        };
         const double share = 1.1 * kRansBalanceRows / rows * (double)(cus - reserve) / cus;   // of the strips, beside
         const uint32_t strips_alone = share >= 1.0 ? 0u : (uint32_t)((1.0 - share) * strips);
         if (strips_alone == 0) {
@@ -1976,30 +1966,27 @@ int pcc_encode(pcc_ctx* ctx, const uint8_t* d_img, int n, int H, int W, uint8_t*
         } else {
             prof_begin(ctx, PCC_T_ENCODE_PIXELS, st);
             rc = launch_encode_any(ctx, d_img, n, H, W, nullptr, nullptr, nullptr, d_tagged, 0, 0, strips_alone, st);
-            if (rc != PCC_OK) return rc;
-            if (hipEventRecord(ctx->ev_joined, st) != hipSuccess) return PCC_E_HIP;
-            if (hipStreamWaitEvent(ctx->side, ctx->ev_joined, 0) != hipSuccess) return PCC_E_HIP;
+            if (rc != PCC_OK) return drain(rc);
+            if (hipEventRecord(ctx->ev_joined, st) != hipSuccess) return drain(PCC_E_HIP);
+            if (hipStreamWaitEvent(ctx->side, ctx->ev_joined, 0) != hipSuccess) return drain(PCC_E_HIP);
             launch_rans(ctx->side);
         }
         rc = launch_encode_any(ctx, d_img, n, H, W, nullptr, nullptr, nullptr, d_tagged, reserve, strips_alone,
                                strips - strips_alone, st);
-        if (rc != PCC_OK) {
-            (void)hipStreamSynchronize(ctx->side);   // the row coder stands down when its patience is over
-            return rc;
-        }
+        if (rc != PCC_OK) return drain(rc);
         prof_end(ctx, PCC_T_ENCODE_PIXELS, st);
         rc = finish(ctx->side);
-        if (rc != PCC_OK) return rc;
+        if (rc != PCC_OK) return drain(rc);
         // the row coder ends after the pixel kernel's last store; the caller's stream is waited for as well, so
         // that the pixel kernel has retired when this returns
-        if (hipStreamSynchronize(st) != hipSuccess) { (void)hipGetLastError(); return PCC_E_HIP; }
+        if (hipStreamSynchronize(st) != hipSuccess) return drain(PCC_E_HIP);
         if (ctx->h_status[kStErr] == 0 && ctx->h_status[kStSide + kSideDefer] != 0) {
             // The row coder saw nothing of the pixel kernel for a long time and stood down: the two did not run side
             // by side.  The symbols are all there now; code them on the caller's stream.
-            if (hipMemsetAsync(ctx->d_status, 0, kStCleared, st) != hipSuccess) return PCC_E_HIP;
+            if (hipMemsetAsync(ctx->d_status, 0, kStCleared, st) != hipSuccess) return drain(PCC_E_HIP);
             launch_rans(st);
             rc = finish(st);
-            if (rc != PCC_OK) return rc;
+            if (rc != PCC_OK) return drain(rc);
             if (ctx->h_status[kStSide + kSideDefer] != 0) return PCC_E_INTERNAL;   // a symbol was never written
         }
     }

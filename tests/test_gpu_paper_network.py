@@ -13,7 +13,9 @@ pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
 
 PARAM_ATOL = 2e-3         # raw head outputs against the exact fp64 network
-PARAM_ATOL_SPLIT = 2e-4   # against the oracle rounding activations to hi + lo bf16 the same way
+# Informative only: the oracle's MODE_SPLIT is a model of the kernel's own hi + lo rounding, so this compares the kernel
+# with a description of itself and carries no independent weight.  The gate is MODE_EXACT at PARAM_ATOL.
+PARAM_ATOL_SPLIT = 2e-4
 BITS_RTOL = 1e-3          # bits/pixel within 0.1 %
 CQ_ATOL = 2               # integer CDF counts
 TAG = 3 | (12 << 8) | (3 << 16) | (16 << 24)
