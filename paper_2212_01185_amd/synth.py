@@ -227,6 +227,51 @@ def make_predictor_blob(sigma_levels: float = 6.0) -> bytes:
     return pack_blob(make_predictor_weights(sigma_levels))
 
 
+DELTA_R_LEVEL, DELTA_G_LEVELS, DELTA_B_LEVEL = 100, (50, 200), 255
+
+
+def make_delta_blob() -> bytes:
+    """Test-only weights of the default shape that drive the coder to its extreme frequencies: all weights 0, so
+    every pixel gets the same three distributions from the head biases alone; every log-sigma is -8 (the lower
+    clamp: sigma = 0.086 grey levels, all of a component's mass in one bin).  R: every component sits on the
+    centre of bin 100, so level 100 takes the whole scaled mass (frequency 65,281 with the one-count floor of
+    every bin) and every other level has frequency 1.  G: three components on bin 50, two on bin 200, equal
+    weights (frequencies about 0.6 and 0.4 of the total).  B: means far above the range (3.0 = 768 grey levels),
+    so level 255 takes the open upper tail (65,281) and all others frequency 1.  No coupling."""
+    dims, k = DEFAULT_DIMS, DEFAULT_K
+    layers = [[np.zeros((o, i), dtype=np.float32), np.zeros(o, dtype=np.float32)] for i, o in zip(dims[:-1], dims[1:])]
+    b = layers[-1][1]
+    for ch in range(3):
+        b[3 * k * ch + 2 * k: 3 * k * ch + 3 * k] = -8.0
+    b[k:2 * k] = DELTA_R_LEVEL / 256.0
+    b[3 * k + k: 3 * k + k + 3] = DELTA_G_LEVELS[0] / 256.0
+    b[3 * k + k + 3: 3 * k + 2 * k] = DELTA_G_LEVELS[1] / 256.0
+    b[6 * k + k: 6 * k + 2 * k] = 3.0
+    return pack_blob([(w, bb) for w, bb in layers])
+
+
+def make_delta_image(seed: int, n: int, h: int, w: int) -> np.ndarray:
+    """uint8 [n, h, w, 3] for the delta weights: runs of the levels the distributions sit on (frequencies near
+    the maximum: the coder state hardly moves), runs of uniformly random pixels (frequency 1: a renormalisation
+    word every other symbol), and single pixels of either kind, in seeded order."""
+    rng = np.random.default_rng(seed)
+    flat = np.empty((n * h * w, 3), dtype=np.uint8)
+    at = 0
+    heavy = bool(rng.integers(2))
+    while at < len(flat):
+        run = int(rng.choice([1, 2, 7, 40, 333]))
+        run = min(run, len(flat) - at, max(1, len(flat) // 5))      # both kinds occur in any image of a few pixels
+        heavy = not heavy
+        if heavy:
+            flat[at:at + run, 0] = DELTA_R_LEVEL
+            flat[at:at + run, 1] = rng.choice(DELTA_G_LEVELS, run)
+            flat[at:at + run, 2] = DELTA_B_LEVEL
+        else:
+            flat[at:at + run] = rng.integers(0, 256, (run, 3), dtype=np.uint8)
+        at += run
+    return flat.reshape(n, h, w, 3)
+
+
 PROBE_TAPS = (11, 4, 5)     # of the 12 neighbours in raster order: (0,-1), (-2,+2), (-1,-2)
 
 

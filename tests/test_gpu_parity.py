@@ -16,8 +16,9 @@ torch = pytest.importorskip("torch")
 # bound set for this path; the expected error is ~1e-4 (16-bit activations,
 # fp32 sums of up to 160 terms).
 PARAM_ATOL = 2e-3
-# Against the oracle rounding activations the same way only summation order differs,
-# except where a lo part rounds the other way (one unit of 2^-17 relative).
+# Informative only: the oracle's MODE_SPLIT is a model of the kernel's own hi + lo rounding (only the summation
+# order differs, except where a lo part rounds the other way), so this compares the kernel with a description of
+# itself and carries no independent weight.  The gate is MODE_EXACT at PARAM_ATOL.
 PARAM_ATOL_SPLIT = 2e-4
 BITS_RTOL = 1e-3          # bits/pixel within 0.1 %
 CQ_ATOL = 2               # integer CDF counts: fp32 + table-interpolated Phi vs fp64 erfc
@@ -143,6 +144,50 @@ def test_coder_and_container_bit_exact(codec, codec_sharp, shape):
         want = _expected_stream(imgs.shape, iv)
         got = stream.cpu().numpy().tobytes()
         assert got == want
+
+
+def test_coder_at_extreme_frequencies(monkeypatch):
+    """The delta weights put (nearly) all of a channel's mass into one bin: sub-pixels on that bin have
+    frequencies of 65,280 or 65,281 of 65,536 (the coder state hardly moves for hundreds of symbols), all others
+    frequency 1 (a renormalisation word every other symbol).  The row coder's exact division and its
+    renormalisation must give the oracle coder's bytes for these intervals too, at widths of 1 symbol triple, of
+    one and of many coder chunks, with the row coder beside the pixel kernel, after it, and standing down; and
+    the decoder must return the images."""
+    from paper_2212_01185_amd import binding
+    blob_d = synth.make_delta_blob()
+    orc_d = po.Oracle(blob_d)
+    beside = binding.Codec(blob_d, 0)
+    monkeypatch.setenv("PCC_ENCODE_OVERLAP", "0")
+    after = binding.Codec(blob_d, 0)
+    monkeypatch.delenv("PCC_ENCODE_OVERLAP")
+    monkeypatch.setenv("PCC_RANS_PATIENCE", "0")
+    impatient = binding.Codec(blob_d, 0)
+    monkeypatch.delenv("PCC_RANS_PATIENCE")
+    try:
+        for n, h, w in [(1, 3, 1), (2, 5, 33), (1, 4, 300), (1, 3, 4100), (1, 70, 130)]:
+            imgs = synth.make_delta_image(40 + w, n, h, w)
+            d = _dev(imgs)
+            for name, c in (("beside", beside), ("after", after), ("impatient", impatient)):
+                _log("delta weights %dx%dx%d, row coder %s" % (n, h, w, name))
+                stream = c.pcc_encode(d)
+                iv = c.pcc_copy_intervals(n, h, w)
+                torch.cuda.synchronize()
+                iv = iv.cpu().numpy().view(np.uint32)
+                freq = (iv >> 16) + 1
+                assert freq.min() >= 1 and ((iv & 0xFFFF) + freq).max() <= 65536
+                if w >= 33:
+                    assert freq.min() == 1 and freq.max() >= 65280 and (freq == 1).mean() > 0.2 and (freq >= 26000).mean() > 0.2
+                assert stream.cpu().numpy().tobytes() == _expected_stream(imgs.shape, iv)
+                out = c.pcc_decode(stream, n, h, w)
+                torch.cuda.synchronize()
+                np.testing.assert_array_equal(out.cpu().numpy(), imgs)
+            _, bits = beside.pcc_encode_probs(d)
+            _, want = orc_d.encode(imgs, po.MODE_EXACT)
+            assert abs(float(bits.double().sum().item()) / want.sum() - 1) <= BITS_RTOL
+    finally:
+        beside.close()
+        after.close()
+        impatient.close()
 
 
 def test_cdf_tables_against_oracle(codec, orc):

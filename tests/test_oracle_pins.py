@@ -634,6 +634,41 @@ def test_decoder_rejects_damaged_streams(orc):
         assert (out != imgs).any()
 
 
+def test_delta_weights_reach_the_extreme_frequencies():
+    """The test-only delta weights (all mass of a channel in one or two bins, sigma at its lower clamp): the
+    oracle's tables are checked against the mixture written out with scipy's normal CDF in grey-level units
+    (Eq. (1) with the open tails and the integer rule), they hold one bin of (nearly) the whole mass and
+    frequency 1 (or 2 right next to the mass) everywhere else, and images made of such runs round-trip with
+    the code length the frequencies give (a frequency-1 symbol costs exactly 16 bits)."""
+    orc_d = po.Oracle(synth.make_delta_blob())
+    img = synth.make_delta_image(5, 1, 6, 40)
+    o = orc_d.params_at(img[0], 3, 7, po.MODE_EXACT)
+    np.testing.assert_array_equal(o, orc_d.params_at(img[0], 0, 0, po.MODE_EXACT))     # weights are zero: biases only
+    s_levels = 256.0 * np.exp(-8.0)
+    means = {0: [synth.DELTA_R_LEVEL] * 5, 1: [synth.DELTA_G_LEVELS[0]] * 3 + [synth.DELTA_G_LEVELS[1]] * 2, 2: [768.0] * 5}
+    tables = {}
+    for ch in range(3):
+        cq = orc_d.cdf_table(o, ch, 17, 201).astype(np.int64)
+        edges = np.arange(1, 256) - 0.5
+        F = sum(0.2 * scipy.stats.norm.cdf((edges - m) / s_levels) for m in means[ch])
+        want = np.concatenate([[0], np.arange(1, 256) + np.minimum(np.floor(65280.0 * F), 65280).astype(np.int64), [65536]])
+        np.testing.assert_array_equal(cq, want)
+        freq = np.diff(cq)
+        assert freq.sum() == 65536 and freq.min() == 1
+        tables[ch] = freq
+    assert tables[0][synth.DELTA_R_LEVEL] == 65280 and (tables[0] == 1).sum() == 254       # one neighbour bin holds 2
+    assert tables[2][synth.DELTA_B_LEVEL] == 65281 and (tables[2] == 1).sum() == 255       # the open upper tail
+    assert tables[1][synth.DELTA_G_LEVELS[0]] + tables[1][synth.DELTA_G_LEVELS[1]] == 65280 and (tables[1] == 1).sum() == 252
+    stream, bits = orc_d.encode(img, po.MODE_EXACT)
+    for order in (po.ORDER_RASTER, po.ORDER_WAVEFRONT):
+        np.testing.assert_array_equal(orc_d.decode(stream, 1, 6, 40, po.MODE_EXACT, order), img)
+    want_bits = sum(-np.log2(tables[ch][int(v)] / 65536.0) for px in img.reshape(-1, 3) for ch, v in enumerate(px))
+    assert abs(bits.sum() - want_bits) < 1e-6
+    assert (tables[0][img[..., 0].reshape(-1)] == 1).sum() > 50 and (tables[0][img[..., 0].reshape(-1)] == 65280).sum() > 50
+    payload = len(stream) - (32 + 8 * 7)
+    assert 6 * 32 <= 8 * payload - bits.sum() <= 6 * 96 + 3 * 240 * 2.0 ** -14
+
+
 def test_blob_validation():
     blob = synth.make_blob(0)
     for bad in (blob[:-4], b"\0" * len(blob), blob + b"\0\0\0\0"):
