@@ -57,3 +57,30 @@ def test_macs_of_the_papers_network_against_its_table_iii():
 def test_peaks_are_the_published_ones():
     bench = _bench()
     assert bench.PEAK_BF16_TFLOPS == 2500.0 and bench.PEAK_HBM_GBS == 8000.0
+
+
+def _traffic_rows():
+    """kernel name -> (fetched MB, written MB) from the table of the committed rocprofv3 traffic summary."""
+    rows = {}
+    with open(os.path.join(ROOT, "profiles", "bench_768x512_hbm_traffic.md")) as f:
+        for line in f:
+            cells = [c.strip() for c in line.strip().strip("|").split("|")]
+            if len(cells) == 6 and cells[0] not in ("kernel", "---") and not set(cells[0]) <= {"-"}:
+                try:
+                    rows[cells[0]] = (float(cells[2].replace(",", "")), float(cells[4].replace(",", "")))
+                except ValueError:
+                    pass
+    return rows
+
+
+def test_roofline_traffic_is_the_committed_profile_summary():
+    """`roofline.traffic` of the driver line is what profiles/bench_768x512_hbm_traffic.md reports for the
+    encode kernel in the form the bench runs it (symbols handed to the row coder as tagged 8-byte words)."""
+    bench = _bench()
+    rows = _traffic_rows()
+    key = [k for k in rows if k.startswith("encode_kernel<NetWorkload") and "tagged" in k]
+    assert len(key) == 1, rows.keys()
+    fetched_mb, written_mb = rows[key[0]]
+    t = bench.ENCODE_KERNEL_TRAFFIC_768x512
+    assert t["fetch_bytes"] == fetched_mb * 1e6 and t["write_bytes"] == written_mb * 1e6
+    assert t["algorithmic_bytes"] == (3 + 24) * 768 * 512
