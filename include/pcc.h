@@ -75,6 +75,7 @@ extern "C" {
 #define PCC_E_HIP (-5)      /* a HIP runtime call failed */
 #define PCC_E_INTERNAL (-6) /* zero frequency or bounded device wait expired */
 #define PCC_E_UNIMPL (-7)
+#define PCC_E_SCRATCH (-8)  /* pcc_decode_static: the job needs more than PCC_STATIC_SCRATCH_BYTES of scratch memory */
 
 #define PCC_HEAD_OUTPUTS 60 /* of the 30-160-160-128-60 network; in general pcc_model_info()[0] */
 
@@ -140,6 +141,25 @@ int pcc_encode(pcc_ctx *ctx, const uint8_t *d_img, int n, int H, int W,
  * PCC_E_STREAM the image content is unspecified. */
 int pcc_decode(pcc_ctx *ctx, const uint8_t *d_stream, size_t nbytes, int n, int H, int W,
                uint8_t *d_img_out, void *hip_stream);
+
+/* pcc_decode for callers that cannot allocate device memory: code under HIP
+ * graph capture restrictions, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, same result and same errors as pcc_decode, but the
+ * decoder's only scratch buffer -- the mailbox through which a band of 16 rows
+ * hands its last two rows to the band below, 8 bytes per pixel column and band:
+ * pcc_decode_static_scratch_bytes(n, H, W) -- lives in an array of
+ * PCC_STATIC_SCRATCH_BYTES that is part of the library's device code (every GPU
+ * the library runs on holds it until the process ends) instead of the ctx's
+ * workspace.  The call allocates and frees nothing, and clears what it uses of
+ * the array with a kernel (no memset node).  A job that needs more returns
+ * PCC_E_SCRATCH before anything is launched (8 MiB covers one 4096 x 2160 image
+ * and 24 images of 768 x 512).  All ctxs on a GPU share that GPU's array: two
+ * pcc_decode_static calls that overlap in time on one GPU race, whatever their
+ * ctxs and streams.  Synchronises hip_stream before returning. */
+#define PCC_STATIC_SCRATCH_BYTES (8u << 20)
+size_t pcc_decode_static_scratch_bytes(int n, int H, int W);   /* 0 for invalid dimensions */
+int pcc_decode_static(pcc_ctx *ctx, const uint8_t *d_stream, size_t nbytes, int n, int H, int W,
+                      uint8_t *d_img_out, void *hip_stream);
 
 /* Test hooks (not on the hot path). */
 

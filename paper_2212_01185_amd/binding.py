@@ -16,12 +16,12 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpcc.so")
 
 PCC_OK = 0
-PCC_E_ARG, PCC_E_BLOB, PCC_E_CAP, PCC_E_STREAM, PCC_E_HIP, PCC_E_INTERNAL, PCC_E_UNIMPL = -1, -2, -3, -4, -5, -6, -7
+PCC_E_ARG, PCC_E_BLOB, PCC_E_CAP, PCC_E_STREAM, PCC_E_HIP, PCC_E_INTERNAL, PCC_E_UNIMPL, PCC_E_SCRATCH = -1, -2, -3, -4, -5, -6, -7, -8
 HEAD_OUTPUTS = 60          # of the 30-160-160-128-60 network; a Codec knows its own (head_outputs)
 
 EXPORTS = (
     "pcc_create", "pcc_destroy", "pcc_stream_bound", "pcc_wavefront_steps", "pcc_model_info", "pcc_encode_probs", "pcc_encode",
-    "pcc_decode", "pcc_cdf_tables", "pcc_copy_intervals", "pcc_set_profiling", "pcc_last_timings", "pcc_strerror",
+    "pcc_decode", "pcc_decode_static", "pcc_decode_static_scratch_bytes", "pcc_cdf_tables", "pcc_copy_intervals", "pcc_set_profiling", "pcc_last_timings", "pcc_strerror",
 )
 TIMING_NAMES = ("encode_pixels", "encode_rans", "encode_scan", "encode_compact", "decode")
 
@@ -54,6 +54,10 @@ def load():
     L.pcc_encode.restype = i32
     L.pcc_decode.argtypes = [vp, vp, sz, i32, i32, i32, vp, vp]
     L.pcc_decode.restype = i32
+    L.pcc_decode_static.argtypes = [vp, vp, sz, i32, i32, i32, vp, vp]
+    L.pcc_decode_static.restype = i32
+    L.pcc_decode_static_scratch_bytes.argtypes = [i32, i32, i32]
+    L.pcc_decode_static_scratch_bytes.restype = sz
     L.pcc_cdf_tables.argtypes = [vp, vp, vp, sz, vp, vp]
     L.pcc_cdf_tables.restype = i32
     L.pcc_copy_intervals.argtypes = [vp, vp, sz, vp]
@@ -159,6 +163,15 @@ class Codec:
         rc = load().pcc_decode(self._h, stream.data_ptr(), stream.numel(), n, h, w, out.data_ptr(), _stream_handle())
         if rc != PCC_OK:
             raise PccError(rc, "pcc_decode")
+        return out
+
+    def pcc_decode_static(self, stream: torch.Tensor, n: int, h: int, w: int, out: torch.Tensor) -> torch.Tensor:
+        """pcc_decode with the mailbox in the library's static device array: allocates nothing (``out`` is required)."""
+        if stream.dtype != torch.uint8 or not stream.is_cuda or not stream.is_contiguous():
+            raise ValueError("stream must be a contiguous CUDA uint8 tensor")
+        rc = load().pcc_decode_static(self._h, stream.data_ptr(), stream.numel(), n, h, w, out.data_ptr(), _stream_handle())
+        if rc != PCC_OK:
+            raise PccError(rc, "pcc_decode_static")
         return out
 
     def pcc_cdf_tables(self, params: torch.Tensor, rg: torch.Tensor) -> torch.Tensor:

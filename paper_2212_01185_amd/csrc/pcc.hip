@@ -22,6 +22,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <mutex>
 #include <new>
 #include <type_traits>
 #include <vector>
@@ -1396,7 +1397,22 @@ cdf_tables_kernel(const uint8_t* __restrict__ model, const float* __restrict__ p
     for (int e = 0; e <= 256; ++e) dst[e] = cq_full<K>(cp, e, lut);
 }
 
+// ---------------------------------------------------------------------------
+// pcc_decode_static: the decoder's mailbox in an array that is part of the loaded code object, so that the call
+// allocates nothing.  Each GPU the library runs on holds its own copy at its own address (resolved once per device,
+// see static_scratch()); host code never uses the array's name for anything but that resolution.
+// ---------------------------------------------------------------------------
+constexpr size_t kStaticScratchBytes = PCC_STATIC_SCRATCH_BYTES;
+
+// Zero `count` 32-bit words (a kernel rather than a memset node: a caller may be capturing the stream).
+__global__ void __launch_bounds__(256)
+clear_words_kernel(uint32_t* __restrict__ dst, size_t count) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (size_t)gridDim.x * 256) dst[i] = 0u;
+}
+
 }  // namespace pcc
+
+static __device__ __align__(256) uint32_t scratch[pcc::kStaticScratchBytes / 4];
 
 // ===========================================================================
 // host side
@@ -1419,6 +1435,7 @@ struct pcc_ctx {
     uint32_t* d_sf = nullptr;
     size_t sf_count = 0;
     int num_cus = 0;
+    uint32_t* d_static_scratch = nullptr;   // this device's copy of the static scratch array (pcc_decode_static)
     uint32_t dist = 0;             // written to / checked against stream header word 6
     int encode_variant = 1;
     uint32_t spin_limit = 1u << 22;      // polls of a band for one pixel of the band above (seconds) before the call fails (PCC_DECODE_SPIN_LIMIT, for tests)
@@ -1486,6 +1503,22 @@ int ensure_tagged(pcc_ctx* ctx, size_t count) {
 }
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Device address of this GPU's copy of `scratch`, resolved once per device with that device current (the caller
+// holds a DeviceGuard).  nullptr if the runtime cannot resolve it.
+constexpr int kMaxDevices = 64;
+uint32_t* static_scratch(int device) {
+    static std::mutex mu;
+    static uint32_t* ptr[kMaxDevices] = {};
+    if (device < 0 || device >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr[device]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
+        ptr[device] = static_cast<uint32_t*>(p);
+    }
+    return ptr[device];
+}
 
 inline void prof_reset(pcc_ctx* ctx) {
     for (int i = 0; i < PCC_N_TIMINGS; ++i) { ctx->ev_used[i] = false; ctx->last_ms[i] = 0.0f; }
@@ -1729,6 +1762,7 @@ const char* pcc_strerror(int code) {
         case PCC_E_HIP: return "HIP runtime error";
         case PCC_E_INTERNAL: return "internal error (zero frequency or device wait expired)";
         case PCC_E_UNIMPL: return "not implemented";
+        case PCC_E_SCRATCH: return "job needs more scratch memory than the library's static array holds";
         default: return "unknown error";
     }
 }
@@ -1777,6 +1811,8 @@ int pcc_create(pcc_ctx** out, const void* h_blob, size_t blob_bytes, int hip_dev
     hipDeviceProp_t prop;
     bool ok = hipGetDeviceProperties(&prop, hip_device) == hipSuccess;
     if (ok) ctx->num_cus = prop.multiProcessorCount;
+    ctx->d_static_scratch = static_scratch(hip_device);
+    ok = ok && ctx->d_static_scratch != nullptr;
     ok = ok && hipMalloc((void**)&ctx->d_model, image.size()) == hipSuccess;
     ok = ok && hipMalloc((void**)&ctx->d_status, kStBytes) == hipSuccess;
     ok = ok && hipMemset(ctx->d_status, 0, kStBytes) == hipSuccess;
@@ -1999,24 +2035,20 @@ int pcc_encode(pcc_ctx* ctx, const uint8_t* d_img, int n, int H, int W, uint8_t*
     return PCC_OK;
 }
 
-int pcc_decode(pcc_ctx* ctx, const uint8_t* d_stream, size_t nbytes, int n, int H, int W, uint8_t* d_img_out,
-               void* hip_stream) {
-    if (!ctx || !d_stream || !d_img_out || !dims_ok(n, H, W)) return PCC_E_ARG;
-    if (((uintptr_t)d_stream & 7u) != 0) return PCC_E_ARG;
-    DeviceGuard guard(ctx->device);
-    if (!guard.ok) return PCC_E_HIP;
-    hipStream_t st = (hipStream_t)hip_stream;
-    const uint64_t rows = (uint64_t)n * H;
-    const uint64_t table = (uint64_t)kStreamHeader + 8 * (rows + 1);
-    if (nbytes < table + 8 * rows) return PCC_E_STREAM;   // every row payload holds at least its 8-byte state
-    const int nbands = (H + kBandRows - 1) / kBandRows;
-    const size_t mail_bytes = align_up((size_t)n * nbands * 2 * (size_t)W * 4, 256);
-    int rc = ensure_workspace(ctx, mail_bytes);
-    if (rc != PCC_OK) return rc;
-    ctx->d_sf = nullptr; ctx->sf_count = 0;
-    uint32_t* d_mail = reinterpret_cast<uint32_t*>(ctx->d_ws);
-    if (hipMemsetAsync(ctx->d_status, 0, kStCleared, st) != hipSuccess) return PCC_E_HIP;
-    if (hipMemsetAsync(d_mail, 0, mail_bytes, st) != hipSuccess) return PCC_E_HIP;
+// Both decoders: `d_mail` is the mailbox (zeroed here), big enough for the job.
+static int decode_with_mailbox(pcc_ctx* ctx, const uint8_t* d_stream, size_t nbytes, int n, int H, int W, int nbands,
+                               uint8_t* d_img_out, uint32_t* d_mail, size_t mail_bytes, bool clear_by_kernel, hipStream_t st) {
+    if (clear_by_kernel) {
+        const size_t words = mail_bytes / 4;
+        hipLaunchKernelGGL(clear_words_kernel, dim3(1), dim3(256), 0, st, reinterpret_cast<uint32_t*>(ctx->d_status),
+                           kStCleared / 4);
+        hipLaunchKernelGGL(clear_words_kernel, dim3((uint32_t)std::min<size_t>((words + 255) / 256, 1024)), dim3(256), 0, st,
+                           d_mail, words);
+        if (hipGetLastError() != hipSuccess) return PCC_E_HIP;
+    } else {
+        if (hipMemsetAsync(ctx->d_status, 0, kStCleared, st) != hipSuccess) return PCC_E_HIP;
+        if (hipMemsetAsync(d_mail, 0, mail_bytes, st) != hipSuccess) return PCC_E_HIP;
+    }
     const uint32_t spin_limit = ctx->spin_limit;
     prof_reset(ctx);
     prof_begin(ctx, PCC_T_DECODE, st);
@@ -2031,6 +2063,47 @@ int pcc_decode(pcc_ctx* ctx, const uint8_t* d_stream, size_t nbytes, int n, int 
     if (hipStreamSynchronize(st) != hipSuccess) { (void)hipGetLastError(); return PCC_E_HIP; }
     prof_collect(ctx);
     return ctx->h_status[kStErr];
+}
+
+int pcc_decode(pcc_ctx* ctx, const uint8_t* d_stream, size_t nbytes, int n, int H, int W, uint8_t* d_img_out,
+               void* hip_stream) {
+    if (!ctx || !d_stream || !d_img_out || !dims_ok(n, H, W)) return PCC_E_ARG;
+    if (((uintptr_t)d_stream & 7u) != 0) return PCC_E_ARG;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return PCC_E_HIP;
+    const uint64_t rows = (uint64_t)n * H;
+    const uint64_t table = (uint64_t)kStreamHeader + 8 * (rows + 1);
+    if (nbytes < table + 8 * rows) return PCC_E_STREAM;   // every row payload holds at least its 8-byte state
+    const int nbands = (H + kBandRows - 1) / kBandRows;
+    const size_t mail_bytes = align_up((size_t)n * nbands * 2 * (size_t)W * 4, 256);
+    int rc = ensure_workspace(ctx, mail_bytes);
+    if (rc != PCC_OK) return rc;
+    ctx->d_sf = nullptr; ctx->sf_count = 0;
+    return decode_with_mailbox(ctx, d_stream, nbytes, n, H, W, nbands, d_img_out, reinterpret_cast<uint32_t*>(ctx->d_ws),
+                               mail_bytes, false, (hipStream_t)hip_stream);
+}
+
+size_t pcc_decode_static_scratch_bytes(int n, int H, int W) {
+    if (!dims_ok(n, H, W)) return 0;
+    const int nbands = (H + kBandRows - 1) / kBandRows;
+    return align_up((size_t)n * nbands * 2 * (size_t)W * 4, 256);
+}
+
+int pcc_decode_static(pcc_ctx* ctx, const uint8_t* d_stream, size_t nbytes, int n, int H, int W, uint8_t* d_img_out,
+                      void* hip_stream) {
+    if (!ctx || !d_stream || !d_img_out || !dims_ok(n, H, W)) return PCC_E_ARG;
+    if (((uintptr_t)d_stream & 7u) != 0) return PCC_E_ARG;
+    const size_t mail_bytes = pcc_decode_static_scratch_bytes(n, H, W);
+    if (mail_bytes > kStaticScratchBytes) return PCC_E_SCRATCH;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return PCC_E_HIP;
+    const uint64_t rows = (uint64_t)n * H;
+    const uint64_t table = (uint64_t)kStreamHeader + 8 * (rows + 1);
+    if (nbytes < table + 8 * rows) return PCC_E_STREAM;
+    const int nbands = (H + kBandRows - 1) / kBandRows;
+    // the array keeps the last call's words (tagged pixels of another image): the part this job uses is cleared
+    return decode_with_mailbox(ctx, d_stream, nbytes, n, H, W, nbands, d_img_out, ctx->d_static_scratch, mail_bytes, true,
+                               (hipStream_t)hip_stream);
 }
 
 int pcc_cdf_tables(pcc_ctx* ctx, const float* d_params, const uint8_t* d_rg, size_t count, uint32_t* d_cq,
