@@ -16,13 +16,19 @@ FLAGS = [
     # encoder and decoder must round identically: no contraction the source does not spell out
     "-ffp-contract=off",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # MFMA results land in vector registers proper (the vector ALU reads them without a copy per register); the
+    # decoder's resident weights, which only the matrix cores read, go to the accumulation registers instead
+    "-mllvm", "-amdgpu-mfma-vgpr-form",
     "-Wall", "-Wno-unused-function",
     "-I" + os.path.join(ROOT, "include"),
     "-I" + os.path.join(_HERE, "csrc"),
 ]
 
 
-def build(verbose: bool = False, extra=()) -> str:
+def build(verbose: bool = False, extra=(), lib: str = LIB) -> str:
+    """Compile the library to `lib` (default: libpcc.so next to the package).  `extra` are more hipcc flags, e.g.
+    -DPCC_PHASE_TIMING for the measurement build that counts the decode step's cycles per phase."""
+    LIB = lib
     tmp = LIB + ".tmp%d" % os.getpid()
     cmd = [HIPCC] + FLAGS + list(extra) + ["-o", tmp, SRC]
     if verbose:
@@ -38,5 +44,9 @@ def build(verbose: bool = False, extra=()) -> str:
 
 
 if __name__ == "__main__":
-    build(verbose=True, extra=sys.argv[1:])
-    print(LIB)
+    # python -m paper_2212_01185_amd.build [--out PATH] [hipcc flags ...]
+    argv = sys.argv[1:]
+    out = LIB
+    if argv[:1] == ["--out"]:
+        out, argv = os.path.abspath(argv[1]), argv[2:]
+    print(build(verbose=True, extra=argv, lib=out))

@@ -709,6 +709,35 @@ compact_scan_kernel(const uint32_t* __restrict__ slabs, const uint32_t* __restri
 // ---------------------------------------------------------------------------
 constexpr int kDecThreads = 256;
 
+// Where a decode step spends its cycles: built only with -DPCC_PHASE_TIMING (a measurement build; the product has
+// an empty struct here and no code).  Every wave reads the shader clock at the marks of the step and sums the
+// differences per phase; the workgroup that decodes ticket kPhaseTicket leaves the sums in phase_cycles.
+enum { kPhGather = 0, kPhLayer0 = 1 /* + layer */, kPhMixture = 8, kPhR = 9, kPhG = 10, kPhB = 11, kPhPublish = 12,
+       kPhFetch = 13, kPhBarrier = 14, kPhTop = 15, kPhCount = 16 };
+#ifdef PCC_PHASE_TIMING
+constexpr int kPhaseTicket = 8;
+__device__ unsigned long long phase_cycles[4][kPhCount + 1];
+struct PhaseClock {
+    uint64_t t, acc[kPhCount];
+    __device__ __forceinline__ void reset() {
+        for (int i = 0; i < kPhCount; ++i) acc[i] = 0;
+        t = __builtin_readcyclecounter();
+    }
+    __device__ __forceinline__ void mark(int i) {
+        __builtin_amdgcn_sched_barrier(0);      // no instruction of one phase is moved into another
+        const uint64_t now = __builtin_readcyclecounter();
+        acc[i] += now - t;
+        t = now;
+        __builtin_amdgcn_sched_barrier(0);
+    }
+};
+#else
+struct PhaseClock {
+    __device__ __forceinline__ void reset() {}
+    __device__ __forceinline__ void mark(int) {}
+};
+#endif
+
 // decode LDS: the CDF table, two activation buffers, head outputs, mixtures, ring
 template <class Net>
 struct DecLds {
@@ -735,8 +764,8 @@ struct DecLds {
     static constexpr int kRingRowElems = 2 * Net::kRingCols * 3 + Net::kRingPad;
     static constexpr int kRingOff = kCpOff + 16 * 3 * kCpStride * 4;
     static constexpr int kMiscOff = kRingOff + 18 * kRingRowElems * 2; // ticket, abort flag
-    static constexpr int kDumpOff = (kMiscOff + 64 + 15) / 16 * 16;    // 2 KB nobody reads: stores of out-blocks a wave does not own
-    static constexpr int kBytes = kDumpOff + 2 * 64 * 16;
+    static constexpr int kPxOff = kMiscOff + 64;                       // the step's 16 decoded pixels, r | g << 8 | b << 16
+    static constexpr int kBytes = (kPxOff + 16 * 4 + 15) / 16 * 16;
     // Two workgroups per CU have 256 registers per lane each, too few for the whole of a wave's weight slices: there
     // the biases, and the weights of the first layer and of the head where two workgroups' LDS then still fits a CU,
     // are kept in LDS behind the above and read when used.
@@ -760,6 +789,33 @@ struct DecLds {
     // reach two columns further back, while the column being written and the zero columns right
     // of the image are stored: all of these must be distinct slots.
     static constexpr int kMaxReach = Net::kReach1 > Net::kReach2 ? Net::kReach1 : Net::kReach2;
+    // Wave w computes out-blocks w, w + 4, ... of a layer.  Where a layer's block count is not a multiple of four,
+    // the last wave has a round without a block; its spare time there, in MFMAs of the other waves' chains, is
+    // kIdleSlack in layer kIdleLayer (the layer where it is largest; 0: no layer has any).  That wave uses it to fetch
+    // the pixels of the rows above the band (decode_kernel).
+    static constexpr int kFetchWave = kDecThreads / 64 - 1;
+    static constexpr int idle_slack(int l) {
+        const int nob = Net::ob(l), slots = (nob + 3) / 4;
+        return kFetchWave + 4 * (slots - 1) >= nob ? Net::kb(l) * (l > 0 ? 2 : 1) : 0;
+    }
+    static constexpr int idle_layer() {
+        int best = Net::kLayers - 1;
+        for (int l = 0; l < Net::kLayers; ++l) if (idle_slack(l) > idle_slack(best)) best = l;
+        return best;
+    }
+    static constexpr int kIdleLayer = idle_layer();
+    static constexpr int kIdleSlack = idle_slack(kIdleLayer);
+    // Waves that idle in that round (the last ones).  With two of them the one before the fetch wave writes the decoded
+    // pixels to the image; with one the fetch wave does both.
+    static constexpr int kIdleWaves = kIdleSlack > 0 ? 4 * ((Net::ob(kIdleLayer) + 3) / 4) - Net::ob(kIdleLayer) : 0;
+    static constexpr int kStoreWave = kIdleWaves >= 2 ? kFetchWave - 1 : kFetchWave;
+    // Does wave w have a round without an out-block in layer l?
+    static constexpr bool wave_idles(int l, int w) { return w + 4 * ((Net::ob(l) + 3) / 4 - 1) >= Net::ob(l); }
+    // The idle waves also have a (short) round to spare in the first layer where that is not the layer above: the
+    // first, cheaper half of their jobs goes there (the fetch wave's request, the storing wave's read of the pixels).
+    static constexpr bool kIdleInFirstLayer =
+        kIdleSlack > 0 && kIdleLayer != 0 && wave_idles(0, kStoreWave) && wave_idles(0, kFetchWave);
+    static_assert(kIdleLayer > 0 || kIdleSlack == 0, "the fetch must lie behind the barrier that follows the step's gather");
     static_assert(2 * Net::kDelay + 3 + kMaxReach <= Net::kRingCols, "ring too small for the neighbourhood");
     // what a row reads of the rows above must have been decoded in an earlier pass
     static_assert(Net::kReach1 <= Net::kDelay - 1 && Net::kReach2 <= 2 * Net::kDelay - 1, "schedule is not causal");
@@ -867,11 +923,21 @@ struct WaveLayer {
 #pragma unroll
         for (int s = 0; s < SLOTS; ++s) {
             const int ob = min(wave + 4 * s, NOB - 1);
-            if constexpr (!B_LDS) bias[s] = *reinterpret_cast<const f32x4_t*>(b + 16 * ob + 4 * (lane >> 4));
+            if constexpr (!B_LDS) {
+                f32x4_t t = *reinterpret_cast<const f32x4_t*>(b + 16 * ob + 4 * (lane >> 4));
+                asm volatile("" : "+v"(t));      // the biases start the accumulators: in the same register file as those
+                bias[s] = t;
+            }
             if constexpr (!W_LDS) {
 #pragma unroll
-                for (int kb = 0; kb < NKB; ++kb)
-                    a[s][kb] = *reinterpret_cast<const u32x4_t*>(w + ((ob * NKB + kb) * 64 + lane) * 16);
+                for (int kb = 0; kb < NKB; ++kb) {
+                    u32x4_t t = *reinterpret_cast<const u32x4_t*>(w + ((ob * NKB + kb) * 64 + lane) * 16);
+                    // Register allocation only: the weights, read-only MFMA operands for the whole kernel, are
+                    // placed in accumulation registers, which leaves the vector registers proper to the
+                    // accumulators that the vector ALU reads (no copies between the two files per block).
+                    asm volatile("" : "+a"(t));
+                    a[s][kb] = t;
+                }
             }
         }
     }
@@ -888,50 +954,82 @@ struct WaveLayer {
 // One hidden layer on this wave's out-blocks.  Same arithmetic per output element
 // as hidden_layer<> in pcc_device.h: bias, then k-blocks in order, each hi then
 // lo; activation; split into hi + lo.  The out-blocks are taken one after the
-// other (an accumulation chain of MFMAs issues back to back at full rate), so that
-// the activation and split of one block run in the shadow of the next block's MFMAs.
-// A block this wave does not own (ob >= NOB) is computed on a copy of the layer's
-// last block (or not at all, SKIP_UNOWNED) and stored to `dump`.
-template <int NOB, int NKB, int SLOTS, bool W_LDS, bool B_LDS, bool SPLIT_IN, bool LEAKY, bool SKIP_UNOWNED>
+// other (an accumulation chain of MFMAs issues back to back at full rate).
+// In a layer's last round some waves may have no block (ob >= NOB): such a wave skips the round (a branch on
+// `wave_s`, the wave's index as a scalar) and calls idle() instead, if RUN_IDLE.  Every block is finished
+// (activation, split, store) inside the branch that computed it: an MFMA result is never first read behind a
+// branch that the MFMA's own block does not contain.
+template <int NOB, int NKB, int SLOTS, bool W_LDS, bool B_LDS, bool SPLIT_IN, bool LEAKY, bool SKIP_UNOWNED, bool RUN_IDLE,
+          class Idle>
 __device__ __forceinline__ void dec_hidden_layer(const WaveLayer<NOB, NKB, SLOTS, W_LDS, B_LDS>& wl, int lane, int wave,
-                                                 const u32x4_t (&in)[NKB][2], uint8_t* __restrict__ act_out,
-                                                 uint8_t* __restrict__ dump) {
+                                                 int wave_s, const u32x4_t (&in)[NKB][2], uint8_t* __restrict__ act_out,
+                                                 Idle& idle) {
     auto finish = [&](int s, const f32x4_t& acc) {
         const int ob = wave + 4 * s;
         uint32_t l0, l1;
         const uint32_t h0 = act_split_bf16<LEAKY>(acc.x, acc.y, l0);
         const uint32_t h1 = act_split_bf16<LEAKY>(acc.z, acc.w, l1);
         // out-block ob is half (ob & 1) of k-block ob/2 of the next layer's operand
-        uint8_t* dst = ob < NOB ? act_out + (((ob >> 1) * 2) * 64 + lane) * 16 + 8 * (ob & 1) : dump + lane * 16;
+        uint8_t* dst = act_out + (((ob >> 1) * 2) * 64 + lane) * 16 + 8 * (ob & 1);
         *reinterpret_cast<uint2*>(dst) = make_uint2(h0, h1);
         *reinterpret_cast<uint2*>(dst + 64 * 16) = make_uint2(l0, l1);
     };
-    f32x4_t acc[SLOTS];
+    auto chain = [&](int s, f32x4_t& acc) {
+        acc = wl.B(s, wave);
 #pragma unroll
-    for (int s = 0; s < SLOTS; ++s) {
-        acc[s] = wl.B(s, wave);
-        // Two workgroups per CU share the matrix cores: there a wave without this block skips its MFMAs
-        // (`wave` is a scalar, the dump store below still runs).  With one workgroup per CU the pipe is
-        // idle anyway, and a branch here would keep the previous block's split from running under them.
-        if (!SKIP_UNOWNED || 4 * s + 3 < NOB || wave + 4 * s < NOB) {
+        for (int kb = 0; kb < NKB; ++kb) {
+            const u32x4_t a = wl.A(s, kb, wave);
+            acc = mfma16(a, in[kb][0], acc);
+            if (SPLIT_IN) acc = mfma16(a, in[kb][1], acc);
+        }
+        asm volatile("" : "+v"(acc));            // register allocation only: the result where the vector ALU reads it
+    };
+    constexpr bool kLastShared = 4 * (SLOTS - 1) + 3 >= NOB;      // not every wave has a block in the last round
+    f32x4_t acc[SLOTS];
+    if constexpr (SKIP_UNOWNED) {
+        // Two workgroups per CU share the matrix cores: block after block, each finished before the next begins.
+#pragma unroll
+        for (int s = 0; s < SLOTS; ++s) {
+            if (s < SLOTS - 1 || !kLastShared || wave_s + 4 * s < NOB) {
+                chain(s, acc[s]);
+                finish(s, acc[s]);
+            } else if constexpr (RUN_IDLE) {
+                idle();
+            }
+            __builtin_amdgcn_sched_barrier(0);      // the next block's instructions stay behind this one's
+        }
+    } else {
+        // One workgroup per CU: the wave's blocks advance together, k-block by k-block (hi of every block, then lo of
+        // every block: per output element the order stays bias, k-blocks in order, hi then lo).  A k-block's input is
+        // then wanted once per SLOTS x 2 MFMAs, which is the pace at which LDS delivers the layer's input to four
+        // waves reading at once; block after block, the first block's chain waited for every one of its reads.
+        auto chains = [&](auto count) __attribute__((always_inline)) {
+            constexpr int N = decltype(count)::value;
+#pragma unroll
+            for (int s = 0; s < N; ++s) acc[s] = wl.B(s, wave);
 #pragma unroll
             for (int kb = 0; kb < NKB; ++kb) {
-                const u32x4_t a = wl.A(s, kb, wave);
-                acc[s] = mfma16(a, in[kb][0], acc[s]);
-                if (SPLIT_IN) acc[s] = mfma16(a, in[kb][1], acc[s]);
+#pragma unroll
+                for (int s = 0; s < N; ++s) acc[s] = mfma16(wl.A(s, kb, wave), in[kb][0], acc[s]);
+                if (SPLIT_IN) {
+#pragma unroll
+                    for (int s = 0; s < N; ++s) acc[s] = mfma16(wl.A(s, kb, wave), in[kb][1], acc[s]);
+                }
             }
-        }
-        // Where that branch exists, a block is finished before the next block's branch, never behind it: the wait
-        // states between an MFMA and the first read of its result are counted along the instruction stream as laid
-        // out, and a taken branch straight after the MFMA would skip them (seen as wrong activations now and then).
-        if constexpr (SKIP_UNOWNED) {
-            finish(s, acc[s]);
-            __builtin_amdgcn_sched_barrier(0);      // the next block's instructions stay behind this one's
+#pragma unroll
+            for (int s = 0; s < N; ++s) asm volatile("" : "+v"(acc[s]));    // register allocation only, see chain()
+#pragma unroll
+            for (int s = 0; s < N; ++s) finish(s, acc[s]);
+        };
+        if constexpr (!kLastShared) {
+            chains(std::integral_constant<int, SLOTS>());
+        } else if (wave_s + 4 * (SLOTS - 1) < NOB) {
+            chains(std::integral_constant<int, SLOTS>());
         } else {
-            if (s > 0) finish(s - 1, acc[s - 1]);
+            chains(std::integral_constant<int, SLOTS - 1>());
+            if constexpr (RUN_IDLE) idle();
         }
     }
-    if constexpr (!SKIP_UNOWNED) finish(SLOTS - 1, acc[SLOTS - 1]);
 }
 
 template <int NKB>
@@ -965,37 +1063,51 @@ struct WaveNet {
         wl.load(w, reinterpret_cast<const float*>(b), lane, wave);
         rest.load(model, lds, lane, wave);
     }
-    template <bool SKIP_UNOWNED>
-    __device__ __forceinline__ void run(const u32x4_t (&in)[NKB][2], int lane, int wave, uint8_t* __restrict__ act0,
-                                        uint8_t* __restrict__ act1, float* __restrict__ headout,
-                                        uint8_t* __restrict__ dump) const {
+    // wave_s: the wave's index as a scalar (for branches); idle: what a wave without a block in the last round of
+    // layer DecLds::kIdleLayer does in its place (the fetch wave is the only one that has work there).
+    template <bool SKIP_UNOWNED, class Idle>
+    __device__ __forceinline__ void run(const u32x4_t (&in)[NKB][2], int lane, int wave, int wave_s,
+                                        uint8_t* __restrict__ act0, uint8_t* __restrict__ act1,
+                                        float* __restrict__ headout, Idle& idle, PhaseClock& clk) const {
+        // what waves without an out-block in this layer's last round do instead (decode_kernel says what)
+        constexpr bool kRunIdle = DecLds<Net>::kIdleSlack > 0 &&
+                                  (L == DecLds<Net>::kIdleLayer || (L == 0 && DecLds<Net>::kIdleInFirstLayer));
+        auto idle_here = [&]() __attribute__((always_inline)) { idle(std::integral_constant<int, L>()); };
         if constexpr (kHead) {
             // registers s = 4 ob + i of group g, kept in (group, register) order; out-blocks ob = wave + 4 slot
             constexpr int HS = Layout<Net>::kHeadSlots;
 #pragma unroll
             for (int slot = 0; slot < SLOTS; ++slot) {
-                f32x4_t acc = wl.B(slot, wave);
+                // a wave without a block in this round skips it; the store follows the MFMAs inside the branch
+                if (4 * slot + 3 < NOB || wave_s + 4 * slot < NOB) {
+                    f32x4_t acc = wl.B(slot, wave);
 #pragma unroll
-                for (int kb = 0; kb < NKB; ++kb) {
-                    const u32x4_t a = wl.A(slot, kb, wave);
-                    acc = mfma16(a, in[kb][0], acc);
-                    acc = mfma16(a, in[kb][1], acc);
-                }
-                const int ob = wave + 4 * slot;
-                if (ob < NOB)
+                    for (int kb = 0; kb < NKB; ++kb) {
+                        const u32x4_t a = wl.A(slot, kb, wave);
+                        acc = mfma16(a, in[kb][0], acc);
+                        acc = mfma16(a, in[kb][1], acc);
+                    }
+                    const int ob = wave + 4 * slot;
                     *reinterpret_cast<f32x4_t*>(headout + (lane & 15) * DecLds<Net>::kHeadStride + (lane >> 4) * HS + 4 * ob) = acc;
+                } else if constexpr (kRunIdle) {
+                    idle_here();
+                }
+                if constexpr (SKIP_UNOWNED) __builtin_amdgcn_sched_barrier(0);
             }
             lds_barrier();
+            clk.mark(kPhLayer0 + L);
         } else {
             uint8_t* out = (L & 1) ? act1 : act0;
-            dec_hidden_layer<NOB, NKB, SLOTS, kWLds, kBLds, (L > 0), Net::kLeaky, SKIP_UNOWNED>(wl, lane, wave, in, out, dump);
+            dec_hidden_layer<NOB, NKB, SLOTS, kWLds, kBLds, (L > 0), Net::kLeaky, SKIP_UNOWNED, kRunIdle>(wl, lane, wave, wave_s, in,
+                                                                                                        out, idle_here);
             lds_barrier();
+            clk.mark(kPhLayer0 + L);
             u32x4_t nxt[Net::kb(L + 1)][2];
             dec_load_act<Net::kb(L + 1)>(out, lane, nxt);
             // scheduling only: every read of the layer's input is issued before its first MFMA, so
             // the LDS latency is paid once per layer and not once per k-block
             __builtin_amdgcn_sched_barrier(0);
-            rest.template run<SKIP_UNOWNED>(nxt, lane, wave, act0, act1, headout, dump);
+            rest.template run<SKIP_UNOWNED>(nxt, lane, wave, wave_s, act0, act1, headout, idle, clk);
         }
     }
 };
@@ -1062,11 +1174,12 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
     float* cpbuf = reinterpret_cast<float*>(lds + D::kCpOff);
     uint16_t* ring = reinterpret_cast<uint16_t*>(lds + D::kRingOff);
     int* misc = reinterpret_cast<int*>(lds + D::kMiscOff);            // [0] ticket, [1] abort
-    uint8_t* dump = lds + D::kDumpOff;
+    uint32_t* pxbuf = reinterpret_cast<uint32_t*>(lds + D::kPxOff);
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     // a scalar where a branch on it pays (two workgroups per CU); measured slower as a scalar otherwise
     const int wave = MINBLOCKS > 1 ? __builtin_amdgcn_readfirstlane(tid >> 6) : tid >> 6;
+    const int wave_s = __builtin_amdgcn_readfirstlane(tid >> 6);     // for branches that whole waves take
     // network role: pixel nl of the tile, k-slot group g
     const int g = lane >> 4, nl = lane & 15;
     // search role: pixel q of the band, lane j of its group
@@ -1163,7 +1276,10 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
 
     const int last_row = min(r0 + kBandRows - 1, H - 1);
     const int t_begin = kDelay * r0, t_end = kDelay * last_row + W - 1;
-    const bool fetcher = band > 0 && tid < 2;     // thread 0: row r0-2 -> ring row 0; thread 1: row r0-1 -> ring row 1
+    // The first two lanes of the last wave bring in the rows above the band: lane 0 row r0-2 -> ring row 0, lane 1
+    // row r0-1 -> ring row 1.  That wave has a round without an out-block in one of the layers (DecLds::kIdleLayer)
+    // and does the fetch there, off the path that all four waves share.
+    const bool fetcher = band > 0 && tid >= D::kFetchWave * 64 && tid < D::kFetchWave * 64 + 2;
     const uint32_t* mail_row = mail_in + (size_t)(tid & 1) * W;
     // Columns right of the band's first row's column that the fetched row must be known to: row r0-2 is
     // read by the band's first row only; row r0-1 by the first row and, one delay later, by the second.
@@ -1217,8 +1333,77 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
     }
     lds_barrier();
 
-    for (int t = t_begin; t <= t_end; ++t) {
+    // Per step: the word of column (t - t_begin) + ahead + 1, requested a step ago, goes to the ring for the next
+    // step's gather, and the column after it is requested; columns right of the image read as zero.  The fetch wave
+    // does this where it has no out-block to compute, in two halves when it has such a round in the first layer too:
+    // first the check of the word that has arrived and its conversion (fetch_check), then, behind the barrier that
+    // follows this step's gather and before the one that ends the step, the ring write and the next request
+    // (fetch_put).  The request always loads (the row's last word again beyond the image): no branch, the value is
+    // not used then.
+    uint32_t fetched = 0;
+    auto fetch_check = [&](int t) __attribute__((always_inline)) {
+        if (fetcher) {
+            const int cc = t - t_begin + ahead + 1;
+            uint32_t v = cc < W ? pf : 0u;
+            if (cc < W && !(v & kMailTag)) {            // seldom: the band above is less than a step ahead
+                bool ok = true;
+                v = wait_word(cc, v, ok);
+                if (!ok) give_up();
+            }
+            fetched = v;
+        }
+    };
+    auto fetch_put = [&](int t) __attribute__((always_inline)) {
+        if (fetcher) {
+            const int cc = t - t_begin + ahead + 1;
+            if (cc < W + kMaxReach) ring_put(tid & 1, cc, fetched);
+            pf = __hip_atomic_load(mail_row + min(cc + 1, W - 1), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    };
+    // The pixels decoded in step t_done go from the ring (which holds a pixel for kRingCols steps, as three bf16 of
+    // its bytes) to the image: by the 16 first lanes of the storing wave, a lane per row of the band, a step later,
+    // where that wave has no out-block to compute, instead of by the lanes that decoded them at the end of their
+    // step, where all four waves would wait for it.  Again in two halves: the ring read, then the stores.
+    uint16_t held[3] = {0, 0, 0};
+    auto store_read = [&](int t_done) __attribute__((always_inline)) {
+        if ((tid >> 6) == D::kStoreWave && lane < kBandRows) {
+            const int cc = t_done - kDelay * (r0 + lane);
+            const uint16_t* e = ring + (lane + 2) * D::kRingRowElems + (cc & (RC - 1)) * 3;
+#pragma unroll
+            for (int ch = 0; ch < 3; ++ch) held[ch] = e[ch];
+        }
+    };
+    auto store_write = [&](int t_done) __attribute__((always_inline)) {
+        if ((tid >> 6) == D::kStoreWave && lane < kBandRows) {
+            const int row = r0 + lane, cc = t_done - kDelay * row;
+            if (row < H && cc >= 0 && cc < W) {
+                uint8_t* o = out_img + ((size_t)row * W + cc) * 3;
+#pragma unroll
+                for (int ch = 0; ch < 3; ++ch) o[ch] = (uint8_t)(uint32_t)__uint_as_float((uint32_t)held[ch] << 16);
+            }
+        }
+    };
+    constexpr bool kStoreInIdle = D::kIdleSlack > 0;
+    int t = t_begin;
+    auto idle = [&](auto layer) __attribute__((always_inline)) {
+        constexpr int L = decltype(layer)::value;
+        if constexpr (!D::kIdleInFirstLayer) {
+            fetch_check(t); fetch_put(t);
+            store_read(t - 1); store_write(t - 1);
+        } else if constexpr (L == 0) {
+            fetch_check(t);
+            store_read(t - 1);
+        } else {
+            fetch_put(t);
+            store_write(t - 1);
+        }
+    };
+
+    PhaseClock clk;
+    clk.reset();
+    for (; t <= t_end; ++t) {
         if ((t & 7) == 0 && misc[1] != 0) break;  // uniform: written before the last barrier; a late exit only decodes garbage
+        clk.mark(kPhTop);
 
         // ---- gather C_ij from the ring (zeros stand for pixels outside the image); every wave builds the full tile
         u32x4_t in1[KB0][2];
@@ -1252,8 +1437,9 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
             }
         }
 
+        clk.mark(kPhGather);
         // ---- network, layers meeting in LDS
-        net.template run<(MINBLOCKS > 1)>(in1, lane, wave, act0, act1, headout, dump);
+        net.template run<(MINBLOCKS > 1)>(in1, lane, wave, wave_s, act0, act1, headout, idle, clk);
 
         // ---- mixtures: lane j < 3K of pixel q prepares component j % K of channel j / K
         auto prepare = [&](int jj) __attribute__((always_inline)) {
@@ -1312,6 +1498,7 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
             });
         }
 
+        clk.mark(kPhMixture);
         const int c = t - kDelay * qrow;
         const bool active = qrow_ok && c >= 0 && c < W;
         uint32_t start, freq;
@@ -1320,18 +1507,21 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
         const int sr = group_search<K>(cpr, slot, lut, lane, start, freq);
         reader_advance(rd, slot, start, freq, j, active);
         const float rhat = (float)sr * (1.0f / 256.0f);
+        clk.mark(kPhR);
         // G given R
         couple_green<K>(cpg, alpha, rhat);
         slot = (uint32_t)rd.x & 0xFFFFu;
         const int sg = group_search<K>(cpg, slot, lut, lane, start, freq);
         reader_advance(rd, slot, start, freq, j, active);
         const float ghat = (float)sg * (1.0f / 256.0f);
+        clk.mark(kPhG);
         // B given R, G
         couple_blue<K>(cpb, beta, gamma, rhat, ghat);
         slot = (uint32_t)rd.x & 0xFFFFu;
         const int sb = group_search<K>(cpb, slot, lut, lane, start, freq);
         reader_advance(rd, slot, start, freq, j, active);
         reader_refill(rd, j);
+        clk.mark(kPhB);
 
         // ---- publish
         if (j == 0 && active) {
@@ -1341,27 +1531,29 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
 #pragma unroll
                 for (int z = 0; z < kMaxReach; ++z) ring_put(q + 2, W + z, 0u);
             }
-            uint8_t* o = out_img + ((size_t)qrow * W + c) * 3;
-            o[0] = (uint8_t)sr; o[1] = (uint8_t)sg; o[2] = (uint8_t)sb;
+            if constexpr (!kStoreInIdle) {
+                uint8_t* o = out_img + ((size_t)qrow * W + c) * 3;
+                o[0] = (uint8_t)sr; o[1] = (uint8_t)sg; o[2] = (uint8_t)sb;
+            }
             if (q >= kBandRows - 2)
                 __hip_atomic_store(mail_out + (size_t)(q - (kBandRows - 2)) * W + c, px | kMailTag, __ATOMIC_RELAXED,
                                    __HIP_MEMORY_SCOPE_AGENT);
             if (c == W - 1 && (rd.bad || rd.x != kRansL || rd.pos != rd.nwords)) set_error(status, PCC_E_STREAM);
         }
-        // ---- rows above the band: column needed by the next step, and request the one after
-        if (fetcher) {
-            const int cc = t - t_begin + ahead + 1;
-            if (cc >= W && cc < W + kMaxReach) ring_put(tid & 1, cc, 0u);    // the columns right of the image read as zero
-            if (cc < W && t < t_end) {
-                bool ok = true;
-                const uint32_t v = wait_word(cc, pf, ok);
-                if (ok) ring_put(tid & 1, cc, v);
-                pf = (ok && cc + 1 < W) ? __hip_atomic_load(mail_row + cc + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
-                if (!ok) give_up();
-            }
-        }
+        clk.mark(kPhPublish);
+        // ---- rows above the band, where no layer leaves the fetch wave spare time for it
+        if constexpr (D::kIdleSlack == 0) { fetch_check(t); fetch_put(t); }
+        clk.mark(kPhFetch);
         lds_barrier();
+        clk.mark(kPhBarrier);
     }
+#ifdef PCC_PHASE_TIMING
+    if (ticket == min(kPhaseTicket, total_bands - 1) && lane == 0) {
+        for (int i = 0; i < kPhCount; ++i) phase_cycles[wave][i] = clk.acc[i];
+        phase_cycles[wave][kPhCount] = (unsigned long long)(t_end - t_begin + 1);
+    }
+#endif
+    if constexpr (kStoreInIdle) { store_read(t_end); store_write(t_end); }      // the last step's pixels (the loop ended behind a barrier)
     if (misc[1] != 0) break;    // uniform: written before the last barrier.  The call has failed; no further bands.
     }
 }
@@ -2154,5 +2346,14 @@ int pcc_copy_intervals(pcc_ctx* ctx, uint32_t* d_out, size_t count, void* hip_st
         hipSuccess) return PCC_E_HIP;
     return PCC_OK;
 }
+
+#ifdef PCC_PHASE_TIMING
+// measurement build only: cycles per phase and wave of the last decode's workgroup of ticket kPhaseTicket,
+// h_out[4][kPhCount + 1] (the last value is the number of steps)
+int pcc_debug_phase_cycles(unsigned long long* h_out) {
+    return hipMemcpyFromSymbol(h_out, HIP_SYMBOL(pcc::phase_cycles), sizeof(unsigned long long) * 4 * (kPhCount + 1)) == hipSuccess
+               ? PCC_OK : PCC_E_HIP;
+}
+#endif
 
 }  // extern "C"
