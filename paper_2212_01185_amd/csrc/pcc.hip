@@ -764,8 +764,7 @@ struct DecLds {
     static constexpr int kRingRowElems = 2 * Net::kRingCols * 3 + Net::kRingPad;
     static constexpr int kRingOff = kCpOff + 16 * 3 * kCpStride * 4;
     static constexpr int kMiscOff = kRingOff + 18 * kRingRowElems * 2; // ticket, abort flag
-    static constexpr int kPxOff = kMiscOff + 64;                       // the step's 16 decoded pixels, r | g << 8 | b << 16
-    static constexpr int kBytes = (kPxOff + 16 * 4 + 15) / 16 * 16;
+    static constexpr int kBytes = (kMiscOff + 64 + 15) / 16 * 16;
     // Two workgroups per CU have 256 registers per lane each, too few for the whole of a wave's weight slices: there
     // the biases, and the weights of the first layer and of the head where two workgroups' LDS then still fits a CU,
     // are kept in LDS behind the above and read when used.
@@ -1118,9 +1117,11 @@ struct WaveNet<Net, SHARED, L, true> {
 
 // Symbol search by the 16 lanes (j = 0..15) of one pixel: two sweeps of 16
 // evaluations.  All lanes of the group return the same x, start, freq.
-template <int K>
+// prefetch(): called once the second sweep's table reads are issued; memory requests made there (the next channel's
+// parameters) queue behind those reads and arrive while this channel's reductions and the coder's update run.
+template <int K, class Prefetch>
 __device__ __forceinline__ int group_search(const ChanParams<K>& cp, uint32_t slot, const float2* __restrict__ lut, int lane,
-                                            uint32_t& start, uint32_t& freq) {
+                                            uint32_t& start, uint32_t& freq, Prefetch& prefetch) {
     const int j = lane & 15, shift = lane & 48;
     // first sweep: Cq(16 j); lanes 0..b satisfy Cq <= slot (Cq is increasing and Cq(0) = 0).
     // Lane 0 evaluates too and discards the value: no branch.
@@ -1131,7 +1132,12 @@ __device__ __forceinline__ int group_search(const ChanParams<K>& cp, uint32_t sl
     const uint32_t lo1 = row_allmax(p1 ? c1 : 0u);           // Cq(16 b)
     const uint32_t hi1 = row_allmin(p1 ? 65536u : c1);       // Cq(16 b + 16)
     // second sweep: Cq(16 b + j)
-    const uint32_t e2 = cq_eval<K>(cp, 16 * b + j, lut);
+    CqLookup<K> look;
+    cq_lookup<K>(cp, 16 * b + j, lut, look);
+    asm volatile("" ::: "memory");           // ordering of memory requests only: the table reads first
+    prefetch();
+    asm volatile("" ::: "memory");
+    const uint32_t e2 = cq_finish<K>(cp, 16 * b + j, look);
     const uint32_t c2 = j == 0 ? lo1 : e2;
     const bool p2 = c2 <= slot;
     const int cnt2 = __popcll((__ballot(p2) >> shift) & 0xFFFFull);
@@ -1174,7 +1180,6 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
     float* cpbuf = reinterpret_cast<float*>(lds + D::kCpOff);
     uint16_t* ring = reinterpret_cast<uint16_t*>(lds + D::kRingOff);
     int* misc = reinterpret_cast<int*>(lds + D::kMiscOff);            // [0] ticket, [1] abort
-    uint32_t* pxbuf = reinterpret_cast<uint32_t*>(lds + D::kPxOff);
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     // a scalar where a branch on it pays (two workgroups per CU); measured slower as a scalar otherwise
@@ -1473,30 +1478,44 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
 
-        // everything the three searches need, in one batch of LDS reads
+        // What the three searches need, channel by channel: R's mixture now, G's and B's (with their coupling
+        // coefficients) while the search before them waits for its last table reads.  Requested all at once, the reads
+        // of the four waves keep LDS busy for hundreds of cycles in front of R's first table reads.
         ChanParams<K> cpr, cpg, cpb;
         float alpha[K], beta[K], gamma[K];
-        {
-            auto load_cp = [&](int ch, ChanParams<K>& cp) {
-                float v[3 * K];
-                lds_read_floats<3 * K>(cpbuf + (q * 3 + ch) * D::kCpStride, v);
+        const float* hq = headout + q * D::kHeadStride;
+        // `tail` receives the last vector read, padding included: the caller keeps it in use until the values are
+        // consumed (register allocation only: a padding register that is free at once is handed to the next read,
+        // which then has to wait for this one)
+        auto load_cp = [&](int ch, ChanParams<K>& cp, f32x4_t& tail) __attribute__((always_inline)) {
+            constexpr int NV = (3 * K + 3) / 4;
+            const f32x4_t* src = reinterpret_cast<const f32x4_t*>(cpbuf + (q * 3 + ch) * D::kCpStride);
+            f32x4_t vv[NV];
 #pragma unroll
-                for (int k = 0; k < K; ++k) { cp.pi[k] = v[k]; cp.mu[k] = v[K + k]; cp.a[k] = v[2 * K + k]; }
-            };
-            load_cp(0, cpr); load_cp(1, cpg); load_cp(2, cpb);
-            // coupling coefficients: canonical head outputs 9K.. (alpha), 10K.. (beta), 11K.. (gamma), wherever
-            // the head's (group, register) layout put them
-            const float* hq = headout + q * D::kHeadStride;
-            float g3[HS];                           // group 3 holds most of them: whole vector reads
-            lds_read_floats<HS>(hq + 3 * HS, g3);
+            for (int i = 0; i < NV; ++i) vv[i] = src[i];
+            tail = vv[NV - 1];
+            auto at = [&](int i) { const f32x4_t w = vv[i >> 2]; return (i & 3) == 0 ? w.x : (i & 3) == 1 ? w.y : (i & 3) == 2 ? w.z : w.w; };
+#pragma unroll
+            for (int k = 0; k < K; ++k) { cp.pi[k] = at(k); cp.mu[k] = at(K + k); cp.a[k] = at(2 * K + k); }
+        };
+        f32x4_t tail_r, tail_g, tail_b;
+        // coupling coefficients: canonical head outputs 9K.. (alpha), 10K.. (beta), 11K.. (gamma), wherever the head's
+        // (group, register) layout put them
+        auto load_g = [&]() __attribute__((always_inline)) {
+            load_cp(1, cpg, tail_g);
+            static_for<0, K>([&](auto kc) { alpha[decltype(kc)::value] = hq[head_slot<Net>(9 * K + decltype(kc)::value)]; });
+        };
+        auto load_b = [&]() __attribute__((always_inline)) {
+            load_cp(2, cpb, tail_b);
             static_for<0, K>([&](auto kc) {
                 constexpr int k = decltype(kc)::value;
-                constexpr int sa = head_slot<Net>(9 * K + k), sb = head_slot<Net>(10 * K + k), sc = head_slot<Net>(11 * K + k);
-                if constexpr (sa / HS == 3) alpha[k] = g3[sa % HS]; else alpha[k] = hq[sa];
-                if constexpr (sb / HS == 3) beta[k] = g3[sb % HS]; else beta[k] = hq[sb];
-                if constexpr (sc / HS == 3) gamma[k] = g3[sc % HS]; else gamma[k] = hq[sc];
+                beta[k] = hq[head_slot<Net>(10 * K + k)];
+                gamma[k] = hq[head_slot<Net>(11 * K + k)];
             });
-        }
+        };
+        auto load_nothing = [&]() __attribute__((always_inline)) {};
+        load_cp(0, cpr, tail_r);
+        asm volatile("" ::: "memory");
 
         clk.mark(kPhMixture);
         const int c = t - kDelay * qrow;
@@ -1504,21 +1523,23 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
         uint32_t start, freq;
         // R
         uint32_t slot = (uint32_t)rd.x & 0xFFFFu;
-        const int sr = group_search<K>(cpr, slot, lut, lane, start, freq);
+        const int sr = group_search<K>(cpr, slot, lut, lane, start, freq, load_g);
         reader_advance(rd, slot, start, freq, j, active);
-        const float rhat = (float)sr * (1.0f / 256.0f);
+        float rhat = (float)sr * (1.0f / 256.0f);
         clk.mark(kPhR);
         // G given R
+        asm volatile("" : "+v"(rhat) : "v"(tail_r), "v"(tail_g));    // (tied to a value known only now: stays here)
         couple_green<K>(cpg, alpha, rhat);
         slot = (uint32_t)rd.x & 0xFFFFu;
-        const int sg = group_search<K>(cpg, slot, lut, lane, start, freq);
+        const int sg = group_search<K>(cpg, slot, lut, lane, start, freq, load_b);
         reader_advance(rd, slot, start, freq, j, active);
-        const float ghat = (float)sg * (1.0f / 256.0f);
+        float ghat = (float)sg * (1.0f / 256.0f);
         clk.mark(kPhG);
         // B given R, G
+        asm volatile("" : "+v"(ghat) : "v"(tail_b));
         couple_blue<K>(cpb, beta, gamma, rhat, ghat);
         slot = (uint32_t)rd.x & 0xFFFFu;
-        const int sb = group_search<K>(cpb, slot, lut, lane, start, freq);
+        const int sb = group_search<K>(cpb, slot, lut, lane, start, freq, load_nothing);
         reader_advance(rd, slot, start, freq, j, active);
         reader_refill(rd, j);
         clk.mark(kPhB);

@@ -490,17 +490,28 @@ __device__ __forceinline__ void couple_blue(ChanParams<K>& cp, const float (&bet
 // differences are exact, so one fma per lookup is non-decreasing in z; with
 // pi_k >= 0 every later step (fma, floor) keeps that, hence Cq is strictly
 // increasing in e and every symbol has frequency >= 1.
+// In two halves, so that a caller can put other memory requests between the table reads and their use:
+// cq_lookup computes the table coordinates and issues the reads, cq_finish interpolates, sums and rounds.
 template <int K>
-__device__ __forceinline__ uint32_t cq_eval(const ChanParams<K>& cp, int e, const float2* __restrict__ lut) {
-    static_assert(K == 3 || K == 5 || K == 7, "the scheduling barrier below lists the table reads explicitly");
-    const float edge = (float)(2 * e - 1) * (1.0f / 512.0f);
+struct CqLookup {
     float t[K];
     float2 td[K];
+};
+
+template <int K>
+__device__ __forceinline__ void cq_lookup(const ChanParams<K>& cp, int e, const float2* __restrict__ lut, CqLookup<K>& q) {
+    const float edge = (float)(2 * e - 1) * (1.0f / 512.0f);
 #pragma unroll
     for (int k = 0; k < K; ++k) {
-        t[k] = __builtin_amdgcn_fmed3f(__builtin_fmaf(edge - cp.mu[k], cp.a[k], kLutBias), 0.0f, kLutMax);
-        td[k] = lut[(int)t[k]];                                // t >= 0: truncation is floor
+        q.t[k] = __builtin_amdgcn_fmed3f(__builtin_fmaf(edge - cp.mu[k], cp.a[k], kLutBias), 0.0f, kLutMax);
+        q.td[k] = lut[(int)q.t[k]];                                // t >= 0: truncation is floor
     }
+}
+
+template <int K>
+__device__ __forceinline__ uint32_t cq_finish(const ChanParams<K>& cp, int e, CqLookup<K>& q) {
+    static_assert(K == 3 || K == 5 || K == 7, "the scheduling barrier below lists the table reads explicitly");
+    float2 (&td)[K] = q.td;
     // Scheduling only: all table reads are in flight before the first is used
     // (one LDS latency per evaluation instead of K).
     if constexpr (K == 7) {
@@ -516,11 +527,19 @@ __device__ __forceinline__ uint32_t cq_eval(const ChanParams<K>& cp, int e, cons
     float acc = 0.0f;
 #pragma unroll
     for (int k = 0; k < K; ++k) {
-        const float phi = __builtin_fmaf(__builtin_amdgcn_fractf(t[k]), td[k].y, td[k].x);
+        const float phi = __builtin_fmaf(__builtin_amdgcn_fractf(q.t[k]), td[k].y, td[k].x);
         acc = __builtin_fmaf(cp.pi[k], phi, acc);
     }
-    const float v = fminf(floorf(acc * 65280.0f), 65280.0f);
+    // acc >= 0: the conversion to an unsigned integer, which drops the fraction, is the floor
+    const float v = fminf(acc * 65280.0f, 65280.0f);
     return (uint32_t)e + (uint32_t)v;
+}
+
+template <int K>
+__device__ __forceinline__ uint32_t cq_eval(const ChanParams<K>& cp, int e, const float2* __restrict__ lut) {
+    CqLookup<K> q;
+    cq_lookup<K>(cp, e, lut, q);
+    return cq_finish<K>(cp, e, q);
 }
 
 template <int K>
