@@ -89,6 +89,43 @@ def host_description():
     return {"cpu_model": model, "nproc": os.cpu_count()}
 
 
+PHASE_NAMES = ("gather", "layer 1", "layer 2", "layer 3", "layer 4", "layer 5", "layer 6", "layer 7", "mixtures",
+               "search R", "search G", "search B", "publish", "fetch at step end", "end barrier", "loop top")
+
+
+def phase_profile(codec, d_img, d_stream, d_out, n, h, w):
+    """Cycles per decode step and phase, per wave of the workgroup that decoded ticket 8 (or the last one), from the
+    build with -DPCC_PHASE_TIMING.  Each of the 13 marks of a step costs that build about 56 cycles (what an empty
+    phase reads) and keeps the compiler from moving instructions across it: the sum is above the product's step."""
+    import ctypes
+    import torch
+    from paper_2212_01185_amd import binding
+    lib = binding.load()
+    if not hasattr(lib, "pcc_debug_phase_cycles"):
+        sys.exit("bench.py --phase-profile: %s was not built with -DPCC_PHASE_TIMING" % binding.LIB_PATH)
+    codec.pcc_set_profiling(True)
+    s = codec.pcc_encode(d_img, out=d_stream)
+    for _ in range(4):
+        codec.pcc_decode(s, n, h, w, out=d_out)
+    torch.cuda.synchronize()
+    assert torch.equal(d_out, d_img)
+    ms = codec.pcc_last_timings()["decode"]
+    arr = (ctypes.c_ulonglong * (4 * 17))()
+    lib.pcc_debug_phase_cycles.argtypes = [ctypes.c_void_p]
+    assert lib.pcc_debug_phase_cycles(arr) == 0
+    steps = float(arr[16])
+    print("decode %.3f ms, %.3f us per wavefront step (%d); the profiled band ran %d steps" %
+          (ms, ms * 1e3 / binding.pcc_wavefront_steps(h, w, codec.delay), binding.pcc_wavefront_steps(h, w, codec.delay), steps))
+    print("| phase | wave 0 | wave 1 | wave 2 | wave 3 |\n|---|---|---|---|---|")
+    tot = [0.0] * 4
+    for k, name in enumerate(PHASE_NAMES):
+        row = [arr[wv * 17 + k] / steps for wv in range(4)]
+        if any(row):
+            print("| %s | %s |" % (name, " | ".join("%.0f" % v for v in row)))
+            tot = [a + b for a, b in zip(tot, row)]
+    print("| sum | %s |" % " | ".join("%.0f" % v for v in tot))
+
+
 def measure_workload(codec, imgs, steps, warmup, flop_per_pixel):
     """Encode + decode `steps` times (after `warmup` untimed ones), inputs and outputs resident in HBM: the figures
     of one workload for the all_configs table.  The round trip is checked."""
@@ -140,6 +177,9 @@ def main():
     ap.add_argument("--cpu-rows", type=int, default=256, help="rows of image 0 the oracle baseline codes (about 13 s)")
     ap.add_argument("--network", choices=("workload", "paper", "diagonal") + tuple(ABLATION_SHAPES), default="workload")
     ap.add_argument("--image", default=None, help="WxH of one synthetic image instead of a numbered config")
+    ap.add_argument("--phase-profile", action="store_true",
+                    help="needs PCC_LIBRARY to name a build made with -DPCC_PHASE_TIMING: decode the workload and print "
+                         "the cycles per decode step and phase that the waves of one workgroup counted, no JSON")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs: three encodes + decodes and one plain "
                          "64 MiB device copy of known traffic, no timing, no JSON")
@@ -170,6 +210,9 @@ def main():
     d_img = torch.from_numpy(imgs).cuda()
     d_stream = torch.empty(binding.pcc_stream_bound(n, h, w), dtype=torch.uint8, device="cuda")
     d_out = torch.empty_like(d_img)
+    if args.phase_profile:
+        phase_profile(codec, d_img, d_stream, d_out, n, h, w)
+        return
     if args.traffic_probe:
         src = torch.zeros(64 << 20, dtype=torch.uint8, device="cuda")
         dst = torch.empty_like(src)

@@ -13,7 +13,9 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libpcc.so")
+# PCC_LIBRARY: another build of the same library, e.g. the measurement build with per-phase cycle counters
+# (python -m paper_2212_01185_amd.build --out PATH -DPCC_PHASE_TIMING)
+LIB_PATH = os.environ.get("PCC_LIBRARY") or os.path.join(_HERE, "libpcc.so")
 
 PCC_OK = 0
 PCC_E_ARG, PCC_E_BLOB, PCC_E_CAP, PCC_E_STREAM, PCC_E_HIP, PCC_E_INTERNAL, PCC_E_UNIMPL, PCC_E_SCRATCH = -1, -2, -3, -4, -5, -6, -7, -8

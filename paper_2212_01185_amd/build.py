@@ -29,6 +29,7 @@ def build(verbose: bool = False, extra=(), lib: str = LIB) -> str:
     """Compile the library to `lib` (default: libpcc.so next to the package).  `extra` are more hipcc flags, e.g.
     -DPCC_PHASE_TIMING for the measurement build that counts the decode step's cycles per phase."""
     LIB = lib
+    os.makedirs(os.path.dirname(os.path.abspath(LIB)), exist_ok=True)
     tmp = LIB + ".tmp%d" % os.getpid()
     cmd = [HIPCC] + FLAGS + list(extra) + ["-o", tmp, SRC]
     if verbose:

@@ -336,8 +336,9 @@ def test_errors_are_reported(codec):
 
 # ----------------------------------------------------------------- full-size workloads
 
-def _sample_check(codec, orc, imgs, n_pixels, n_rows, seed):
-    """Sampled pixels' head outputs and sampled rows' bits against the oracle."""
+def _sample_check(codec, orc, imgs, n_pixels, n_rows, seed, whole_image=None):
+    """Sampled pixels' head outputs and the bits of sampled rows (always rows 0, 1 and the last one, then random
+    ones; of image `whole_image` every row) against the oracle."""
     n, h, w, _ = imgs.shape
     params, bits = codec.pcc_encode_probs(_dev(imgs))
     torch.cuda.synchronize()
@@ -350,16 +351,22 @@ def _sample_check(codec, orc, imgs, n_pixels, n_rows, seed):
     err = np.abs(got - want).max()
     _log("sampled params: max err %.3g over %d pixels" % (err, len(pts)))
     assert err <= PARAM_ATOL
-    # bits on whole rows: encode single-row-context strips with the oracle
+    # bits on whole rows: the oracle codes a strip that ends with the row, so that the row sees its true context
+    rows = [(0, 0), (0, min(1, h - 1)), (n - 1, h - 1)] + [(int(rng.integers(n)), int(rng.integers(h))) for _ in range(max(0, n_rows - 3))]
     tot_g = tot_o = 0.0
-    for _ in range(n_rows):
-        i, r = int(rng.integers(n)), int(rng.integers(2, h))
-        strip = imgs[i:i + 1, r - 2:r + 1]          # rows r-2..r: the last row sees its true context
+    for i, r in rows:
+        strip = imgs[i:i + 1, max(0, r - 2):r + 1]
         _, b = orc.encode(strip, po.MODE_EXACT)
-        tot_o += b[0, 2].sum()
+        tot_o += b[0, -1].sum()
         tot_g += float(bits[i, r].double().sum().item())
-    _log("sampled rows: bits gpu %.1f oracle %.1f" % (tot_g, tot_o))
+    _log("sampled rows (%d): bits gpu %.1f oracle %.1f" % (len(rows), tot_g, tot_o))
     assert abs(tot_g / tot_o - 1) <= BITS_RTOL
+    if whole_image is not None:
+        _, b = orc.encode(imgs[whole_image:whole_image + 1], po.MODE_EXACT)
+        g = float(bits[whole_image].double().sum().item())
+        _log("whole image %d: bits gpu %.1f oracle %.1f" % (whole_image, g, b.sum()))
+        assert abs(g / b.sum() - 1) <= BITS_RTOL
+        assert np.abs(bits[whole_image].cpu().numpy().astype(np.float64) - b[0]).mean() < 0.01
 
 
 @pytest.mark.parametrize("config", [1, 3, 4])
@@ -367,7 +374,7 @@ def test_full_size_single_image(codec, orc, config):
     _log("config %d: generate" % config)
     imgs = synth.make_batch(config)
     n, h, w, _ = imgs.shape
-    _sample_check(codec, orc, imgs, 200, 3 if config == 1 else 1, 20 + config)
+    _sample_check(codec, orc, imgs, 200, 16, 20 + config, whole_image=0 if config == 1 else None)
     _log("config %d: round trip" % config)
     stream, out = _roundtrip(codec, imgs)
     assert np.array_equal(out, imgs)
@@ -383,10 +390,28 @@ def test_full_size_single_image(codec, orc, config):
 def test_batch_of_24(codec, orc):
     _log("config 2: generate")
     imgs = synth.make_batch(2)
-    _sample_check(codec, orc, imgs, 100, 2, 22)
+    _sample_check(codec, orc, imgs, 100, 16, 22, whole_image=17)
     _log("config 2: round trip")
     _, out = _roundtrip(codec, imgs)
     assert np.array_equal(out, imgs)
+
+
+def test_full_size_bits_where_they_are_sensitive(codec_sharp, orc_sharp, predictor_blob, orc_predictor):
+    """With He-initialised weights the distributions are nearly uniform and bit totals hardly react to parameter
+    errors.  The sharp weights (narrow mixtures) and the plane-predictor weights (4.4 bits per sub-pixel) react:
+    sampled rows of the 768x512 workload against the oracle, and the round trip."""
+    from paper_2212_01185_amd import binding
+    imgs = synth.make_batch(1)
+    _log("sharp weights, 768x512")
+    _sample_check(codec_sharp, orc_sharp, imgs, 60, 16, 31)
+    pred = binding.Codec(predictor_blob, 0)
+    try:
+        _log("plane-predictor weights, 768x512")
+        _sample_check(pred, orc_predictor, imgs, 60, 16, 32)
+        _, out = _roundtrip(pred, imgs)
+        assert np.array_equal(out, imgs)
+    finally:
+        pred.close()
 
 
 # ----------------------------------------------------------------- hand-structured weights (closed-form head outputs)

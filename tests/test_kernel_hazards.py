@@ -1,12 +1,22 @@
-"""A check of the compiled kernels, on the CPU: no MFMA result is read too soon along a taken branch.
+"""A check of the compiled kernels, on the CPU: no MFMA result is read too soon on ANY path through the code.
 
-An MFMA's result may be read by another kind of instruction only some wait states after the MFMA was issued
-(eight for the 16x16x32 bf16 shape as this compiler counts them: it puts `s_nop 7` between the two when nothing else
-is there).  The compiler counts those wait states along the instruction stream as laid out; where a branch follows
-the MFMA closely and is taken, the instructions it skipped do not count, and the hardware then reads accumulators
-that are not written yet.  The decoder with two workgroups per compute unit once had such a place (wrong decodes
-now and then, different from run to run).  This test compiles the device code to assembly and looks for the pattern
-in every kernel."""
+An MFMA's result may be read (or overwritten) by another kind of instruction only some wait states after the MFMA
+was issued.  In straight-line code the compiler's hazard recogniser sees to that (it puts `s_nop`s where nothing else
+fills the gap); this test does not trust it across control flow.  It compiles the device code to assembly and walks
+the control-flow graph of every kernel: from each MFMA it follows the fall-through, every branch target and every
+back-edge, counts the wait states along each path (an instruction is one, `s_nop n` is n + 1) and reports any
+instruction other than an MFMA that touches the result registers before the required number has passed.  A branch
+whose target it cannot resolve (an indirect jump) inside such a window fails the test too.
+
+The number required is not typed in: per MFMA opcode it is the gap the compiler itself leaves, in this very
+assembly, between an MFMA and a dependent instruction that follows it with nothing but `s_nop` in between (the
+smallest such gap: the compiler inserts exactly what the hardware needs, hand-written `s_nop`s only add to it;
+with the 16x16x32 bf16 shape it is eight, for vector-ALU and LDS consumers alike).
+
+History: the decoder with two workgroups per compute unit once decoded wrongly now and then (different from run to
+run) when a scalar branch sat between a block's last MFMA and the first read of its accumulators; the kernels now
+finish every block (activation, split, store) inside the branch region that computed it, which this walk confirms
+for whatever the compiler lays out."""
 import os
 import re
 import shutil
@@ -17,16 +27,27 @@ import pytest
 
 from paper_2212_01185_amd import build as pcc_build
 
-WINDOW = 14          # instructions looked at behind an MFMA and behind a branch target
-NEEDED = 8           # wait states between an MFMA and the first read of its result by a non-MFMA instruction
+FALLBACK_NEEDED = 8      # used for an opcode the assembly holds no calibration case for (and as the floor of the planted test)
 
 
 def _regs(tok):
-    m = re.match(r"v\[(\d+):(\d+)\]", tok)
+    """Vector registers (v) and accumulation registers (a, numbered from 1000) named by one operand."""
+    tok = tok.strip().rstrip(",")
+    m = re.match(r"([va])\[(\d+):(\d+)\]$", tok)
     if m:
-        return set(range(int(m.group(1)), int(m.group(2)) + 1))
-    m = re.match(r"v(\d+)$", tok)
-    return {int(m.group(1))} if m else set()
+        base = 1000 if m.group(1) == "a" else 0
+        return set(range(base + int(m.group(2)), base + int(m.group(3)) + 1))
+    m = re.match(r"([va])(\d+)$", tok)
+    return {(1000 if m.group(1) == "a" else 0) + int(m.group(2))} if m else set()
+
+
+def _touched(ins):
+    """Vector registers an instruction reads or writes (operand modifiers are ignored; memory and DPP forms included)."""
+    ops = ins.replace(",", " ").split()[1:]
+    out = set()
+    for o in ops:
+        out |= _regs(o)
+    return out
 
 
 def _functions(lines):
@@ -46,45 +67,78 @@ def _functions(lines):
         yield lines[start].split(":")[0], body, labels
 
 
-def _wait_states(instrs):
-    return sum(int(x.split()[1]) + 1 if x.startswith("s_nop") else 1 for x in instrs)
+def _states(ins):
+    return int(ins.split()[1]) + 1 if ins.startswith("s_nop") else 1
 
 
-def shortest_taken_paths(asm_text):
-    """(wait states, description) of every place where a non-MFMA instruction reads an MFMA's result close behind
-    a branch that was taken close behind that MFMA."""
-    out = []
-    for name, body, labels in _functions(asm_text.split("\n")):
+def calibrate(functions):
+    """opcode -> number of wait states the compiler puts between an MFMA and a dependent instruction that follows it
+    behind nothing but s_nop (the smallest seen: hand-written nops only ever add to the compiler's)."""
+    need = {}
+    for _, body, _ in functions:
         for i, ins in enumerate(body):
             if not ins.startswith("v_mfma"):
                 continue
-            dst = _regs(ins.split()[1].rstrip(","))
-            for d in range(1, WINDOW):
-                if i + d >= len(body):
-                    break
-                br = body[i + d]
-                if not (br.startswith("s_cbranch") or br.startswith("s_branch")):
-                    continue
-                target = labels.get(br.split()[-1])
-                if target is None:
-                    continue
-                for e in range(WINDOW):
-                    if target + e >= len(body):
-                        break
-                    use = body[target + e]
-                    ops = use.replace(",", " ").split()[1:]
-                    is_store = use.startswith(("ds_write", "global_store", "global_atomic", "buffer_store", "scratch_store"))
-                    srcs = ops if is_store else ops[1:]
-                    read = set().union(*[_regs(o) for o in srcs]) if srcs else set()
-                    if read & dst and not use.startswith("v_mfma"):
-                        # between the two: the instructions behind the MFMA up to and with the branch, then the target's
-                        states = _wait_states(body[i + 1:i + d + 1]) + _wait_states(body[target:target + e])
-                        out.append((states, "%s: %s ... %s ... %s" % (name[:60], ins.split()[0], br, use)))
-                        break
-    return out
+            dst = _regs(ins.split()[1])
+            k, gap = i + 1, 0
+            while k < len(body) and body[k].startswith("s_nop"):
+                gap += _states(body[k])
+                k += 1
+            if gap and k < len(body) and not body[k].startswith("v_mfma") and _touched(body[k]) & dst:
+                op = ins.split()[0]
+                need[op] = min(need.get(op, 1 << 30), gap)
+    return need
 
 
-def test_scanner_finds_a_planted_case():
+def early_reads(asm_text, needed=None):
+    """[(wait states, needed, description)] for every path on which an MFMA's result is touched too soon."""
+    functions = list(_functions(asm_text.split("\n")))
+    need = dict(calibrate(functions))
+    if needed is not None:
+        need = {op: needed for op in need} or {}
+    default = needed if needed is not None else max(list(need.values()) + [FALLBACK_NEEDED])
+    out = []
+    for name, body, labels in functions:
+        for i, ins in enumerate(body):
+            if not ins.startswith("v_mfma"):
+                continue
+            op = ins.split()[0]
+            want = need.get(op, default)
+            dst = _regs(ins.split()[1])
+            best = {}
+            stack = [(i + 1, 0)]
+            while stack:
+                pc, st = stack.pop()
+                while pc < len(body) and st < want:
+                    if best.get(pc, 1 << 30) <= st:
+                        break
+                    best[pc] = st
+                    cur = body[pc]
+                    if cur.startswith("v_mfma"):
+                        if _regs(cur.split()[1]) >= dst:
+                            break                      # the accumulators pass on to the next MFMA: its own window starts there
+                    elif _touched(cur) & dst:
+                        out.append((st, want, "%s: %s ... %s" % (name[:70], ins, cur)))
+                        break
+                    if cur.startswith("s_endpgm"):
+                        break
+                    if cur.startswith(("s_setpc", "s_swappc", "s_call")):
+                        out.append((st, want, "%s: %s ... unresolvable jump %s" % (name[:70], ins, cur)))
+                        break
+                    if cur.startswith("s_branch") or cur.startswith("s_cbranch"):
+                        target = labels.get(cur.split()[-1])
+                        if target is None:
+                            out.append((st, want, "%s: %s ... unknown label in %s" % (name[:70], ins, cur)))
+                            break
+                        stack.append((target, st + 1))
+                        if cur.startswith("s_branch"):
+                            break
+                    st += _states(cur)
+                    pc += 1
+    return out, need
+
+
+def test_scanner_finds_planted_cases():
     asm = "\n".join([
         "_Z6kernelv: ; @_Z6kernelv",
         "\tv_mfma_f32_16x16x32_bf16 v[4:7], v[8:11], v[12:15], v[4:7]",
@@ -94,16 +148,35 @@ def test_scanner_finds_a_planted_case():
         ".LBB0_2:",
         "\ts_nop 1",
         "\tv_max_f32_e32 v2, v5, v5",
+        "\ts_endpgm",
         ".Lfunc_end0:",
     ])
-    found = shortest_taken_paths(asm)
-    assert len(found) == 1 and found[0][0] == 3          # the branch, then s_nop 1: three wait states
-    safe = asm.replace("s_nop 1", "s_nop 7")
-    assert shortest_taken_paths(safe)[0][0] == 9
+    found, _ = early_reads(asm, needed=8)
+    assert [f[0] for f in found] == [3]                   # the branch, then s_nop 1: three wait states on the taken path
+    assert not early_reads(asm.replace("s_nop 1", "s_nop 7"), needed=8)[0]
+    # a back-edge: the loop's first instruction reads the accumulators of the MFMA at its end
+    loop = "\n".join([
+        "_Z6kernelv: ; @_Z6kernelv",
+        ".LBB0_1:",
+        "\tv_mul_f32_e32 v0, v4, v4",
+        "\ts_nop 7",
+        "\tv_mfma_f32_16x16x32_bf16 v[4:7], v[8:11], v[12:15], v[4:7]",
+        "\ts_cbranch_scc1 .LBB0_1",
+        "\ts_nop 7",
+        "\ts_endpgm",
+        ".Lfunc_end0:",
+    ])
+    found, _ = early_reads(loop, needed=8)
+    assert [f[0] for f in found] == [1]
+    # a jump the walk cannot follow inside the window
+    jump = asm.replace("s_cbranch_vccnz .LBB0_2", "s_setpc_b64 s[4:5]")
+    assert "unresolvable" in early_reads(jump, needed=8)[0][0][2]
+    # calibration: the planted straight-line case says eight
+    assert calibrate(list(_functions(asm.replace("\ts_cbranch_vccnz .LBB0_2\n", "").split("\n"))))["v_mfma_f32_16x16x32_bf16"] == 8
 
 
 @pytest.mark.skipif(shutil.which(pcc_build.HIPCC) is None and not os.path.exists(pcc_build.HIPCC), reason="no hipcc")
-def test_no_mfma_result_is_read_early_behind_a_taken_branch():
+def test_no_mfma_result_is_touched_early_on_any_path():
     with tempfile.TemporaryDirectory() as tmp:
         out = os.path.join(tmp, "pcc.s")
         flags = [f for f in pcc_build.FLAGS if f not in ("-shared", "-fPIC")]
@@ -112,6 +185,7 @@ def test_no_mfma_result_is_read_early_behind_a_taken_branch():
         assert res.returncode == 0, res.stdout[-2000:]
         asm = open(out).read()
     assert asm.count("v_mfma_f32_16x16x32_bf16") > 1000          # the kernels are in there
-    found = shortest_taken_paths(asm)
-    short = sorted(f for f in found if f[0] < NEEDED)
-    assert not short, "MFMA results read too soon behind a taken branch:\n" + "\n".join("%d wait states: %s" % f for f in short[:10])
+    found, need = early_reads(asm)
+    print("wait states the compiler leaves in straight-line code:", need)
+    assert need.get("v_mfma_f32_16x16x32_bf16", 0) >= 4, need     # calibration cases exist for the shape the kernels use
+    assert not found, "MFMA results touched too soon:\n" + "\n".join("%d of %d wait states: %s" % f for f in sorted(found)[:10])
