@@ -314,55 +314,69 @@ void orc_pmf(const orc_model *m, const double *o, int ch, int r, int g, double *
 
 /* ------------------------------------------------------------------ rANS */
 
-/* Range asymmetric numeral system, one independent stream per image row.
- * 64-bit state x in [2^31, 2^63), 16-bit frequencies (total 2^16), 32-bit
- * renormalisation words.  A row payload is: final encoder state (8 bytes,
- * little-endian), then the words in the order the decoder consumes them.
- * Symbols are pushed last-to-first so the decoder pops them first-to-last. */
+/* Range asymmetric numeral system, one independent stream per image row, coded
+ * with two interleaved states: symbol i of the row (i = 3 c + channel) is coded
+ * on state i mod 2.  Both states share the row's one sequence of words, so the
+ * row stays one stream; two states halve the chain of dependent operations that
+ * a coder has to go through per row (this build's choice, like the coder itself:
+ * the paper used an arithmetic coder on the CPU).
+ * 64-bit states x in [2^31, 2^63), 16-bit frequencies (total 2^16), 32-bit
+ * renormalisation words.  A row payload is: the final encoder states 0 and 1
+ * (8 bytes each, little-endian), then the words in the order the decoder
+ * consumes them.  Symbols are pushed last-to-first so the decoder pops them
+ * first-to-last; a word written before symbol i is pushed is the word read
+ * after symbol i is popped, whichever state it belongs to. */
 #define RANS_L ((uint64_t)1 << 31)
 
-size_t orc_rans_bound(size_t nsym) { return 8 + 4 * (nsym / 2 + 2); }
+size_t orc_rans_bound(size_t nsym) { return 16 + 4 * (nsym / 2 + 2); }
 
 /* start[i], freq[i] for i in decode order.  Returns payload bytes or 0 on error. */
 size_t orc_rans_encode(const uint32_t *start, const uint32_t *freq, size_t nsym, uint8_t *out, size_t cap) {
     uint32_t *words = (uint32_t *)malloc(sizeof(uint32_t) * (nsym / 2 + 2));
     if (!words) return 0;
     size_t nw = 0;
-    uint64_t x = RANS_L;
+    uint64_t x[2] = {RANS_L, RANS_L};
     for (size_t i = nsym; i-- > 0;) {
         uint64_t f = freq[i], s = start[i];
+        uint64_t *xs = &x[i & 1];
         if (f == 0 || s + f > 65536) { free(words); return 0; }
-        if (x >= (f << 47)) { words[nw++] = (uint32_t)x; x >>= 32; }
-        x = ((x / f) << 16) + (x % f) + s;
+        if (*xs >= (f << 47)) { words[nw++] = (uint32_t)*xs; *xs >>= 32; }
+        *xs = ((*xs / f) << 16) + (*xs % f) + s;
     }
-    size_t nbytes = 8 + 4 * nw;
+    size_t nbytes = 16 + 4 * nw;
     if (nbytes > cap) { free(words); return 0; }
-    wr64(out, x);
-    for (size_t j = 0; j < nw; ++j) wr32(out + 8 + 4 * j, words[nw - 1 - j]);
+    wr64(out, x[0]);
+    wr64(out + 8, x[1]);
+    for (size_t j = 0; j < nw; ++j) wr32(out + 16 + 4 * j, words[nw - 1 - j]);
     free(words);
     return nbytes;
 }
 
-typedef struct { uint64_t x; const uint8_t *p, *end; int bad; } rans_dec;
+typedef struct { uint64_t x[2]; size_t n; const uint8_t *p, *end; int bad; } rans_dec;   /* n: symbols popped so far */
 
 static void rans_dec_init(rans_dec *d, const uint8_t *payload, size_t nbytes) {
-    d->bad = nbytes < 8;
-    d->x = d->bad ? RANS_L : rd64(payload);
-    d->p = payload + 8;
+    d->bad = nbytes < 16;
+    d->n = 0;
+    for (int k = 0; k < 2; ++k) {
+        d->x[k] = d->bad ? RANS_L : rd64(payload + 8 * k);
+        if (!d->bad && (d->x[k] < RANS_L || (d->x[k] >> 63))) d->bad = 1;
+    }
+    d->p = payload + 16;
     d->end = payload + nbytes;
-    if (!d->bad && (d->x < RANS_L || (d->x >> 63))) d->bad = 1;
 }
-static uint32_t rans_dec_peek(const rans_dec *d) { return (uint32_t)(d->x & 0xFFFF); }
+static uint32_t rans_dec_peek(const rans_dec *d) { return (uint32_t)(d->x[d->n & 1] & 0xFFFF); }
 static void rans_dec_advance(rans_dec *d, uint32_t start, uint32_t freq) {
-    d->x = (uint64_t)freq * (d->x >> 16) + (d->x & 0xFFFF) - start;
-    if (d->x < RANS_L) {
-        if (d->p + 4 > d->end) { d->bad = 1; d->x |= RANS_L; return; }
-        d->x = (d->x << 32) | rd32(d->p);
+    uint64_t *xs = &d->x[d->n & 1];
+    d->n += 1;
+    *xs = (uint64_t)freq * (*xs >> 16) + (*xs & 0xFFFF) - start;
+    if (*xs < RANS_L) {
+        if (d->p + 4 > d->end) { d->bad = 1; *xs |= RANS_L; return; }
+        *xs = (*xs << 32) | rd32(d->p);
         d->p += 4;
     }
 }
 /* A well-formed payload ends exactly where the encoder began. */
-static int rans_dec_finished(const rans_dec *d) { return !d->bad && d->x == RANS_L && d->p == d->end; }
+static int rans_dec_finished(const rans_dec *d) { return !d->bad && d->x[0] == RANS_L && d->x[1] == RANS_L && d->p == d->end; }
 
 /* Decode nsym symbols against explicit tables cq[i][0..256] (test hook for the coder alone). */
 int orc_rans_decode_tables(const uint8_t *payload, size_t nbytes, const uint32_t *cq_tables, size_t nsym, uint8_t *sym_out) {
@@ -382,12 +396,13 @@ int orc_rans_decode_tables(const uint8_t *payload, size_t nbytes, const uint32_t
 
 /* ------------------------------------------------------------------ container */
 
-/* Stream: 8 little-endian uint32 header words (magic "PCC1", version 1, n, H,
+/* Stream: 8 little-endian uint32 header words (magic "PCC1", version 2, n, H,
  * W, K | nbhd<<8 | delay<<16 | 16<<24 (CDF bits), distribution id, 0), then uint64
  * offsets[n*H + 1] of the row payloads relative to the end of the offset
  * table, then the payloads back to back (each a multiple of 4 bytes). */
 #define STREAM_MAGIC 0x31434350u
 #define STREAM_HEADER 32
+#define STREAM_VERSION 2   /* 1: one coder state per row */
 
 size_t orc_stream_bound(int n, int H, int W) {
     size_t rows = (size_t)n * H;
@@ -413,7 +428,7 @@ int orc_encode(const orc_model *m, const uint8_t *img, int n, int H, int W, int 
     uint32_t *start = (uint32_t *)malloc(nsym * sizeof(uint32_t));
     uint32_t *freq = (uint32_t *)malloc(nsym * sizeof(uint32_t));
     if (!start || !freq) { free(start); free(freq); return ORC_E_INTERNAL; }
-    wr32(stream, STREAM_MAGIC); wr32(stream + 4, 1); wr32(stream + 8, (uint32_t)n);
+    wr32(stream, STREAM_MAGIC); wr32(stream + 4, STREAM_VERSION); wr32(stream + 8, (uint32_t)n);
     wr32(stream + 12, (uint32_t)H); wr32(stream + 16, (uint32_t)W); wr32(stream + 20, model_tag(m));
     wr32(stream + 24, (uint32_t)m->dist); wr32(stream + 28, 0);
     size_t off = 0;
@@ -466,7 +481,7 @@ int orc_decode(const orc_model *m, const uint8_t *stream, size_t nbytes, int n, 
     size_t rows = (size_t)n * H;
     size_t table = STREAM_HEADER + 8 * (rows + 1);
     if (nbytes < table) return ORC_E_STREAM;
-    if (rd32(stream) != STREAM_MAGIC || rd32(stream + 4) != 1 || rd32(stream + 8) != (uint32_t)n ||
+    if (rd32(stream) != STREAM_MAGIC || rd32(stream + 4) != STREAM_VERSION || rd32(stream + 8) != (uint32_t)n ||
         rd32(stream + 12) != (uint32_t)H || rd32(stream + 16) != (uint32_t)W || rd32(stream + 20) != model_tag(m) ||
         rd32(stream + 24) != (uint32_t)m->dist)
         return ORC_E_STREAM;
