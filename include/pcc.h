@@ -50,10 +50,11 @@
  * K gammas of Eq. (3)-(4).
  *
  * Stream (device memory): 8 little-endian uint32 words {magic "PCC1", version
- * 1, n, H, W, K | nbhd<<8 | delay<<16 | 16<<24, distribution id, 0}, uint64 offsets[n*H+1]
+ * 2, n, H, W, K | nbhd<<8 | delay<<16 | 16<<24, distribution id, 0}, uint64 offsets[n*H+1]
  * (relative to the end of that table), then one rANS payload per image row:
- * 8-byte initial decoder state, then 32-bit words in the order the decoder
- * reads them.  Streams written by this library are read by this library; the
+ * the two initial decoder states (8 bytes each; sub-pixel i = 3 c + channel of
+ * the row is coded on state i mod 2), then the 32-bit words, shared by both
+ * states, in the order the decoder reads them.  Streams written by this library are read by this library; the
  * bytes depend on its floating-point evaluation order and are not portable to
  * another implementation of the same model.
  */

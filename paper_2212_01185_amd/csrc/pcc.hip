@@ -36,6 +36,7 @@ namespace pcc {
 constexpr uint32_t kBlobMagic = 0x57434350u;    // "PCCW"
 constexpr uint32_t kStreamMagic = 0x31434350u;  // "PCC1"
 constexpr int kStreamHeader = 32;
+constexpr uint32_t kStreamVersion = 2;          // two coder states per row (1: one)
 constexpr int kBandRows = 16;
 constexpr uint32_t kMailTag = 0x80000000u;
 
@@ -89,7 +90,8 @@ constexpr int kStSide = (int)(kStCleared / sizeof(int));     // index of the fir
 enum { kSideDefer = 0 };
 constexpr size_t kStBytes = kStCleared + 2 * sizeof(int);
 
-__host__ __device__ inline size_t slab_words(int W) { return (6 * (size_t)W + 16) / 4 + 1; }
+// Most 32-bit words a row's payload can have: four of the two final coder states, and one per two symbols plus two.
+__host__ __device__ inline size_t slab_words(int W) { return (6 * (size_t)W + 24) / 4 + 1; }
 
 // ---------------------------------------------------------------------------
 // shared device helpers
@@ -415,7 +417,8 @@ rans_rows_kernel(const uint32_t* __restrict__ sf, const uint64_t* sf_tagged, uin
     const uint32_t live_rows = min((uint32_t)kRansRows, rows - row0);
     const size_t sw = slab_words(W);
     uint32_t wp = (uint32_t)sw;     // slabs fill from the end: the decoder reads the words in reverse order of production
-    uint32_t xl = (uint32_t)kRansL, xh = (uint32_t)(kRansL >> 32);   // the coder state x = xh 2^32 + xl
+    // the two coder states x = xh 2^32 + xl: symbol i of the row is coded on state i mod 2
+    uint32_t xl[2] = {(uint32_t)kRansL, (uint32_t)kRansL}, xh[2] = {(uint32_t)(kRansL >> 32), (uint32_t)(kRansL >> 32)};
 
     // Wave 0 codes; waves 2 and 3 load (symbols from global memory, reciprocals, both to LDS); wave 1 stores (the
     // words the coding wave produced, from LDS to the rows' slabs).  Loads and stores are kept in different waves
@@ -425,6 +428,7 @@ rans_rows_kernel(const uint32_t* __restrict__ sf, const uint64_t* sf_tagged, uin
     constexpr int kLoaders = kRansThreads - 128;
     constexpr int kPerLoader = (kRansRows * kRansChunk + kLoaders - 1) / kLoaders;
     static_assert(kRansRows * kRansChunk % kLoaders == 0 && kRansChunk == 32 && kRansRows == 64, "whole elements per thread");
+    static_assert(kRansChunk % 2 == 0, "a chunk starts at an even symbol index: the state of a symbol follows from its place in the chunk");
     // The pipeline, one stage per round (a round = the coding wave codes a chunk; rounds end in a workgroup
     // barrier), so that no wave waits for memory inside a round:
     //   round k + 3  the chunk's symbols are requested from global memory into registers (two sets, by round parity)
@@ -546,15 +550,20 @@ rans_rows_kernel(const uint32_t* __restrict__ sf, const uint64_t* sf_tagged, uin
                 if (n + 1 < kBatches) fetch(n + 1);
 #pragma unroll
                 for (int u = 0; u < kU; ++u) {
+                    // chunks and batches hold even numbers of symbols: the symbol's index in the row has the parity
+                    // of its index in the batch, so the state is known at compile time and consecutive pushes go to
+                    // different states (two independent chains of dependent operations instead of one)
+                    constexpr int kFirst = (kRansChunk - 1) & 1;
+                    const int st = (kFirst + u) & 1;
                     const uint32_t start = v[n & 1][u] & 0xFFFFu, f = (v[n & 1][u] >> 16) + 1u;
                     // renormalise when x >= f * 2^47; the word is stored either way and only
                     // kept (cnt moves) when it was due: no branch on the serial chain
-                    const bool emit = (xh >> 15) >= f;
-                    outw[b][lane][cnt] = xl;
+                    const bool emit = (xh[st] >> 15) >= f;
+                    outw[b][lane][cnt] = xl[st];
                     cnt += emit ? 1u : 0u;
-                    xl = emit ? xh : xl;
-                    xh = emit ? 0u : xh;
-                    rans_push(xl, xh, f, start, rf[n & 1][u]);
+                    xl[st] = emit ? xh[st] : xl[st];
+                    xh[st] = emit ? 0u : xh[st];
+                    rans_push(xl[st], xh[st], f, start, rf[n & 1][u]);
                 }
             }
             outmeta[b][lane] = (wp << 6) | cnt;   // wp < 2^25, cnt <= 32
@@ -572,9 +581,11 @@ rans_rows_kernel(const uint32_t* __restrict__ sf, const uint64_t* sf_tagged, uin
     }
     if (coder && row < rows) {
         uint32_t* slab = slabs + (size_t)row * sw;
-        slab[wp - 1] = xh;
-        slab[wp - 2] = xl;
-        row_words[row] = (uint32_t)sw - (wp - 2u);
+        slab[wp - 1] = xh[1];
+        slab[wp - 2] = xl[1];
+        slab[wp - 3] = xh[0];
+        slab[wp - 4] = xl[0];
+        row_words[row] = (uint32_t)sw - (wp - 4u);
     }
 }
 
@@ -588,7 +599,7 @@ scan_kernel(const uint32_t* __restrict__ row_words, uint32_t rows, int n, int H,
     if (threadIdx.x == 0) {
         carry = 0;
         uint32_t* hdr = reinterpret_cast<uint32_t*>(stream);
-        hdr[0] = kStreamMagic; hdr[1] = 1; hdr[2] = (uint32_t)n; hdr[3] = (uint32_t)H; hdr[4] = (uint32_t)W;
+        hdr[0] = kStreamMagic; hdr[1] = kStreamVersion; hdr[2] = (uint32_t)n; hdr[3] = (uint32_t)H; hdr[4] = (uint32_t)W;
         hdr[5] = tag; hdr[6] = dist; hdr[7] = 0;
     }
     __syncthreads();
@@ -671,7 +682,7 @@ compact_scan_kernel(const uint32_t* __restrict__ slabs, const uint32_t* __restri
         offsets[row] = off;
         if (row == 0) {
             uint32_t* hdr = reinterpret_cast<uint32_t*>(stream);
-            hdr[0] = kStreamMagic; hdr[1] = 1; hdr[2] = (uint32_t)n; hdr[3] = (uint32_t)H; hdr[4] = (uint32_t)W;
+            hdr[0] = kStreamMagic; hdr[1] = kStreamVersion; hdr[2] = (uint32_t)n; hdr[3] = (uint32_t)H; hdr[4] = (uint32_t)W;
             hdr[5] = tag; hdr[6] = dist; hdr[7] = 0;
         }
         if (row + 1 == rows) {
@@ -842,9 +853,9 @@ __device__ __forceinline__ uint32_t row_allmin(uint32_t v) {
 // memory: a pixel consumes at most three words, and the refill issued at the end
 // of the step in which a block is used up is not needed for another 13 words.
 struct RowReader {
-    uint64_t x;
-    const uint32_t* payload;  // the row's payload: 8-byte state, then the words
-    uint32_t last;            // index of the payload's last 32-bit word (>= 1: the state is two words)
+    uint64_t x, y;            // the two coder states: x is the next symbol's, y the one after's (they swap per symbol)
+    const uint32_t* payload;  // the row's payload: the two 8-byte states, then the words
+    uint32_t last;            // index of the payload's last 32-bit word (>= 3: the states are four words)
     uint32_t nwords, pos;     // words after the state; words consumed so far
     uint32_t blk;             // block held in cur; pos >> 4 is blk or, within a step, blk + 1
     uint32_t cur, nxt;
@@ -857,40 +868,50 @@ struct RowReader {
 // no condition, so its result can stay in flight until it is needed, and it is
 // in bounds for every i as long as payload[0 .. last] is readable.
 __device__ __forceinline__ uint32_t reader_word(const RowReader& rd, uint32_t i) {
-    return rd.payload[min(i + 2u, rd.last)];
+    return rd.payload[min(i + 4u, rd.last)];
 }
 
 // A reader over no words at all (rows outside the image, rows whose offsets are
 // damaged): `safe` is any readable pair of words; every renormalisation then counts as an over-read.
 __device__ __forceinline__ void reader_init_empty(RowReader& rd, const uint32_t* safe, bool bad) {
-    rd.x = kRansL; rd.payload = safe; rd.last = 1; rd.nwords = 0; rd.pos = 0; rd.blk = 0; rd.cur = 0; rd.nxt = 0;
+    rd.x = kRansL; rd.y = kRansL; rd.payload = safe; rd.last = 1; rd.nwords = 0; rd.pos = 0; rd.blk = 0; rd.cur = 0; rd.nxt = 0;
     rd.bad = bad;
 }
 
 __device__ __forceinline__ void reader_init(RowReader& rd, const uint32_t* payload, uint32_t nwords_total, int j) {
     rd.x = (uint64_t)payload[0] | ((uint64_t)payload[1] << 32);
+    rd.y = (uint64_t)payload[2] | ((uint64_t)payload[3] << 32);
     rd.payload = payload;
     rd.last = nwords_total - 1;
-    rd.nwords = nwords_total - 2;
+    rd.nwords = nwords_total - 4;
     rd.pos = 0;
     rd.blk = 0;
     rd.cur = reader_word(rd, (uint32_t)j);
     rd.nxt = reader_word(rd, (uint32_t)j + 16u);
     rd.bad = false;
     if (rd.x < kRansL || (rd.x >> 63)) { rd.bad = true; rd.x = kRansL; }
+    if (rd.y < kRansL || (rd.y >> 63)) { rd.bad = true; rd.y = kRansL; }
 }
 
 // D(x) for the symbol found at (start, freq), and the renormalisation read.  No branches:
 // the next channel's search only waits for the arithmetic, never for control flow.
-__device__ __forceinline__ void reader_advance(RowReader& rd, uint32_t slot, uint32_t start, uint32_t freq, int j,
-                                               bool active) {
+// `state` is the state the symbol was coded on (rd.x for a pixel's first and third symbol, rd.y for its second).
+__device__ __forceinline__ void reader_advance(RowReader& rd, uint64_t& state, uint32_t slot, uint32_t start, uint32_t freq,
+                                               int j, bool active) {
     const uint32_t held = (rd.pos >> 4) != rd.blk ? rd.nxt : rd.cur;
     const uint32_t w = row_allmax((uint32_t)j == (rd.pos & 15u) ? held : 0u);   // words[pos], in every lane of the group
-    const uint64_t x1 = (uint64_t)freq * (rd.x >> 16) + slot - start;
+    const uint64_t x1 = (uint64_t)freq * (state >> 16) + slot - start;
     const bool renorm = active && x1 < kRansL;
-    rd.x = active ? (renorm ? ((x1 << 32) | w) : x1) : rd.x;
+    state = active ? (renorm ? ((x1 << 32) | w) : x1) : state;
     rd.bad = rd.bad | (renorm & (rd.pos >= rd.nwords));
     rd.pos += renorm ? 1u : 0u;
+}
+
+// After a pixel's three symbols (states x, y, x) the next symbol's state is y.
+__device__ __forceinline__ void reader_next_pixel(RowReader& rd, bool active) {
+    const uint64_t x = rd.x, y = rd.y;
+    rd.x = active ? y : x;
+    rd.y = active ? x : y;
 }
 
 // Once per step, after the pixel's three symbols: when a block has been used up, move on
@@ -1254,7 +1275,7 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
     if (ticket == 0 && tid == 0) {
         const uint32_t* hdr = reinterpret_cast<const uint32_t*>(stream);
         const uint64_t last = reinterpret_cast<const uint64_t*>(stream + kStreamHeader)[rows_total];
-        if (hdr[0] != kStreamMagic || hdr[1] != 1u || hdr[2] != (uint32_t)n || hdr[3] != (uint32_t)H ||
+        if (hdr[0] != kStreamMagic || hdr[1] != kStreamVersion || hdr[2] != (uint32_t)n || hdr[3] != (uint32_t)H ||
             hdr[4] != (uint32_t)W || hdr[5] != model_tag<Net>() || hdr[6] != dist || last != payload_bytes)
             set_error(status, PCC_E_STREAM);
     }
@@ -1268,7 +1289,7 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
         const uint64_t* offs = reinterpret_cast<const uint64_t*>(stream + kStreamHeader);
         const uint64_t rowg = (uint64_t)im * H + qrow;
         const uint64_t a = offs[rowg], b = offs[rowg + 1];
-        if (a > b || b > payload_bytes || (b - a) < 8 || ((b - a) & 3) != 0 || (a & 3) != 0 ||
+        if (a > b || b > payload_bytes || (b - a) < 16 || ((b - a) & 3) != 0 || (a & 3) != 0 ||
             (b - a) > 4ull * slab_words(W))
             rd.bad = true;
         else
@@ -1524,15 +1545,15 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
         // R
         uint32_t slot = (uint32_t)rd.x & 0xFFFFu;
         const int sr = group_search<K>(cpr, slot, lut, lane, start, freq, load_g);
-        reader_advance(rd, slot, start, freq, j, active);
+        reader_advance(rd, rd.x, slot, start, freq, j, active);
         float rhat = (float)sr * (1.0f / 256.0f);
         clk.mark(kPhR);
         // G given R
         asm volatile("" : "+v"(rhat) : "v"(tail_r), "v"(tail_g));    // (tied to a value known only now: stays here)
         couple_green<K>(cpg, alpha, rhat);
-        slot = (uint32_t)rd.x & 0xFFFFu;
+        slot = (uint32_t)rd.y & 0xFFFFu;
         const int sg = group_search<K>(cpg, slot, lut, lane, start, freq, load_b);
-        reader_advance(rd, slot, start, freq, j, active);
+        reader_advance(rd, rd.y, slot, start, freq, j, active);
         float ghat = (float)sg * (1.0f / 256.0f);
         clk.mark(kPhG);
         // B given R, G
@@ -1540,7 +1561,8 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
         couple_blue<K>(cpb, beta, gamma, rhat, ghat);
         slot = (uint32_t)rd.x & 0xFFFFu;
         const int sb = group_search<K>(cpb, slot, lut, lane, start, freq, load_nothing);
-        reader_advance(rd, slot, start, freq, j, active);
+        reader_advance(rd, rd.x, slot, start, freq, j, active);
+        reader_next_pixel(rd, active);
         reader_refill(rd, j);
         clk.mark(kPhB);
 
@@ -1559,7 +1581,7 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
             if (q >= kBandRows - 2)
                 __hip_atomic_store(mail_out + (size_t)(q - (kBandRows - 2)) * W + c, px | kMailTag, __ATOMIC_RELAXED,
                                    __HIP_MEMORY_SCOPE_AGENT);
-            if (c == W - 1 && (rd.bad || rd.x != kRansL || rd.pos != rd.nwords)) set_error(status, PCC_E_STREAM);
+            if (c == W - 1 && (rd.bad || rd.x != kRansL || rd.y != kRansL || rd.pos != rd.nwords)) set_error(status, PCC_E_STREAM);
         }
         clk.mark(kPhPublish);
         // ---- rows above the band, where no layer leaves the fetch wave spare time for it
@@ -2286,7 +2308,7 @@ int pcc_decode(pcc_ctx* ctx, const uint8_t* d_stream, size_t nbytes, int n, int 
     if (!guard.ok) return PCC_E_HIP;
     const uint64_t rows = (uint64_t)n * H;
     const uint64_t table = (uint64_t)kStreamHeader + 8 * (rows + 1);
-    if (nbytes < table + 8 * rows) return PCC_E_STREAM;   // every row payload holds at least its 8-byte state
+    if (nbytes < table + 16 * rows) return PCC_E_STREAM;   // every row payload holds at least its two 8-byte states
     const int nbands = (H + kBandRows - 1) / kBandRows;
     const size_t mail_bytes = align_up((size_t)n * nbands * 2 * (size_t)W * 4, 256);
     int rc = ensure_workspace(ctx, mail_bytes);
@@ -2312,7 +2334,7 @@ int pcc_decode_static(pcc_ctx* ctx, const uint8_t* d_stream, size_t nbytes, int 
     if (!guard.ok) return PCC_E_HIP;
     const uint64_t rows = (uint64_t)n * H;
     const uint64_t table = (uint64_t)kStreamHeader + 8 * (rows + 1);
-    if (nbytes < table + 8 * rows) return PCC_E_STREAM;
+    if (nbytes < table + 16 * rows) return PCC_E_STREAM;
     const int nbands = (H + kBandRows - 1) / kBandRows;
     // the array keeps the last call's words (tagged pixels of another image): the part this job uses is cleared
     return decode_with_mailbox(ctx, d_stream, nbytes, n, H, W, nbands, d_img_out, ctx->d_static_scratch, mail_bytes, true,

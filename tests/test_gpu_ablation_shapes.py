@@ -119,7 +119,7 @@ def test_coder_and_container_bit_exact(variant):
         sf = iv.reshape(n * h, 3 * w)
         payloads = [po.rans_encode(row & 0xFFFF, (row >> 16) + 1) for row in sf]
         offs = np.concatenate([[0], np.cumsum([len(p) for p in payloads])]).astype("<u8")
-        want = struct.pack("<8I", 0x31434350, 1, n, h, w, tag, 0, 0) + offs.tobytes() + b"".join(payloads)
+        want = struct.pack("<8I", 0x31434350, 2, n, h, w, tag, 0, 0) + offs.tobytes() + b"".join(payloads)
         assert stream.cpu().numpy().tobytes() == want
 
 

@@ -112,7 +112,7 @@ def _expected_stream(imgs_shape, intervals):
     sf = intervals.reshape(n * h, 3 * w).astype(np.uint32)
     payloads = [po.rans_encode(row & 0xFFFF, (row >> 16) + 1) for row in sf]
     offs = np.concatenate([[0], np.cumsum([len(p) for p in payloads])]).astype("<u8")
-    head = struct.pack("<8I", 0x31434350, 1, n, h, w, TAG, 0, 0)
+    head = struct.pack("<8I", 0x31434350, 2, n, h, w, TAG, 0, 0)
     return head + offs.tobytes() + b"".join(payloads)
 
 
@@ -138,7 +138,7 @@ def test_container_structure(codec_paper):
     stream = codec_paper.pcc_encode(_dev(imgs))
     raw = stream.cpu().numpy().tobytes()
     hdr = struct.unpack("<8I", raw[:32])
-    assert hdr[:7] == (0x31434350, 1, 1, 9, 21, TAG, 0)
+    assert hdr[:7] == (0x31434350, 2, 1, 9, 21, TAG, 0)
     offs = np.frombuffer(raw[32:32 + 8 * 10], dtype="<u8")
     assert offs[0] == 0 and (np.diff(offs.astype(np.int64)) >= 8).all()
     assert 32 + 80 + int(offs[-1]) == len(raw)
@@ -203,7 +203,7 @@ def test_512x512_as_in_the_papers_timing_table(codec_paper, orc_paper):
     ideal = float(bits.double().sum().item())
     over = 8 * stream.numel() - ideal
     _log("stream %d bytes (%.3f bpsp), overhead over ideal %.0f bits" % (stream.numel(), 8 * stream.numel() / (3 * 512 * 512), over))
-    assert 0 <= over - 8 * (32 + 8 * 513) <= 512 * 96 + 64
+    assert 0 <= over - 8 * (32 + 8 * 513) <= 512 * 128 + 64
     assert binding.pcc_wavefront_steps(512, 512, codec_paper.delay) == po.wavefront_steps(512, 512, 3)
 
 
@@ -279,7 +279,7 @@ def test_diagonal_container_bit_exact(codec_diagonal, codec_diagonal_sharp):
         sf = iv.reshape(2 * 17, 3 * 33)
         payloads = [po.rans_encode(row & 0xFFFF, (row >> 16) + 1) for row in sf]
         offs = np.concatenate([[0], np.cumsum([len(p) for p in payloads])]).astype("<u8")
-        want = struct.pack("<8I", 0x31434350, 1, 2, 17, 33, TAG_DIAGONAL, 0, 0) + offs.tobytes() + b"".join(payloads)
+        want = struct.pack("<8I", 0x31434350, 2, 2, 17, 33, TAG_DIAGONAL, 0, 0) + offs.tobytes() + b"".join(payloads)
         assert stream.cpu().numpy().tobytes() == want
 
 

@@ -107,8 +107,8 @@ def test_roundtrip_config0_and_stream_length(codec, orc):
     ideal = float(bits.double().sum().item())
     rows = 64
     over = 8 * stream.numel() - ideal
-    lo = 8 * (32 + 8 * (rows + 1)) + rows * 32
-    hi = 8 * (32 + 8 * (rows + 1)) + rows * 96 + 3 * 64 * 64 * 2.0 ** -14
+    lo = 8 * (32 + 8 * (rows + 1)) + rows * 64       # two 64-bit coder states per row, each carrying 0..32 bits
+    hi = 8 * (32 + 8 * (rows + 1)) + rows * 128 + 3 * 64 * 64 * 2.0 ** -14
     _log("stream %d bytes, ideal %.1f bytes, overhead %.0f bits" % (stream.numel(), ideal / 8, over))
     assert lo - 64 <= over <= hi + 64      # the fp32 log2 of the bit count carries a little rounding
     # oracle stream is about as long (different floating point, same model)
@@ -125,7 +125,7 @@ def _expected_stream(imgs_shape, intervals, dist=0):
     payloads = [po.rans_encode(row & 0xFFFF, (row >> 16) + 1) for row in sf]
     offs = np.concatenate([[0], np.cumsum([len(p) for p in payloads])]).astype("<u8")
     tag = 5 | (10 << 8) | (2 << 16) | (16 << 24)
-    head = struct.pack("<8I", 0x31434350, 1, n, h, w, tag, dist, 0)
+    head = struct.pack("<8I", 0x31434350, 2, n, h, w, tag, dist, 0)
     return head + offs.tobytes() + b"".join(payloads)
 
 
@@ -383,8 +383,8 @@ def test_full_size_single_image(codec, orc, config):
     rows = n * h
     over = 8 * stream.numel() - ideal
     _log("config %d: %d bytes, %.4f bpsp, overhead %.0f bits" % (config, stream.numel(), ideal / imgs.size, over))
-    assert 8 * (32 + 8 * (rows + 1)) + rows * 32 - 1e-4 * ideal <= over
-    assert over <= 8 * (32 + 8 * (rows + 1)) + rows * 96 + imgs.size * 2.0 ** -14 + 1e-4 * ideal
+    assert 8 * (32 + 8 * (rows + 1)) + rows * 64 - 1e-4 * ideal <= over
+    assert over <= 8 * (32 + 8 * (rows + 1)) + rows * 128 + imgs.size * 2.0 ** -14 + 1e-4 * ideal
 
 
 def test_batch_of_24(codec, orc):
@@ -446,8 +446,8 @@ def test_plane_predictor_weights(predictor_blob, orc_predictor):
         np.testing.assert_array_equal(out, imgs)
         rows = n * h
         payload = stream.numel() - (32 + 8 * (rows + 1))               # without header and offsets
-        over = 8.0 * payload - gbits.sum()                             # per row: the 64-bit state, less what it carries
-        assert 32 * rows - 64 <= over <= 96 * rows + 64
+        over = 8.0 * payload - gbits.sum()                             # per row: the two 64-bit states, less what they carry
+        assert 64 * rows - 64 <= over <= 128 * rows + 64
     finally:
         c.close()
 

@@ -31,9 +31,9 @@ def test_host_only_entry_points():
     # Eq. (6) with the paper's neighbourhood (h = 2, so each row trails by 3): D + (D - 1)(h + 1)
     assert binding.pcc_wavefront_steps(512, 512, 3) == 512 + 511 * 3
     assert binding.pcc_wavefront_steps(1, 9, 3) == 9 and binding.pcc_wavefront_steps(0, 9, 3) == 0
-    # header + offsets + per row (state + at most 2 bytes per symbol + slack)
+    # header + offsets + per row (two states + at most 2 bytes per symbol + slack)
     b = binding.pcc_stream_bound(1, 64, 64)
-    assert 32 + 8 * 65 + 64 * (8 + 6 * 64) <= b <= 32 + 8 * 65 + 64 * (6 * 64 + 24)
+    assert 32 + 8 * 65 + 64 * (16 + 6 * 64) <= b <= 32 + 8 * 65 + 64 * (6 * 64 + 32)
     assert binding.pcc_stream_bound(0, 1, 1) == 0
 
 
