@@ -356,23 +356,28 @@ encode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ img
 }
 
 // ---------------------------------------------------------------------------
-// rANS encode, one lane per row.  A workgroup owns 64 rows: the lanes of wave 0
-// each run one row's serial chain; waves 2 and 3 fetch the rows' (start, freq)
-// words chunk by chunk (coalesced, two chunks ahead), compute the fp64
-// reciprocal of every frequency and stage both in LDS; wave 1 copies the words
-// the coding wave produced from LDS to the rows' slabs.  The coding wave's
-// instruction stream, which bounds the kernel, then holds only the chain itself.
+// rANS encode, two lanes per row: one per coder state.  A row's stream carries
+// two interleaved states (symbol i on state i mod 2) that meet only in the order
+// of the words they emit, so each state's serial chain runs in a lane of its
+// own and the order is restored afterwards.  A workgroup owns 32 rows: the 64
+// lanes of wave 0 each run one state's chain; waves 2 and 3 fetch the rows'
+// (start, freq) words chunk by chunk (coalesced, two chunks ahead), compute the
+// fp64 reciprocal of every frequency and stage both in LDS; wave 1 merges the
+// words the two lanes of a row produced, in the order of the symbols that
+// caused them, and copies them from LDS to the rows' slabs.  The coding wave's
+// instruction stream, which bounds the kernel (it is limited by instruction
+// issue, not by the latency of the chain), then holds only the chain itself.
 // ---------------------------------------------------------------------------
-constexpr int kRansRows = 64;
-constexpr int kRansChunk = 32;
+constexpr int kRansRows = 32;
+constexpr int kRansChunk = 64;                      // symbols of a row per round: 32 for each of its two lanes
 constexpr int kRansThreads = 256;
-constexpr uint32_t kRansBesideMaxGroups = 48;      // row-coder workgroups that may run beside the pixel kernel
+constexpr uint32_t kRansBesideMaxGroups = 96;      // row-coder workgroups that may run beside the pixel kernel
 constexpr uint32_t kXcds = 8;
 constexpr uint32_t kRansPatience = 2048;            // polls for one symbol before a row coder beside the pixel kernel stands down (a few ms)
 // Rows at which the row coder of an image takes as long as the pixel kernel with the whole chip (both times are
 // proportional to the width; measured with the 30-160-160-128-60 network, 768x512 to 4096x2160): decides how much of
 // a tall image the pixel kernel does before the row coder joins it.
-constexpr uint32_t kRansBalanceRows = 850;
+constexpr uint32_t kRansBalanceRows = 600;
 // Padding symbol (start 0, frequency 2^16): pushing it leaves the state unchanged
 // and never renormalises, so every chunk can be coded as a full one.
 constexpr uint32_t kRansNop = 0xFFFF0000u;
@@ -401,24 +406,31 @@ template <bool BESIDE>
 __global__ void __launch_bounds__(kRansThreads)
 rans_rows_kernel(const uint32_t* __restrict__ sf, const uint64_t* sf_tagged, uint32_t epoch, int W, uint32_t rows,
                  uint32_t* __restrict__ slabs, uint32_t* __restrict__ row_words, int* status, uint32_t patience) {
+    constexpr int kPerState = kRansChunk / 2;   // symbols of a chunk that one state (one coding lane) takes
+    static_assert(kPerState == 32, "a coding lane's emission flags of a round fill one 32-bit word");
     // [buffer][row][symbol of the chunk]; the odd row strides keep the coding wave's column accesses off shared banks
     __shared__ uint32_t sym[2][kRansRows][kRansChunk + 1];
     __shared__ double rcp[2][kRansRows][kRansChunk + 1];
-    // renormalisation words the coding wave produced in a chunk, in the order produced
-    __shared__ uint32_t outw[2][kRansRows][kRansChunk + 1];
+    // [buffer][state][row][step]: the low state word before each of the lane's symbols of the chunk, in the order
+    // coded; it is one of the stream's words where the lane's flag for that step is set
+    __shared__ uint32_t outw[2][2][kRansRows][kPerState + 1];
+    // [buffer][row][state]: the flags, the first step's in bit 31
+    __shared__ uint32_t outflags[2][kRansRows][2];
+    __shared__ uint32_t final_state[kRansRows][4];   // xl, xh of state 0, xl, xh of state 1 after the row's first symbol
     __shared__ uint32_t abandon;                // set by a loader whose wait ran out: every wave leaves after the round
-    __shared__ uint32_t outmeta[2][kRansRows];  // the row's slab position (words) before the chunk << 6 | words produced in it
     const int tid = threadIdx.x, lane = tid & 63;
     const bool coder = tid < 64;
     const uint32_t row0 = blockIdx.x * kRansRows;
-    const uint32_t row = row0 + lane;
     const uint32_t nsym = 3u * (uint32_t)W;
     const int nchunks = (int)((nsym + kRansChunk - 1) / kRansChunk);
     const uint32_t live_rows = min((uint32_t)kRansRows, rows - row0);
     const size_t sw = slab_words(W);
-    uint32_t wp = (uint32_t)sw;     // slabs fill from the end: the decoder reads the words in reverse order of production
-    // the two coder states x = xh 2^32 + xl: symbol i of the row is coded on state i mod 2
-    uint32_t xl[2] = {(uint32_t)kRansL, (uint32_t)kRansL}, xh[2] = {(uint32_t)(kRansL >> 32), (uint32_t)(kRansL >> 32)};
+    // coding lane: row of the workgroup lane & 31, state lane >> 5 (symbol i of the row is coded on state i mod 2)
+    const int crow = lane & (kRansRows - 1), cstate = lane >> 5;
+    uint32_t xl = (uint32_t)kRansL, xh = (uint32_t)(kRansL >> 32);     // the lane's state x = xh 2^32 + xl
+    // storing lanes keep the slab position of row lane & 31: slabs fill from the end, the decoder reads the words in
+    // reverse order of production
+    uint32_t wp = (uint32_t)sw;
 
     // Wave 0 codes; waves 2 and 3 load (symbols from global memory, reciprocals, both to LDS); wave 1 stores (the
     // words the coding wave produced, from LDS to the rows' slabs).  Loads and stores are kept in different waves
@@ -427,7 +439,7 @@ rans_rows_kernel(const uint32_t* __restrict__ sf, const uint64_t* sf_tagged, uin
     const bool storer = tid >= 64 && tid < 128, loader = tid >= 128;
     constexpr int kLoaders = kRansThreads - 128;
     constexpr int kPerLoader = (kRansRows * kRansChunk + kLoaders - 1) / kLoaders;
-    static_assert(kRansRows * kRansChunk % kLoaders == 0 && kRansChunk == 32 && kRansRows == 64, "whole elements per thread");
+    static_assert(kRansRows * kRansChunk % kLoaders == 0 && kRansRows == 32, "whole elements per thread; a row per lane pair");
     static_assert(kRansChunk % 2 == 0, "a chunk starts at an even symbol index: the state of a symbol follows from its place in the chunk");
     // The pipeline, one stage per round (a round = the coding wave codes a chunk; rounds end in a workgroup
     // barrier), so that no wave waits for memory inside a round:
@@ -500,23 +512,31 @@ rans_rows_kernel(const uint32_t* __restrict__ sf, const uint64_t* sf_tagged, uin
             rcp[b][r][i] = rans_recip_below((v >> 16) + 1u);
         }
     };
-    // wave 1: the words of a finished chunk from buffer b to the rows' slabs.  Lane = word index within the chunk
-    // in both halves of the wave, the halves take the even and the odd rows: consecutive lanes write consecutive
-    // words.  All LDS reads are issued before the first store.
+    // Wave 1: the words of a finished chunk from buffer b to the rows' slabs, one row per iteration.  Lane p stands
+    // for the p-th symbol coded in the round (symbol kRansChunk - 1 - p of the chunk: state 1 when p is even, the
+    // state's step p / 2).  Where that symbol's flag is set, its word goes behind the words of the symbols coded
+    // before it, from either state: the flags set among the first ceil(p / 2) steps of state 1 and the first
+    // floor(p / 2) steps of state 0.  All LDS reads are issued before the first store.
     auto flush = [&](int b) __attribute__((always_inline)) {
-        const uint32_t i = (uint32_t)(tid - 64) % kRansChunk, odd = (uint32_t)(tid - 64) / kRansChunk;
-        uint32_t word[kRansRows / 2], meta[kRansRows / 2];
+        const uint32_t p = (uint32_t)lane, step = p >> 1, state = 1u - (p & 1u);
+        auto first_steps = [](uint32_t nsteps) { return nsteps == 0 ? 0u : 0xFFFFFFFFu << (32u - nsteps); };   // their flag bits
+        const uint32_t before1 = first_steps((p + 1) >> 1), before0 = first_steps(p >> 1), mine = 0x80000000u >> step;
+        uint32_t word[kRansRows], f0[kRansRows], f1[kRansRows];
 #pragma unroll
-        for (int it = 0; it < kRansRows / 2; ++it) {
-            word[it] = outw[b][2 * it + odd][i];
-            meta[it] = outmeta[b][2 * it + odd];
+        for (int r = 0; r < kRansRows; ++r) {
+            word[r] = outw[b][state][r][step];
+            f0[r] = outflags[b][r][0];
+            f1[r] = outflags[b][r][1];
         }
+        const uint32_t own0 = outflags[b][lane & (kRansRows - 1)][0], own1 = outflags[b][lane & (kRansRows - 1)][1];
 #pragma unroll
-        for (int it = 0; it < kRansRows / 2; ++it) {
-            const uint32_t r = 2 * it + odd;
-            if (r < live_rows && i < (meta[it] & 63u))
-                slabs[(size_t)(row0 + r) * sw + ((meta[it] >> 6) - 1u - i)] = word[it];
+        for (int r = 0; r < kRansRows; ++r) {
+            const uint32_t at = (uint32_t)__builtin_amdgcn_readlane((int)wp, r);     // the row's position before this chunk
+            const uint32_t ahead = (uint32_t)__popc(f1[r] & before1) + (uint32_t)__popc(f0[r] & before0);
+            const bool emitted = ((state ? f1[r] : f0[r]) & mine) != 0;
+            if ((uint32_t)r < live_rows && emitted) slabs[(size_t)(row0 + r) * sw + (at - 1u - ahead)] = word[r];
         }
+        wp -= (uint32_t)__popc(own0) + (uint32_t)__popc(own1);
     };
     if (tid == 0) abandon = 0;
     lds_barrier();
@@ -531,43 +551,42 @@ rans_rows_kernel(const uint32_t* __restrict__ sf, const uint64_t* sf_tagged, uin
         } else if (storer) {
             if (k >= -1 && k + 1 < nchunks) flush(b ^ 1);
         } else if (k >= 0 && k < nchunks) {
-            uint32_t cnt = 0;
-            // Symbols and reciprocals come from LDS in batches of kU; the next batch is requested before the
-            // serial chain of the current one starts, so that only the round's first read waits for LDS.
-            constexpr int kU = 8, kBatches = kRansChunk / kU;
+            // The lane's symbols of the chunk, last first: kRansChunk - 2 + cstate, then every second one down to
+            // cstate.  Symbols and reciprocals come from LDS in batches of kU; the next batch is requested before
+            // the serial chain of the current one starts, so that only the round's first read waits for LDS.
+            constexpr int kU = 8, kBatches = kPerState / kU;
             uint32_t v[2][kU];
             double rf[2][kU];
+            const uint32_t* my_sym = &sym[b][crow][cstate];
+            const double* my_rcp = &rcp[b][crow][cstate];
+            uint32_t* my_out = &outw[b][cstate][crow][0];
             auto fetch = [&](int n) {
 #pragma unroll
                 for (int u = 0; u < kU; ++u) {
-                    v[n & 1][u] = sym[b][lane][kRansChunk - 1 - n * kU - u];
-                    rf[n & 1][u] = rcp[b][lane][kRansChunk - 1 - n * kU - u];
+                    v[n & 1][u] = my_sym[kRansChunk - 2 - 2 * (n * kU + u)];
+                    rf[n & 1][u] = my_rcp[kRansChunk - 2 - 2 * (n * kU + u)];
                 }
             };
+            uint32_t flags = 0;
             fetch(0);
 #pragma unroll
             for (int n = 0; n < kBatches; ++n) {
                 if (n + 1 < kBatches) fetch(n + 1);
 #pragma unroll
                 for (int u = 0; u < kU; ++u) {
-                    // chunks and batches hold even numbers of symbols: the symbol's index in the row has the parity
-                    // of its index in the batch, so the state is known at compile time and consecutive pushes go to
-                    // different states (two independent chains of dependent operations instead of one)
-                    constexpr int kFirst = (kRansChunk - 1) & 1;
-                    const int st = (kFirst + u) & 1;
                     const uint32_t start = v[n & 1][u] & 0xFFFFu, f = (v[n & 1][u] >> 16) + 1u;
-                    // renormalise when x >= f * 2^47; the word is stored either way and only
-                    // kept (cnt moves) when it was due: no branch on the serial chain
-                    const bool emit = (xh[st] >> 15) >= f;
-                    outw[b][lane][cnt] = xl[st];
-                    cnt += emit ? 1u : 0u;
-                    xl[st] = emit ? xh[st] : xl[st];
-                    xh[st] = emit ? 0u : xh[st];
-                    rans_push(xl[st], xh[st], f, start, rf[n & 1][u]);
+                    // renormalise when x >= f * 2^47; the low word is stored either way, at the step's own place,
+                    // and only counts where the flag says it was due: no branch and no address arithmetic on the
+                    // serial chain
+                    const bool emit = (xh >> 15) >= f;
+                    my_out[n * kU + u] = xl;
+                    flags = (flags << 1) | (emit ? 1u : 0u);
+                    xl = emit ? xh : xl;
+                    xh = emit ? 0u : xh;
+                    rans_push(xl, xh, f, start, rf[n & 1][u]);
                 }
             }
-            outmeta[b][lane] = (wp << 6) | cnt;   // wp < 2^25, cnt <= 32
-            wp -= cnt;
+            outflags[b][crow][cstate] = flags;
         }
         lds_barrier();   // all that crosses threads here is in LDS; the loaders' global loads stay in flight
         return !BESIDE || abandon == 0;
@@ -575,17 +594,23 @@ rans_rows_kernel(const uint32_t* __restrict__ sf, const uint64_t* sf_tagged, uin
     // rounds nchunks + 2 (or + 3, for an even number of rounds) down to -1, where chunk 0's words are stored
     for (int k = nchunks + 2 + (nchunks & 1); k >= 0; k -= 2) {
         if (!round(k, std::integral_constant<int, 0>()) || !round(k - 1, std::integral_constant<int, 1>())) {
-            if (coder && row < rows) row_words[row] = 0;    // stood down: nothing for the compaction to copy
+            if (tid < kRansRows && row0 + tid < rows) row_words[row0 + tid] = 0;    // stood down: nothing for the compaction to copy
             return;
         }
     }
-    if (coder && row < rows) {
-        uint32_t* slab = slabs + (size_t)row * sw;
-        slab[wp - 1] = xh[1];
-        slab[wp - 2] = xl[1];
-        slab[wp - 3] = xh[0];
-        slab[wp - 4] = xl[0];
-        row_words[row] = (uint32_t)sw - (wp - 4u);
+    if (coder) {
+        final_state[crow][2 * cstate] = xl;
+        final_state[crow][2 * cstate + 1] = xh;
+    }
+    lds_barrier();
+    if (storer && lane < kRansRows && row0 + lane < rows) {
+        // the four state words end the slab's data: the decoder reads them first
+        uint32_t* slab = slabs + (size_t)(row0 + lane) * sw;
+        slab[wp - 1] = final_state[lane][3];
+        slab[wp - 2] = final_state[lane][2];
+        slab[wp - 3] = final_state[lane][1];
+        slab[wp - 4] = final_state[lane][0];
+        row_words[row0 + lane] = (uint32_t)sw - (wp - 4u);
     }
 }
 
@@ -2146,7 +2171,7 @@ int pcc_encode(pcc_ctx* ctx, const uint8_t* d_img, int n, int H, int W, uint8_t*
     // runs after the pixel kernel, on the caller's stream.
     const uint32_t groups = (rows + kRansRows - 1) / kRansRows;
     const uint32_t cus = ctx->num_cus > 0 ? (uint32_t)ctx->num_cus : 256u;
-    bool beside = ctx->overlap && groups <= kRansBesideMaxGroups && cus >= 4 * kRansBesideMaxGroups;
+    bool beside = ctx->overlap && groups <= kRansBesideMaxGroups && cus >= 2 * kRansBesideMaxGroups;
     if (beside) {
         const hipError_t busy = hipStreamQuery(st);
         if (busy != hipSuccess) { (void)hipGetLastError(); beside = false; }

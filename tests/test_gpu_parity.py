@@ -549,7 +549,7 @@ def test_row_coder_beside_after_and_busy_stream_agree(blob, paper_blob, monkeypa
     from paper_2212_01185_amd import binding
     rng = np.random.default_rng(23)
     shapes = [(1, 70, 45), (3, 33, 100), (1, 130, 1), (1, 64, 11), (2, 200, 37), (1, 1, 300)]
-    # either side of the most rows the row coder takes beside the pixel kernel (48 groups of 64), and of the most
+    # either side of the most rows the row coder takes beside the pixel kernel (96 groups of 32), and of the most
     # rows whose sizes the compaction sums by itself (4096)
     shapes += [(1, 3072, 5), (1, 3073, 5), (2, 2048, 3), (1, 4097, 3)]
     # tall enough for the pixel kernel to run in two parts, the row coder joining for the second
