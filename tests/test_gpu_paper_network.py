@@ -15,7 +15,7 @@ torch = pytest.importorskip("torch")
 PARAM_ATOL = 2e-3         # raw head outputs against the exact fp64 network
 # Informative only: the oracle's MODE_SPLIT is a model of the kernel's own hi + lo rounding, so this compares the kernel
 # with a description of itself and carries no independent weight.  The gate is MODE_EXACT at PARAM_ATOL.
-PARAM_ATOL_SPLIT = 2e-4
+PARAM_ATOL_SPLIT = 2e-4      # informative only: the kernel against a model of its own rounding; the gate is MODE_EXACT
 BITS_RTOL = 1e-3          # bits/pixel within 0.1 %
 CQ_ATOL = 2               # integer CDF counts
 TAG = 3 | (12 << 8) | (3 << 16) | (16 << 24)
@@ -73,7 +73,7 @@ def test_params_and_bits_match_oracle(codec_paper, orc_paper):
     want = orc_paper.params_rows(imgs[0], range(64), po.MODE_SPLIT)
     err = np.abs(params - want).max()
     _log("max |params - oracle(split activations)| = %.3g" % err)
-    assert err <= PARAM_ATOL_SPLIT
+    assert err <= PARAM_ATOL_SPLIT, "kernel vs a model of its own rounding (informative; the gate is MODE_EXACT)"
     bits = bits.cpu().numpy().astype(np.float64)
     _, wbits = orc_paper.encode(imgs, po.MODE_EXACT)
     _log("bits/pixel gpu %.5f oracle %.5f" % (bits.mean(), wbits.mean()))
@@ -259,7 +259,8 @@ def test_diagonal_params_and_bits_match_oracle(codec_diagonal, orc_diagonal, orc
         err = np.abs(got - exact).max()
         _log("max |params - oracle(exact)| = %.3g" % err)
         assert err <= PARAM_ATOL
-        assert np.abs(got - orc_diagonal.params_rows(img, range(h), po.MODE_SPLIT)).max() <= PARAM_ATOL_SPLIT
+        assert np.abs(got - orc_diagonal.params_rows(img, range(h), po.MODE_SPLIT)).max() <= PARAM_ATOL_SPLIT, \
+            "kernel vs a model of its own rounding (informative; the gate is MODE_EXACT)"
         # the copied neighbours matter: the wavefront model of the same weights gives other outputs
         assert np.abs(got - orc_paper.params_rows(img, range(h), po.MODE_EXACT)).max() > 10 * PARAM_ATOL
         _, wbits = orc_diagonal.encode(img[None], po.MODE_EXACT)
