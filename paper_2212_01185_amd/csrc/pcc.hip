@@ -2162,7 +2162,7 @@ int pcc_encode(pcc_ctx* ctx, const uint8_t* d_img, int n, int H, int W, uint8_t*
     ctx->d_sf = d_sf;
     ctx->sf_count = (size_t)P * 3;
 
-    // A small job's row coder is a handful of workgroups bound by the latency of their serial chains.  It runs
+    // A small job's row coder is a handful of workgroups, each bound by the instruction stream of its one coding wave.  It runs
     // beside the pixel kernel, on compute units the pixel kernel's grid leaves free (a pixel workgroup fills a
     // unit's LDS, so the workgroups of both kernels are resident whatever order the dispatcher takes them in),
     // and takes each symbol when it finds it written.  The row coder and what comes after it go to a stream of
