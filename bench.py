@@ -75,6 +75,34 @@ def cpu_baseline(blob, imgs, rows):
     }
 
 
+def cpu_baseline_batch(blob, imgs, rows, threads):
+    """The same oracle on a batch, one image per thread (the oracle's library keeps no state outside its model object,
+    and ctypes releases the interpreter lock during a call): encode + raster decode of the first `rows` rows of each image."""
+    import numpy as np
+    from concurrent.futures import ThreadPoolExecutor
+    from oracle import pcc_oracle as po
+    n = imgs.shape[0]
+    threads = max(1, min(threads, n))
+    strips = [np.ascontiguousarray(imgs[i:i + 1, :rows]) for i in range(n)]
+
+    def one(strip):
+        orc = po.Oracle(blob)
+        _, h, w, _ = strip.shape
+        stream, _ = orc.encode(strip, po.MODE_EXACT, want_bits=False)
+        return np.array_equal(orc.decode(stream, 1, h, w, po.MODE_EXACT, po.ORDER_RASTER), strip)
+
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(max_workers=threads) as pool:
+        ok = list(pool.map(one, strips))
+    dt = time.perf_counter() - t0
+    assert all(ok)
+    px = n * strips[0].shape[1] * strips[0].shape[2]
+    return {"value": px / dt / 1e6, "unit": "MPix/s", "cores": threads, "kind": "oracle",
+            "sample": "first %d rows of each of the %d images of the 24 x 768x512 workload (%d pixels), one image per thread, "
+                      "encode + raster decode, fp64" % (rows, n, px),
+            "seconds": dt}
+
+
 def host_description():
     """CPU model and logical core count of the machine the oracle baseline runs on."""
     model = "unknown"
@@ -348,6 +376,10 @@ def main():
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(blob, imgs, min(args.cpu_rows, h))
         result["cpu_baseline"]["host"] = host_description()
+        if headline and not args.no_all_configs:
+            # the batch workload with the host's cores: one image per thread (16 threads is the GPU machine's CPU share)
+            result["cpu_baseline"]["batch"] = cpu_baseline_batch(blob, synth.make_batch(2), 16,
+                                                                 min(16, os.cpu_count() or 1))
     print(json.dumps(result))
 
 
