@@ -1175,8 +1175,11 @@ __device__ __forceinline__ int group_search(const ChanParams<K>& cp, uint32_t sl
     const uint32_t c1 = j == 0 ? 0u : e1;
     const bool p1 = c1 <= slot;
     const int b = __popcll((__ballot(p1) >> shift) & 0xFFFFull) - 1;
-    const uint32_t lo1 = row_allmax(p1 ? c1 : 0u);           // Cq(16 b)
-    const uint32_t hi1 = row_allmin(p1 ? 65536u : c1);       // Cq(16 b + 16)
+    // Cq(16 b + 16), the bound of the symbol's interval if it is the block's last: it sits in lane b + 1 (65536 behind
+    // the group's last lane); one lane shift brings it to lane b, which offers it to the closing minimum below.
+    // (No reduction over the group is needed for it, nor for Cq(16 b): the second sweep's lane 0 evaluates that again.)
+    const uint32_t up = (uint32_t)__builtin_amdgcn_update_dpp(65536, (int)c1, 0x101 /* row_shl:1 */, 0xF, 0xF, false);
+    const uint32_t hi_b = j == b ? up : 0xFFFFFFFFu;
     // second sweep: Cq(16 b + j)
     CqLookup<K> look;
     cq_lookup<K>(cp, 16 * b + j, lut, look);
@@ -1184,11 +1187,11 @@ __device__ __forceinline__ int group_search(const ChanParams<K>& cp, uint32_t sl
     prefetch();
     asm volatile("" ::: "memory");
     const uint32_t e2 = cq_finish<K>(cp, 16 * b + j, look);
-    const uint32_t c2 = j == 0 ? lo1 : e2;
+    const uint32_t c2 = (b | j) == 0 ? 0u : e2;
     const bool p2 = c2 <= slot;
     const int cnt2 = __popcll((__ballot(p2) >> shift) & 0xFFFFull);
     start = row_allmax(p2 ? c2 : 0u);
-    freq = row_allmin(p2 ? hi1 : c2) - start;
+    freq = row_allmin(min(p2 ? 0xFFFFFFFFu : c2, hi_b)) - start;
     return 16 * b + cnt2 - 1;
 }
 
