@@ -1464,29 +1464,30 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
         {
             const int c = t - kDelay * (r0 + nl);
             const int w0 = ((c - 2) & (RC - 1)) * 3;
-            uint32_t v[KB0][8];
+            // a run is four consecutive bf16 values of a ring row (8 bytes at a 2-byte aligned address): read as two
+            // dwords, which are the operand's registers as they stand
+            uint32_t v[KB0][4];
 #pragma unroll
             for (int kbi = 0; kbi < KB0; ++kbi) {
-#pragma unroll
-                for (int i = 0; i < 4; ++i) { v[kbi][i] = run_ptr[kbi][0][w0 + i]; v[kbi][4 + i] = run_ptr[kbi][1][w0 + i]; }
+                uint2 lo, hi;
+                __builtin_memcpy(&lo, run_ptr[kbi][0] + w0, 8);
+                __builtin_memcpy(&hi, run_ptr[kbi][1] + w0, 8);
+                v[kbi][0] = lo.x; v[kbi][1] = lo.y; v[kbi][2] = hi.x; v[kbi][3] = hi.y;
             }
             // one batch of LDS reads
             static_assert(KB0 == 1 || KB0 == 2, "the scheduling barrier below lists the reads explicitly");
             if constexpr (KB0 == 1)
-                asm volatile("" : "+v"(v[0][0]), "+v"(v[0][1]), "+v"(v[0][2]), "+v"(v[0][3]), "+v"(v[0][4]), "+v"(v[0][5]),
-                                  "+v"(v[0][6]), "+v"(v[0][7]));
+                asm volatile("" : "+v"(v[0][0]), "+v"(v[0][1]), "+v"(v[0][2]), "+v"(v[0][3]));
             else
-                asm volatile("" : "+v"(v[0][0]), "+v"(v[0][1]), "+v"(v[0][2]), "+v"(v[0][3]), "+v"(v[0][4]), "+v"(v[0][5]),
-                                  "+v"(v[0][6]), "+v"(v[0][7]), "+v"(v[KB0 - 1][0]), "+v"(v[KB0 - 1][1]), "+v"(v[KB0 - 1][2]),
-                                  "+v"(v[KB0 - 1][3]), "+v"(v[KB0 - 1][4]), "+v"(v[KB0 - 1][5]), "+v"(v[KB0 - 1][6]),
-                                  "+v"(v[KB0 - 1][7]));
+                asm volatile("" : "+v"(v[0][0]), "+v"(v[0][1]), "+v"(v[0][2]), "+v"(v[0][3]), "+v"(v[KB0 - 1][0]),
+                                  "+v"(v[KB0 - 1][1]), "+v"(v[KB0 - 1][2]), "+v"(v[KB0 - 1][3]));
 #pragma unroll
             for (int kbi = 0; kbi < KB0; ++kbi) {
                 const uint32_t m0 = run_used[kbi][0] ? 0xFFFFFFFFu : 0u, m1 = run_used[kbi][1] ? 0xFFFFFFFFu : 0u;
-                in1[kbi][0].x = (v[kbi][0] | (v[kbi][1] << 16)) & m0;
-                in1[kbi][0].y = (v[kbi][2] | (v[kbi][3] << 16)) & m0;
-                in1[kbi][0].z = (v[kbi][4] | (v[kbi][5] << 16)) & m1;
-                in1[kbi][0].w = (v[kbi][6] | (v[kbi][7] << 16)) & m1;
+                in1[kbi][0].x = v[kbi][0] & m0;
+                in1[kbi][0].y = v[kbi][1] & m0;
+                in1[kbi][0].z = v[kbi][2] & m1;
+                in1[kbi][0].w = v[kbi][3] & m1;
                 in1[kbi][1] = in1[kbi][0];   // unused (layer-1 inputs are exact)
             }
         }
