@@ -1387,14 +1387,18 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
     }
     lds_barrier();
 
-    // Per step: the word of column (t - t_begin) + ahead + 1, requested a step ago, goes to the ring for the next
-    // step's gather, and the column after it is requested; columns right of the image read as zero.  The fetch wave
-    // does this where it has no out-block to compute, in two halves when it has such a round in the first layer too:
-    // first the check of the word that has arrived and its conversion (fetch_check), then, behind the barrier that
-    // follows this step's gather and before the one that ends the step, the ring write and the next request
-    // (fetch_put).  The request always loads (the row's last word again beyond the image): no branch, the value is
-    // not used then.
+    // Per step: the word of column (t - t_begin) + ahead + 1, requested in the step before, goes to the ring for the
+    // next step's gather, and the column after it is requested; columns right of the image read as zero.  The fetch
+    // wave does this where it has no out-block to compute, in two halves when it has such a round in the first layer
+    // too: first the check of the word that has arrived and its conversion (fetch_check), then, behind the barrier
+    // that follows this step's gather and before the one that ends the step, the ring write (fetch_put).  With those
+    // two rounds the request (fetch_request) is issued late in the step, behind the table reads of the last channel's
+    // search: the later a word is asked for, the closer the band can follow the band above (a word asked for before
+    // it is published is asked for again, which holds the fetch wave up), and three quarters of a step are still
+    // ample for the load.  The request always loads (the row's last word again beyond the image): no branch, the
+    // value is not used then.
     uint32_t fetched = 0;
+    constexpr bool kLateRequest = D::kIdleInFirstLayer;
     auto fetch_check = [&](int t) __attribute__((always_inline)) {
         if (fetcher) {
             const int cc = t - t_begin + ahead + 1;
@@ -1411,6 +1415,12 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
         if (fetcher) {
             const int cc = t - t_begin + ahead + 1;
             if (cc < W + kMaxReach) ring_put(tid & 1, cc, fetched);
+            if constexpr (!kLateRequest) pf = __hip_atomic_load(mail_row + min(cc + 1, W - 1), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    };
+    auto fetch_request = [&](int t) __attribute__((always_inline)) {
+        if (fetcher) {
+            const int cc = t - t_begin + ahead + 1;
             pf = __hip_atomic_load(mail_row + min(cc + 1, W - 1), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     };
@@ -1563,7 +1573,7 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
                 gamma[k] = hq[head_slot<Net>(11 * K + k)];
             });
         };
-        auto load_nothing = [&]() __attribute__((always_inline)) {};
+        auto load_mailbox = [&]() __attribute__((always_inline)) { if constexpr (kLateRequest) fetch_request(t); };
         load_cp(0, cpr, tail_r);
         asm volatile("" ::: "memory");
 
@@ -1589,7 +1599,7 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
         asm volatile("" : "+v"(ghat) : "v"(tail_b));
         couple_blue<K>(cpb, beta, gamma, rhat, ghat);
         slot = (uint32_t)rd.x & 0xFFFFu;
-        const int sb = group_search<K>(cpb, slot, lut, lane, start, freq, load_nothing);
+        const int sb = group_search<K>(cpb, slot, lut, lane, start, freq, load_mailbox);
         reader_advance(rd, rd.x, slot, start, freq, j, active);
         reader_next_pixel(rd, active);
         reader_refill(rd, j);
