@@ -826,12 +826,12 @@ struct DecLds {
     static constexpr int kMaxReach = Net::kReach1 > Net::kReach2 ? Net::kReach1 : Net::kReach2;
     // Wave w computes out-blocks w, w + 4, ... of a layer.  Where a layer's block count is not a multiple of four,
     // the last wave has a round without a block; its spare time there, in MFMAs of the other waves' chains, is
-    // kIdleSlack in layer kIdleLayer (the layer where it is largest; 0: no layer has any).  That wave uses it to fetch
-    // the pixels of the rows above the band (decode_kernel).
-    static constexpr int kFetchWave = kDecThreads / 64 - 1;
+    // kIdleSlack in layer kIdleLayer (the layer where it is largest; 0: no layer has any).  The spare rounds are used to
+    // fetch the pixels of the rows above the band and to write decoded pixels to the image (decode_kernel).
+    static constexpr int kLastWave = kDecThreads / 64 - 1;
     static constexpr int idle_slack(int l) {
         const int nob = Net::ob(l), slots = (nob + 3) / 4;
-        return kFetchWave + 4 * (slots - 1) >= nob ? Net::kb(l) * (l > 0 ? 2 : 1) : 0;
+        return kLastWave + 4 * (slots - 1) >= nob ? Net::kb(l) * (l > 0 ? 2 : 1) : 0;
     }
     static constexpr int idle_layer() {
         int best = Net::kLayers - 1;
@@ -840,10 +840,14 @@ struct DecLds {
     }
     static constexpr int kIdleLayer = idle_layer();
     static constexpr int kIdleSlack = idle_slack(kIdleLayer);
-    // Waves that idle in that round (the last ones).  With two of them the one before the fetch wave writes the decoded
-    // pixels to the image; with one the fetch wave does both.
+    // Waves that idle in that round (the last ones).  With two of them the last wave, whose lanes also publish the
+    // band's last two rows to the mailbox, writes the decoded pixels to the image, and the wave before it fetches:
+    // the fetching wave then has loads in flight and no stores (a wave's loads and stores complete out of order with
+    // each other under one counter, so a wave that has both can only wait for a load by waiting for everything).
+    // With one idle wave it does both.
     static constexpr int kIdleWaves = kIdleSlack > 0 ? 4 * ((Net::ob(kIdleLayer) + 3) / 4) - Net::ob(kIdleLayer) : 0;
-    static constexpr int kStoreWave = kIdleWaves >= 2 ? kFetchWave - 1 : kFetchWave;
+    static constexpr int kStoreWave = kLastWave;
+    static constexpr int kFetchWave = kIdleWaves >= 2 ? kLastWave - 1 : kLastWave;
     // Does wave w have a round without an out-block in layer l?
     static constexpr bool wave_idles(int l, int w) { return w + 4 * ((Net::ob(l) + 3) / 4 - 1) >= Net::ob(l); }
     // The idle waves also have a (short) round to spare in the first layer where that is not the layer above: the
@@ -1330,7 +1334,7 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
 
     const int last_row = min(r0 + kBandRows - 1, H - 1);
     const int t_begin = kDelay * r0, t_end = kDelay * last_row + W - 1;
-    // The first two lanes of the last wave bring in the rows above the band: lane 0 row r0-2 -> ring row 0, lane 1
+    // The first two lanes of the fetch wave bring in the rows above the band: lane 0 row r0-2 -> ring row 0, lane 1
     // row r0-1 -> ring row 1.  That wave has a round without an out-block in one of the layers (DecLds::kIdleLayer)
     // and does the fetch there, off the path that all four waves share.
     const bool fetcher = band > 0 && tid >= D::kFetchWave * 64 && tid < D::kFetchWave * 64 + 2;
@@ -1392,11 +1396,11 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
     // wave does this where it has no out-block to compute, in two halves when it has such a round in the first layer
     // too: first the check of the word that has arrived and its conversion (fetch_check), then, behind the barrier
     // that follows this step's gather and before the one that ends the step, the ring write (fetch_put).  With those
-    // two rounds the request (fetch_request) is issued late in the step, behind the table reads of the last channel's
-    // search: the later a word is asked for, the closer the band can follow the band above (a word asked for before
-    // it is published is asked for again, which holds the fetch wave up), and three quarters of a step are still
-    // ample for the load.  The request always loads (the row's last word again beyond the image): no branch, the
-    // value is not used then.
+    // two rounds the request (fetch_request) is issued at the very end of the step, after the pixel has been
+    // published: the later a word is asked for, the closer the band can follow the band above (a word asked for
+    // before it is published is asked for again, which holds the fetch wave up), and the load is back when the next
+    // step's first layer checks it.  The request always loads (the row's last word again beyond the image): no
+    // branch, the value is not used then.
     uint32_t fetched = 0;
     constexpr bool kLateRequest = D::kIdleInFirstLayer;
     auto fetch_check = [&](int t) __attribute__((always_inline)) {
@@ -1573,7 +1577,7 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
                 gamma[k] = hq[head_slot<Net>(11 * K + k)];
             });
         };
-        auto load_mailbox = [&]() __attribute__((always_inline)) { if constexpr (kLateRequest) fetch_request(t); };
+        auto load_nothing = [&]() __attribute__((always_inline)) {};
         load_cp(0, cpr, tail_r);
         asm volatile("" ::: "memory");
 
@@ -1599,7 +1603,7 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
         asm volatile("" : "+v"(ghat) : "v"(tail_b));
         couple_blue<K>(cpb, beta, gamma, rhat, ghat);
         slot = (uint32_t)rd.x & 0xFFFFu;
-        const int sb = group_search<K>(cpb, slot, lut, lane, start, freq, load_mailbox);
+        const int sb = group_search<K>(cpb, slot, lut, lane, start, freq, load_nothing);
         reader_advance(rd, rd.x, slot, start, freq, j, active);
         reader_next_pixel(rd, active);
         reader_refill(rd, j);
@@ -1622,6 +1626,7 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
                                    __HIP_MEMORY_SCOPE_AGENT);
             if (c == W - 1 && (rd.bad || rd.x != kRansL || rd.y != kRansL || rd.pos != rd.nwords)) set_error(status, PCC_E_STREAM);
         }
+        if constexpr (kLateRequest) fetch_request(t);
         clk.mark(kPhPublish);
         // ---- rows above the band, where no layer leaves the fetch wave spare time for it
         if constexpr (D::kIdleSlack == 0) { fetch_check(t); fetch_put(t); }
