@@ -1278,24 +1278,40 @@ decode_kernel(const uint8_t* __restrict__ model, const uint8_t* __restrict__ str
     }
 
     // The grid has at most as many workgroups as the chip holds at once, and a workgroup decodes band after band:
-    // it takes a ticket, decodes that band, takes the next.  Tickets go out in the order they are asked for, so a
-    // band only ever waits for the band above it (same image), whose smaller ticket some workgroup holds or has
-    // finished.  (Leaving the bands beyond the resident ones to the hardware's dispatcher costs up to a third:
-    // it deals workgroups to dies and shader engines in strict rotation, and waits for a place in the engine
-    // whose turn it is while others are free.)
+    // it takes a ticket, decodes that band, takes the next.  A band only ever waits for the band above it (same
+    // image), which has a smaller ticket.  Tickets come from a counter, in the order they are asked for, so every
+    // ticket below a held one is held by some workgroup or finished.  With two workgroups per compute unit a
+    // workgroup's first ticket is its index in the grid instead (the later ones come from the counter): the two
+    // workgroups that share a unit are those of index k and k + (number of units), but they ask the counter within
+    // microseconds of each other and get neighbouring tickets, so that bands which become runnable at the same time
+    // share units while other units hold two workgroups that both wait (measured: 24 images of 768x512 8.2 ms; with
+    // the index, the bands on a unit become runnable hundreds of steps apart, 7.3 ms).  Every ticket below a held
+    // one is then still held by a workgroup that has been started, or finished: the dispatcher starts workgroups
+    // in the order of their index (per die; dies run ahead of each other), and the whole grid fits the chip.
+    // Should that ever not hold (a chip shared with another job's resident kernels), the bounded wait for the band
+    // above ends the call with an error, not a hang.  With one workgroup per unit the counter stays: the workgroup
+    // that is ready first then takes the band that can run first (a single image of 768x512: 5.52 against 5.58 ms
+    // by index).  (Leaving the bands beyond the
+    // resident ones to the hardware's dispatcher costs up to a third: it deals workgroups to dies and shader
+    // engines in strict rotation, and waits for a place in the engine whose turn it is while others are free.)
     // Tickets are numbered band-major (band 0 of every image, then band 1 of every image, ...): the order in
     // which bands become runnable, so a workgroup holds a band that can run rather than one that waits for
     // hundreds of steps, and all images advance together.
+    constexpr bool kIndexTickets = MINBLOCKS > 1;
+    bool first_band = true;
     for (;;) {
     __syncthreads();                                   // the previous band's last reads of the ring and of misc
     if (tid == 0) {
         const bool stop = __hip_atomic_load(&status[kStAbort], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0;
-        misc[0] = stop ? total_bands : atomicAdd(&status[kStTicket], 1);
+        misc[0] = stop ? total_bands
+                       : (kIndexTickets && first_band) ? (int)blockIdx.x
+                       : (kIndexTickets ? (int)gridDim.x : 0) + atomicAdd(&status[kStTicket], 1);
         misc[1] = 0;
     }
     for (int i = tid; i < 18 * D::kRingRowElems; i += kDecThreads) ring[i] = 0;
     __syncthreads();
     const int ticket = misc[0];
+    first_band = false;
     if (ticket >= total_bands) break;
     const int band = ticket / n, im = ticket - band * n;
 
@@ -2002,17 +2018,19 @@ void launch_decode(pcc_ctx* ctx, const uint8_t* d_stream, size_t nbytes, int n, 
     const uint64_t bands = (uint64_t)n * nbands;                      // dims_ok: below 2^31
     const uint64_t cus = ctx->num_cus > 0 ? (uint64_t)ctx->num_cus : 256u;
     // One workgroup per CU decodes a step in the shortest time; two per CU take Net::kSharedStepPercent / 100 as
-    // long per step when both are busy (a fifth less when most CUs hold one busy workgroup) but decode twice as
-    // many bands at once.  An image is a chain of `chain` steps whatever the machine does; the job is `work`
-    // band-steps, which one workgroup per CU gets through about 12 % slower than evenly once there are more bands
-    // than CUs.  Two per CU pay when the work per place, not the chain, sets the time (measured, batches of 12 to 48
-    // images of 768x512: from 20 images on).
+    // long per step when both are busy but decode twice as many bands at once.  An image is a chain of `chain`
+    // steps whatever the machine does; the job is `work` band-steps.  Estimates, in percent of a step alone, fitted to
+    // batches of 6 to 48 images of 768x512 in both shapes: one per CU takes the chain plus a tenth, or the work per CU
+    // plus a fifth (rounds of bands that do not fill the chip); two per CU take the chain stretched by the share of
+    // the time a unit's two workgroups are both busy (the work per CU over twice the chain, at most all of it), or the
+    // work per place at the shared pace.  Two per CU win from about 2.2 bands per CU on (18 images of 768x512).
     const int band_rows = H < kBandRows ? H : kBandRows;
     const uint64_t chain = (uint64_t)W + (uint64_t)Net::kDelay * (H - 1);
     const uint64_t work = bands * ((uint64_t)W + (uint64_t)Net::kDelay * (band_rows - 1));
     const uint64_t per_cu = (work + cus - 1) / cus, per_half_cu = (work + 2 * cus - 1) / (2 * cus);
-    const uint64_t alone = std::max(chain, per_cu) * (per_cu > chain ? 112u : 100u);
-    const uint64_t shared = std::max(chain * (Net::kSharedStepPercent - 20u), per_half_cu * Net::kSharedStepPercent);
+    const uint64_t alone = std::max(chain * 110u, per_cu * 120u);
+    const uint64_t stretch = (Net::kSharedStepPercent - 113u) * std::min(per_cu, 2 * chain) / (2 * chain);
+    const uint64_t shared = std::max(chain * (100u + stretch), per_half_cu * Net::kSharedStepPercent) * 103u / 100u;
     const bool two = ctx->decode_variant == 2 || (ctx->decode_variant == 0 && DecLds<Net>::kTwoFit && bands > cus && shared < alone);
     const uint32_t grid = (uint32_t)std::min(bands, two ? 2 * cus : cus);
     if (!two)
