@@ -52,14 +52,15 @@ struct NetWorkload {
     static constexpr int kRingPad = 2;        // extra 16-bit elements per ring row
     static constexpr bool kLeaky = false;
     // Decoder with two workgroups per CU (256 registers per lane each): what of a wave's weight slices is then read
-    // from a copy in LDS instead of held in registers, chosen by measurement (batches of 48 images of 768x512): LDS
-    // copies cost time too, so a few spilled registers can be the better deal.  1: the biases, 2: the first layer's
-    // weights, 4: the head's.
+    // from a copy in LDS instead of held in registers, chosen by measurement (batches of 24 and 48 images of 768x512;
+    // 24 images: none 7.21 ms, first layer 7.00, head 6.95, both 7.24, both and the biases 7.59): LDS copies cost
+    // time too, so a few spilled registers can be the better deal.  1: the biases, 2: the first layer's weights,
+    // 4: the head's.
     static constexpr int kEncodeVariant = 1;      // pixel kernel: two tiles per work item, 512 threads (index into the host's table)
-    static constexpr int kSharedCuLds = 6;
+    static constexpr int kSharedCuLds = 4;
     // Time of a decode step when both workgroups of a CU are busy, in percent of a step of a workgroup that has its
     // CU alone (measured the same way; the host chooses between the two launches with it).
-    static constexpr unsigned kSharedStepPercent = 158;
+    static constexpr unsigned kSharedStepPercent = 150;
     __host__ __device__ static constexpr int dim(int l) { return l == 0 ? 30 : l == 1 ? 160 : l == 2 ? 160 : l == 3 ? 128 : 60; }
     __host__ __device__ static constexpr int ob(int l) { return l == 0 ? 10 : l == 1 ? 10 : l == 2 ? 8 : 4; }
     __host__ __device__ static constexpr int kb(int l) { return l == 0 ? 1 : l == 1 ? 5 : l == 2 ? 5 : 4; }
